@@ -1,0 +1,131 @@
+/*
+ * bt_oracle.c -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, single-threaded CPU statement of the sparse bitmap codec of
+ * BitTrain (Section 3.2 "Bitmap Format"; Algorithm 1, dense -> bitmap;
+ * Algorithm 2, bitmap -> dense; the footprint formulas M_d and M_b).  It is
+ * the definition the GPU library is checked against.  Only tests, the smoke
+ * check and the benchmark's cpu_baseline leg may call it; the product path
+ * never does.  It shares no code, header, table or constant with the GPU
+ * library.
+ *
+ * Readings of the paper that this file fixes (each is a deliberate choice):
+ *   - "zero" is the all-zero bit pattern of the element, not an IEEE compare:
+ *     -0.0, NaN, denormals and infinities are kept as values, so the round
+ *     trip of Algorithm 1 followed by Algorithm 2 is bit-exact.
+ *   - element i owns bit (i mod 32), least significant bit first, of the
+ *     32-bit word (i div 32); the bitmap has ceil(n/32) words and the unused
+ *     high bits of the last word are zero.  The paper's N/8 bytes is the same
+ *     number whenever 32 divides N.
+ *   - Algorithm 2's loop runs over the n valid bits.
+ *   - a cleared bit restores the all-zero pattern (+0.0) of the element width.
+ *   - values are appended in ascending flattened index order.
+ *   - the element is defined by its width only (2, 4 or 8 bytes): fp16 and
+ *     bf16 are the same codec.
+ *
+ * Parity pins (tests/test_oracle_*.py): the theoretical columns of Table 1,
+ * hand-built tensors, numpy.packbits / boolean indexing, enumeration of all
+ * 2^16 zero patterns of a 16-element tensor, every n in [0,130], closed forms
+ * for the all-zero and all-non-zero tensors, and a literal pure-Python
+ * transcription of the two algorithms on small inputs.  No function here is
+ * "parity unpinned".
+ */
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+/* Element i of a flat buffer of width-byte elements, as an unsigned integer
+ * holding its raw bit pattern. */
+static uint64_t load_bits(const unsigned char *base, uint64_t i, int width)
+{
+    uint64_t v = 0;
+    memcpy(&v, base + i * (uint64_t)width, (size_t)width); /* little-endian host */
+    return v;
+}
+
+static void store_bits(unsigned char *base, uint64_t i, int width, uint64_t v)
+{
+    memcpy(base + i * (uint64_t)width, &v, (size_t)width);
+}
+
+static int width_ok(int width) { return width == 2 || width == 4 || width == 8; }
+
+/* M_b generalised to any element width: one bit per element, rounded up to
+ * whole 32-bit words, plus the non-zero values.  Returns 0 when the arguments
+ * make no sense (unknown width, nnz > n). */
+uint64_t bt_oracle_compressed_size(uint64_t n, uint64_t nnz, int width)
+{
+    if (!width_ok(width) || nnz > n) return 0;
+    uint64_t words = n / 32 + (n % 32 != 0);
+    return 4 * words + nnz * (uint64_t)width;
+}
+
+/* M_d: the dense footprint. */
+uint64_t bt_oracle_dense_size(uint64_t n, int width)
+{
+    if (!width_ok(width)) return 0;
+    return n * (uint64_t)width;
+}
+
+/* Algorithm 1.  T is the flat dense tensor of n elements.  bitmap must hold
+ * ceil(n/32) words and values up to n elements.  Returns nnz, or UINT64_MAX
+ * for an unknown width. */
+uint64_t bt_oracle_compress(const void *T, uint64_t n, int width,
+                            uint32_t *bitmap, void *values)
+{
+    if (!width_ok(width)) return UINT64_MAX;
+    const unsigned char *t = (const unsigned char *)T;
+    unsigned char *vals = (unsigned char *)values;
+    uint64_t words = n / 32 + (n % 32 != 0);
+    for (uint64_t w = 0; w < words; ++w) bitmap[w] = 0;
+
+    uint64_t j = 0;                          /* length of B.values so far */
+    for (uint64_t i = 0; i < n; ++i) {
+        uint64_t bits = load_bits(t, i, width);
+        if (bits == 0) {
+            /* push a 0 bit: the word was cleared above */
+        } else {
+            store_bits(vals, j, width, bits);             /* push T[i] to B.values */
+            j += 1;
+            bitmap[i / 32] |= (uint32_t)1 << (i % 32);    /* push a 1 bit */
+        }
+    }
+    return j;
+}
+
+/* Algorithm 2.  Rebuilds the n-element dense tensor.  Returns the number of
+ * values consumed (the final j), or UINT64_MAX for an unknown width. */
+uint64_t bt_oracle_decompress(const uint32_t *bitmap, const void *values,
+                              uint64_t n, int width, void *T)
+{
+    if (!width_ok(width)) return UINT64_MAX;
+    const unsigned char *vals = (const unsigned char *)values;
+    unsigned char *t = (unsigned char *)T;
+    uint64_t j = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        if ((bitmap[i / 32] >> (i % 32)) & 1u) {
+            store_bits(t, i, width, load_bits(vals, j, width));
+            j += 1;
+        } else {
+            store_bits(t, i, width, 0);
+        }
+    }
+    return j;
+}
+
+/* The bitmap of y = ReLU(x) is the ReLU derivative mask (bit set <=> y != 0
+ * <=> x > 0), so the backward pass of ReLU needs only the bitmap:
+ * grad_in[i] = bit(i) ? grad_out[i] : +0.  A select, not a multiply: a NaN or
+ * Inf in grad_out under a cleared bit does not leak. */
+int bt_oracle_relu_backward(const uint32_t *bitmap, const void *grad_out,
+                            uint64_t n, int width, void *grad_in)
+{
+    if (!width_ok(width)) return -1;
+    const unsigned char *g = (const unsigned char *)grad_out;
+    unsigned char *o = (unsigned char *)grad_in;
+    for (uint64_t i = 0; i < n; ++i) {
+        uint64_t keep = (bitmap[i / 32] >> (i % 32)) & 1u;
+        store_bits(o, i, width, keep ? load_bits(g, i, width) : 0);
+    }
+    return 0;
+}

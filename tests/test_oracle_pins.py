@@ -1,0 +1,231 @@
+"""Pins for the CPU oracle: each test checks oracle/bt_oracle.c against something
+other than itself -- numbers the paper prints, closed forms, library routines of
+numpy, brute-force enumeration, and a literal list-based transcription of
+Algorithms 1 and 2.  A dropped term, a wrong bit order, a reversed value order,
+an off-by-one at a word boundary or an IEEE (instead of bit-pattern) zero test
+each fail at least one of them."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import py_ref
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "table1_theoretical.txt")
+
+
+def _table1():
+    rows = []
+    for line in open(GOLDEN):
+        if line.startswith("#") or not line.strip():
+            continue
+        b, c, w, h, n, pct, dense, bitmap, improv = line.split()
+        rows.append((int(b), int(c), int(w), int(h), int(n), int(pct), float(dense), float(bitmap),
+                     float(improv)))
+    return rows
+
+
+def test_table1_has_30_rows():
+    rows = _table1()
+    assert len(rows) == 30
+    for b, c, w, h, n, *_ in rows:
+        assert b * c * w * h == n
+
+
+@pytest.mark.parametrize("row", _table1(), ids=lambda r: "%dx%dx%dx%d_nz%d" % (r[0], r[1], r[2], r[3], r[5]))
+def test_size_reproduces_table1(oracle, row):
+    """Table 1, theoretical columns: dense MB, bitmap MB and improvement %, fp32.
+    The paper prints two decimals, so agreement is to half a unit of the last one."""
+    b, c, w, h, n, pct, dense_mb, bitmap_mb, improv = row
+    nnz = n * pct // 100
+    md = oracle.dense_size(n, 4)
+    mb = oracle.compressed_size(n, nnz, 4)
+    assert abs(md / 2**20 - dense_mb) <= 0.005 + 1e-9
+    assert abs(mb / 2**20 - bitmap_mb) <= 0.005 + 1e-9
+    assert abs(100.0 * (1.0 - mb / md) - improv) <= 0.005 + 1e-9
+
+
+def test_size_formula_section_3_2(oracle):
+    """M_d = 4 * total and M_b = 4 * nnz + total / 8 for fp32 whenever 32 | total."""
+    for n in (32, 64, 3211264, 25690112):
+        for nnz in (0, 1, n // 4, n // 2, n):
+            assert oracle.dense_size(n, 4) == 4 * n
+            assert oracle.compressed_size(n, nnz, 4) == 4 * nnz + n // 8
+            assert oracle.compressed_size(n, nnz, 2) == 2 * nnz + n // 8
+
+
+def test_size_closed_forms_and_rounding(oracle):
+    # all-zero tensor: only the bitmap; all-non-zero: expansion by 1/(8*width)
+    n = 25690112
+    assert oracle.compressed_size(n, 0, 4) * 32 == oracle.dense_size(n, 4)
+    assert oracle.compressed_size(n, n, 4) * 32 == 33 * oracle.dense_size(n, 4)
+    assert oracle.compressed_size(n, n, 2) * 16 == 17 * oracle.dense_size(n, 2)
+    # bitmap is rounded up to whole 32-bit words
+    assert [oracle.compressed_size(k, 0, 4) for k in (0, 1, 31, 32, 33, 64, 65)] == [0, 4, 4, 4, 8, 8, 12]
+    # nonsense arguments
+    assert oracle.compressed_size(10, 11, 4) == 0
+    assert oracle.compressed_size(10, 1, 3) == 0
+    for n, nnz, w in ((0, 0, 4), (77, 13, 2), (1000, 1000, 8)):
+        assert oracle.compressed_size(n, nnz, w) == py_ref.footprint_bytes(n, nnz, w)
+
+
+def test_hand_built_tensor(oracle):
+    """A 40-element tensor written out by hand: non-zeros at 1, 2, 5, 31, 32, 39."""
+    x = np.zeros(40, dtype=np.float32)
+    x[1], x[2], x[5], x[31], x[32], x[39] = 1.0, -2.0, 3.5, 4.0, -5.0, 6.0
+    bitmap, values, nnz = oracle.compress(x)
+    assert nnz == 6
+    assert bitmap.tolist() == [(1 << 1) | (1 << 2) | (1 << 5) | (1 << 31), (1 << 0) | (1 << 7)]
+    assert values.tolist() == [1.0, -2.0, 3.5, 4.0, -5.0, 6.0]
+    back = oracle.decompress(bitmap, values, 40)
+    assert back.view(np.uint32).tolist() == x.view(np.uint32).tolist()
+    # bitmap bytes in memory are little-endian: elements 1, 2, 5 live in byte 0, elements 32 and 39 in byte 4
+    assert bitmap.view(np.uint8)[:5].tolist() == [0b00100110, 0, 0, 0x80, 0x81]
+
+
+def test_zero_is_the_bit_pattern(oracle):
+    """-0.0, denormals, NaN payloads and infinities are values; only all-zero bits are dropped."""
+    pats = np.array([0x80000000, 0, 0x00000001, 0x7FC00123, 0, 0xFF800000, 0, 0x80000000], dtype=np.uint32)
+    bitmap, values, nnz = oracle.compress(pats.view(np.float32))
+    assert nnz == 5
+    assert bitmap.tolist() == [0b10101101]
+    assert values.view(np.uint32).tolist() == [0x80000000, 0x00000001, 0x7FC00123, 0xFF800000, 0x80000000]
+    back = oracle.decompress(bitmap, values, 8)
+    assert back.view(np.uint32).tolist() == pats.tolist()
+    h = np.array([0x8000, 0x0000, 0x7E01, 0x0001], dtype=np.uint16)
+    bitmap, values, nnz = oracle.compress(h)
+    assert (nnz, bitmap.tolist(), values.tolist()) == (3, [0b1101], [0x8000, 0x7E01, 0x0001])
+
+
+@pytest.mark.parametrize("npdt", [np.uint16, np.uint32, np.uint64])
+def test_against_numpy_library_routines(oracle, npdt):
+    """bitmap == numpy.packbits(little) as uint32; values == boolean indexing;
+    decompress == zeros with values scattered at the mask; relu == numpy.where."""
+    rng = np.random.default_rng(7)
+    for n in (1, 31, 32, 33, 1000, 4096, 70001):
+        for zf in (0.0, 0.3, 0.9, 1.0):
+            x = rng.integers(1, np.iinfo(npdt).max, size=n, dtype=npdt)
+            x[rng.random(n) < zf] = 0
+            mask = x != 0
+            packed = np.packbits(mask, bitorder="little")
+            packed = np.concatenate([packed, np.zeros((-packed.size) % 4, np.uint8)]).view("<u4")
+            bitmap, values, nnz = oracle.compress(x)
+            assert nnz == np.count_nonzero(x)
+            assert np.array_equal(bitmap, packed)
+            assert np.array_equal(values, x[mask])
+            # popcount invariant and zero tail bits
+            assert int(np.unpackbits(bitmap.view(np.uint8)).sum()) == nnz
+            expect = np.zeros(n, npdt)
+            expect[mask] = values
+            assert np.array_equal(oracle.decompress(bitmap, values, n), expect)
+            assert np.array_equal(oracle.decompress(bitmap, values, n), x)
+            g = rng.integers(0, np.iinfo(npdt).max, size=n, dtype=npdt)
+            assert np.array_equal(oracle.relu_backward(bitmap, g), np.where(mask, g, 0).astype(npdt))
+            assert oracle.compressed_size(n, nnz, x.itemsize) == bitmap.nbytes + values.nbytes
+
+
+@pytest.mark.parametrize("npdt", [np.uint16, np.uint32])
+def test_all_2_to_16_zero_patterns(oracle, npdt):
+    """Every zero pattern p of a 16-element tensor with a distinct payload per
+    position: the bitmap word is p itself, the values are the payloads of the set
+    bits in ascending position, and the round trip is exact."""
+    payload = (np.arange(16, dtype=np.uint32) * 0x0111 + 0x8001).astype(npdt)
+    assert len(set(payload.tolist())) == 16 and payload.min() > 0
+    pos = np.arange(16)
+    for p in range(1 << 16):
+        sel = ((p >> pos) & 1).astype(bool)
+        x = np.where(sel, payload, 0).astype(npdt)
+        bitmap, values, nnz = oracle.compress(x)
+        assert bitmap[0] == p and bitmap.size == 1
+        assert nnz == bin(p).count("1")
+        assert values.tolist() == payload[sel].tolist()
+        if p % 97 == 0 or p > 65000:   # the decoder on a spread of patterns + the dense end
+            assert oracle.decompress(bitmap, values, 16).tolist() == x.tolist()
+
+
+def test_all_2_to_16_patterns_decode(oracle):
+    """Decoder alone on every 16-bit pattern, fed hand-made (bitmap, values)."""
+    payload = np.arange(1, 17, dtype=np.uint32) * 1000003
+    pos = np.arange(16)
+    for p in range(1 << 16):
+        sel = ((p >> pos) & 1).astype(bool)
+        out = oracle.decompress(np.array([p], np.uint32), payload[sel], 16)
+        assert out.tolist() == np.where(sel, payload, 0).tolist()
+
+
+def test_every_length_0_to_130_against_list_transcription(oracle):
+    """Word and tail boundaries: every n in [0,130], C oracle == pure-Python Algorithm 1/2."""
+    rng = np.random.default_rng(11)
+    for n in range(0, 131):
+        x = rng.integers(1, 2**32, size=n, dtype=np.uint32)
+        x[rng.random(n) < 0.5] = 0
+        bits_list, vals_list = py_ref.to_bitmap(x.tolist())
+        bitmap, values, nnz = oracle.compress(x)
+        assert bitmap.size == (n + 31) // 32
+        assert bitmap.tolist() == py_ref.pack_words(bits_list)
+        assert values.tolist() == vals_list and nnz == len(vals_list)
+        assert oracle.decompress(bitmap, values, n).tolist() == py_ref.to_dense(bits_list, vals_list) == x.tolist()
+        g = rng.integers(0, 2**32, size=n, dtype=np.uint32)
+        assert oracle.relu_backward(bitmap, g).tolist() == py_ref.relu_backward(bits_list, g.tolist())
+        if n % 32:
+            assert int(bitmap[-1]) >> (n % 32) == 0      # unused high bits stay clear
+
+
+def test_relu_backward_special_cases(oracle):
+    n = 100
+    g = np.arange(1, n + 1, dtype=np.float32)
+    ones = np.array([0xFFFFFFFF] * 3 + [0xF], dtype=np.uint32)
+    assert np.array_equal(oracle.relu_backward(ones, g), g)                       # identity
+    assert not oracle.relu_backward(np.zeros(4, np.uint32), g).view(np.uint32).any()  # all blocked
+    # select, not multiply: NaN / Inf / -1 under a cleared bit give +0 (bits 0), not NaN or -0
+    bad = np.array([np.nan, np.inf, -1.0, 5.0], dtype=np.float32)
+    out = oracle.relu_backward(np.array([0b1000], np.uint32), bad)
+    assert out.view(np.uint32).tolist() == [0, 0, 0, np.float32(5.0).view(np.uint32)]
+    # it is the ReLU derivative: for y = relu(x), bit set <=> x > 0
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(1000).astype(np.float32)
+    go = rng.standard_normal(1000).astype(np.float32)
+    bitmap, _, _ = oracle.compress(np.maximum(x, 0))
+    assert np.array_equal(oracle.relu_backward(bitmap, go), np.where(x > 0, go, np.float32(0)))
+
+
+def test_degenerate_inputs(oracle):
+    e = np.zeros(0, np.float32)
+    bitmap, values, nnz = oracle.compress(e)
+    assert (bitmap.size, values.size, nnz) == (0, 0, 0)
+    assert oracle.decompress(bitmap, values, 0).size == 0
+    z = np.zeros(1000, np.float32)
+    bitmap, values, nnz = oracle.compress(z)
+    assert nnz == 0 and not bitmap.any() and bitmap.size == 32
+    assert not oracle.decompress(bitmap, values, 1000).view(np.uint32).any()
+    f = np.full(1000, 2.5, np.float32)
+    bitmap, values, nnz = oracle.compress(f)
+    assert nnz == 1000 and np.array_equal(values, f)
+    assert bitmap.tolist() == [0xFFFFFFFF] * 31 + [0xFF]
+    one = np.zeros(1000, np.float32)
+    one[999] = 1.0
+    bitmap, values, nnz = oracle.compress(one)
+    assert nnz == 1 and bitmap[31] == 1 << 7 and not bitmap[:31].any()
+
+
+def test_workload_recipes_round_trip(oracle):
+    """Scaled-down versions of the benchmark configurations: round trip exact,
+    invariants hold, sparsity is what the recipe says."""
+    from paper_2110_15362_amd import workloads as wl
+    c1 = wl.config1()
+    cases = [(c1["x"], 0.5), (wl.config2(0.5, batch=1)["x"], 0.5), (wl.config2(0.7, batch=1)["x"], 0.7),
+             (wl.config2(0.9, batch=1)["x"], 0.9), (wl.config3("a", batch=1)["x"], 0.65),
+             (wl.config3("b", batch=1)["x"], 0.65), (wl.config5(0.05, batch=1)["x"], 0.05),
+             (wl.config5(0.95, batch=1)["x"], 0.95), (next(iter(wl.config4_tensors(batch=1)))["x"], 0.7)]
+    for x, z in cases:
+        xb = wl.bits(x)
+        bitmap, values, nnz = oracle.compress(xb)
+        assert abs((1 - nnz / xb.size) - z) < 0.01
+        assert nnz == np.count_nonzero(xb)
+        assert np.array_equal(oracle.decompress(bitmap, values, xb.size), xb)
+        assert oracle.compressed_size(xb.size, nnz, xb.itemsize) == bitmap.nbytes + values.nbytes
+    for dt in ("f32", "f16", "bf16"):
+        xb = wl.bits(wl.special_values(dt))
+        bitmap, values, nnz = oracle.compress(xb)
+        assert nnz == 12 and bitmap.tolist() == [0b1100101111111110]
+        assert np.array_equal(oracle.decompress(bitmap, values, 16), xb)
