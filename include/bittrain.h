@@ -1,0 +1,144 @@
+/*
+ * libbittrain -- the sparse bitmap activation codec of BitTrain on one MI355X.
+ *
+ * The format (Section 3.2, "Bitmap Format"): an activation tensor of n
+ * elements, flattened in place, is stored as
+ *   (i)  a bitmap with one bit per element, set where the element is non-zero;
+ *   (ii) the non-zero elements, in ascending flattened index order.
+ * Compression runs in the forward pass (Algorithm 1), restoration in the
+ * backward pass (Algorithm 2).  The footprint is M_b = width * nnz + n / 8
+ * bytes against M_d = width * n dense.
+ *
+ * Conventions fixed here where the paper is silent:
+ *   - "zero" is the all-zero bit pattern of the element.  -0.0, NaNs, denormals
+ *     and infinities are kept as values, so Algorithm 2 after Algorithm 1
+ *     reproduces the tensor bit for bit.  fp16 and bf16 are the same codec.
+ *   - element i owns bit (i mod 32), least significant first, of the uint32
+ *     word (i div 32).  The bitmap has ceil(n/32) words; the unused high bits
+ *     of the last word are written as 0, so popcount(bitmap) == nnz.
+ *   - a cleared bit restores +0 (all-zero bits) of the element width.
+ *   - tensors are flat, contiguous buffers; the shape stays with the caller.
+ *
+ * Every pointer named d_* is DEVICE memory owned by the caller.  The library
+ * allocates nothing, frees nothing and never synchronises: each device call
+ * enqueues its kernel(s) on `stream` and returns.  Argument errors are found on
+ * the host before anything is launched; nothing is written in that case.
+ * No exceptions, no errno, no logging: the return code is the only channel.
+ */
+#ifndef BITTRAIN_H
+#define BITTRAIN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BT_F32 = 0,  /* 4-byte elements */
+    BT_F16 = 1,  /* 2-byte elements */
+    BT_BF16 = 2  /* 2-byte elements; identical to BT_F16 at the byte level */
+} bt_dtype;
+
+typedef enum {
+    BT_OK = 0,
+    BT_ERR_NULL = 1,      /* a required pointer is NULL */
+    BT_ERR_DTYPE = 2,     /* dtype is not one of bt_dtype */
+    BT_ERR_ALIGN = 3,     /* a pointer is not aligned as documented */
+    BT_ERR_WORKSPACE = 4, /* workspace smaller than bt_workspace_bytes(n, dtype) */
+    BT_ERR_HIP = 5,       /* the HIP runtime refused the launch */
+    BT_ERR_SIZE = 6       /* n is beyond BT_MAX_ELEMENTS */
+} bt_status;
+
+/* Largest n any call accepts (2^37 elements). */
+#define BT_MAX_ELEMENTS ((uint64_t)1 << 37)
+
+/* A hipStream_t, passed as an opaque pointer so that this header needs no HIP
+ * header.  NULL is the default stream. */
+typedef void *bt_stream;
+
+/* ---- host-only, pure functions (no device is touched) -------------------- */
+
+/* M_b of Section 3.2, generalised to the element width and to whole 32-bit
+ * bitmap words: 4 * ceil(n/32) + nnz * sizeof(dtype).  Equals the paper's
+ * 4 * nnz + n / 8 for fp32 whenever 32 divides n (every row of Table 1).
+ * Returns 0 for an unknown dtype or nnz > n. */
+size_t bt_compressed_size(uint64_t n, uint64_t nnz, bt_dtype dtype);
+
+/* 4 * ceil(n/32): the bytes d_bitmap must hold. */
+size_t bt_bitmap_bytes(uint64_t n);
+
+/* Bytes of scratch that bt_compress / bt_decompress need for a tensor of n
+ * elements: a 256-byte header plus one 8-byte descriptor per tile of the
+ * single-pass grid scan.  Monotone in n; 0 for an unknown dtype. */
+size_t bt_workspace_bytes(uint64_t n, bt_dtype dtype);
+
+/* Size in bytes of one element, 0 for an unknown dtype. */
+size_t bt_dtype_size(bt_dtype dtype);
+
+const char *bt_status_str(bt_status status);
+
+/* ---- device calls -------------------------------------------------------- */
+
+/* Put a workspace into its initial state (all zero bytes) by enqueueing a fill
+ * kernel on `stream`.  Required once after allocating a workspace, before its
+ * first use, and again if a kernel using it was aborted.  After that the
+ * kernels leave the workspace ready for the next call themselves, so
+ * bt_compress and bt_decompress are one launch each.
+ * d_workspace: 8-byte aligned.  Errors: BT_ERR_NULL, BT_ERR_ALIGN, BT_ERR_HIP. */
+bt_status bt_workspace_init(void *d_workspace, size_t workspace_bytes, bt_stream stream);
+
+/* Algorithm 1 (dense -> bitmap), as one fused pass over the input.
+ *   d_in        n elements of `dtype`, 16-byte aligned, read once.
+ *   d_bitmap    ceil(n/32) uint32 words, 4-byte aligned; every word is written.
+ *   d_values    room for values_cap elements, element-aligned; on return
+ *               elements [0, min(nnz, values_cap)) hold the non-zero elements in
+ *               index order; the rest is untouched.
+ *   values_cap  capacity of d_values in elements.  If nnz > values_cap nothing
+ *               is written beyond the capacity, the bitmap and *d_nnz are still
+ *               complete, and the caller sees the overflow as *d_nnz > values_cap.
+ *               The worst case is n.
+ *   d_nnz       one uint64, 8-byte aligned, written by the kernel: valid once
+ *               `stream` has reached this call.
+ *   d_workspace bt_workspace_bytes(n, dtype) bytes, 8-byte aligned, initialised
+ *               once with bt_workspace_init.  A workspace must not be shared by
+ *               two calls that can be in flight at the same time.
+ * Input and outputs must not overlap.  "delete T" of Algorithm 1 is the caller
+ * dropping d_in after this call is enqueued.  n == 0 only writes *d_nnz = 0.
+ * Errors: BT_ERR_NULL, BT_ERR_DTYPE, BT_ERR_ALIGN, BT_ERR_SIZE, BT_ERR_WORKSPACE,
+ * BT_ERR_HIP. */
+bt_status bt_compress(const void *d_in, uint64_t n, bt_dtype dtype,
+                      uint32_t *d_bitmap, void *d_values, uint64_t values_cap,
+                      uint64_t *d_nnz,
+                      void *d_workspace, size_t workspace_bytes, bt_stream stream);
+
+/* Algorithm 2 (bitmap -> dense).
+ *   d_bitmap    ceil(n/32) words as written by bt_compress (bits at positions
+ *               >= n are ignored).
+ *   d_values    the non-zero elements in index order, popcount(bitmap) of them,
+ *               element-aligned.  nnz is not an argument: it is implied by the
+ *               bitmap, so no host synchronisation is needed between the two calls.
+ *   d_out       n elements, 16-byte aligned; every element is written (values at
+ *               set bits, +0 at cleared bits).
+ *   d_workspace as for bt_compress.
+ * Errors: as bt_compress. */
+bt_status bt_decompress(const uint32_t *d_bitmap, const void *d_values, uint64_t n,
+                        bt_dtype dtype, void *d_out,
+                        void *d_workspace, size_t workspace_bytes, bt_stream stream);
+
+/* Backward of y = ReLU(x) from the bitmap of y alone.  Algorithm 1 sets bit i
+ * exactly where y[i] != 0, i.e. where x[i] > 0, which is the ReLU derivative, so
+ * the values array is not needed:
+ *   grad_in[i] = bit(i) ? grad_out[i] : +0      (a select, never a multiply).
+ *   d_grad_out, d_grad_in   n elements each, 16-byte aligned; they may be the
+ *                           same buffer (in place) but must not partly overlap.
+ * Errors: BT_ERR_NULL, BT_ERR_DTYPE, BT_ERR_ALIGN, BT_ERR_SIZE, BT_ERR_HIP. */
+bt_status bt_relu_backward_from_bitmap(const uint32_t *d_bitmap, const void *d_grad_out,
+                                       uint64_t n, bt_dtype dtype, void *d_grad_in,
+                                       bt_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BITTRAIN_H */

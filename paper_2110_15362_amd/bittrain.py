@@ -1,0 +1,155 @@
+"""Thin binding over the C-ABI library ``libbittrain.so``.
+
+Argument marshalling only: every step of the codec runs in the HIP kernels of
+the library.  PyTorch supplies device memory and the stream, nothing else.
+There is no CPU fallback: if the library is missing, or a call fails, this
+module raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbittrain.so")
+
+BT_F32, BT_F16, BT_BF16 = 0, 1, 2
+BT_OK = 0
+STATUS_NAMES = {0: "BT_OK", 1: "BT_ERR_NULL", 2: "BT_ERR_DTYPE", 3: "BT_ERR_ALIGN", 4: "BT_ERR_WORKSPACE",
+                5: "BT_ERR_HIP", 6: "BT_ERR_SIZE"}
+BT_MAX_ELEMENTS = 1 << 37
+
+_DTYPES = {torch.float32: BT_F32, torch.float16: BT_F16, torch.bfloat16: BT_BF16}
+
+_lib = None
+
+
+class BitTrainError(RuntimeError):
+    def __init__(self, call, status):
+        self.status = status
+        super().__init__("%s failed: %s (%s)" % (call, STATUS_NAMES.get(status, status), status_str(status)))
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libbittrain.so is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                               "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        u64, sz, vp, ci = ctypes.c_uint64, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int
+        L.bt_compressed_size.restype, L.bt_compressed_size.argtypes = sz, [u64, u64, ci]
+        L.bt_bitmap_bytes.restype, L.bt_bitmap_bytes.argtypes = sz, [u64]
+        L.bt_workspace_bytes.restype, L.bt_workspace_bytes.argtypes = sz, [u64, ci]
+        L.bt_dtype_size.restype, L.bt_dtype_size.argtypes = sz, [ci]
+        L.bt_status_str.restype, L.bt_status_str.argtypes = ctypes.c_char_p, [ci]
+        L.bt_workspace_init.restype, L.bt_workspace_init.argtypes = ci, [vp, sz, vp]
+        L.bt_compress.restype = ci
+        L.bt_compress.argtypes = [vp, u64, ci, vp, vp, u64, vp, vp, sz, vp]
+        L.bt_decompress.restype = ci
+        L.bt_decompress.argtypes = [vp, vp, u64, ci, vp, vp, sz, vp]
+        L.bt_relu_backward_from_bitmap.restype = ci
+        L.bt_relu_backward_from_bitmap.argtypes = [vp, vp, u64, ci, vp, vp]
+        _lib = L
+    return _lib
+
+
+def status_str(status):
+    return lib().bt_status_str(int(status)).decode()
+
+
+def dtype_code(dtype):
+    try:
+        return _DTYPES[dtype]
+    except KeyError:
+        raise TypeError("libbittrain handles float32, float16 and bfloat16, not %s" % dtype)
+
+
+def bt_compressed_size(n, nnz, dtype):
+    return int(lib().bt_compressed_size(n, nnz, dtype if isinstance(dtype, int) else dtype_code(dtype)))
+
+
+def bt_bitmap_bytes(n):
+    return int(lib().bt_bitmap_bytes(n))
+
+
+def bt_workspace_bytes(n, dtype):
+    return int(lib().bt_workspace_bytes(n, dtype if isinstance(dtype, int) else dtype_code(dtype)))
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr() if t is not None else 0)
+
+
+def _check(call, status):
+    if status != BT_OK:
+        raise BitTrainError(call, status)
+
+
+def _dev(t, name):
+    if not t.is_cuda:
+        raise ValueError("%s must live in device memory" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+
+
+def new_workspace(n, dtype, device="cuda", stream=None):
+    """Allocate and initialise a workspace for tensors of up to n elements."""
+    ws = torch.empty(bt_workspace_bytes(n, dtype), dtype=torch.uint8, device=device)
+    bt_workspace_init(ws, stream)
+    return ws
+
+
+def bt_workspace_init(workspace, stream=None):
+    _dev(workspace, "workspace")
+    _check("bt_workspace_init", lib().bt_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                        _stream(stream)))
+
+
+def bt_compress(x, bitmap, values, nnz, workspace, stream=None):
+    """Algorithm 1 on device tensors.  x: dense tensor (any shape, contiguous);
+    bitmap: int32[ceil(n/32)]; values: x.dtype[cap]; nnz: int64[1]; all on x's
+    device.  Enqueues on the stream and returns; nothing is synchronised."""
+    for t, name in ((x, "x"), (bitmap, "bitmap"), (values, "values"), (nnz, "nnz"), (workspace, "workspace")):
+        _dev(t, name)
+    if values.dtype != x.dtype:
+        raise TypeError("values must have the dtype of x")
+    if bitmap.element_size() != 4 or bitmap.numel() * 4 < bt_bitmap_bytes(x.numel()):
+        raise ValueError("bitmap must hold ceil(n/32) 32-bit words")
+    if nnz.element_size() != 8 or nnz.numel() < 1:
+        raise ValueError("nnz must be one 64-bit integer")
+    _check("bt_compress", lib().bt_compress(
+        _ptr(x), x.numel(), dtype_code(x.dtype), _ptr(bitmap), _ptr(values), values.numel(), _ptr(nnz),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def bt_decompress(bitmap, values, out, workspace, stream=None):
+    """Algorithm 2 on device tensors: fills `out` (n = out.numel()) from bitmap + values."""
+    for t, name in ((bitmap, "bitmap"), (values, "values"), (out, "out"), (workspace, "workspace")):
+        _dev(t, name)
+    if values.dtype != out.dtype:
+        raise TypeError("values must have the dtype of out")
+    if bitmap.element_size() != 4 or bitmap.numel() * 4 < bt_bitmap_bytes(out.numel()):
+        raise ValueError("bitmap must hold ceil(n/32) 32-bit words")
+    _check("bt_decompress", lib().bt_decompress(
+        _ptr(bitmap), _ptr(values), out.numel(), dtype_code(out.dtype), _ptr(out),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def bt_relu_backward_from_bitmap(bitmap, grad_out, grad_in, stream=None):
+    """grad_in[i] = bit(i) ? grad_out[i] : +0; grad_in may be grad_out itself."""
+    for t, name in ((bitmap, "bitmap"), (grad_out, "grad_out"), (grad_in, "grad_in")):
+        _dev(t, name)
+    if grad_in.dtype != grad_out.dtype or grad_in.numel() != grad_out.numel():
+        raise TypeError("grad_in must match grad_out")
+    if bitmap.element_size() != 4 or bitmap.numel() * 4 < bt_bitmap_bytes(grad_out.numel()):
+        raise ValueError("bitmap must hold ceil(n/32) 32-bit words")
+    _check("bt_relu_backward_from_bitmap", lib().bt_relu_backward_from_bitmap(
+        _ptr(bitmap), _ptr(grad_out), grad_out.numel(), dtype_code(grad_out.dtype), _ptr(grad_in), _stream(stream)))

@@ -1,0 +1,80 @@
+"""Helpers for the GPU parity tests: run the library on a CPU tensor's bytes and
+hand the outputs back as numpy bit arrays.  Calls go through the C ABI binding."""
+import numpy as np
+import torch
+
+import paper_2110_15362_amd.bittrain as bt
+from paper_2110_15362_amd import workloads as wl
+
+SENTINEL = 0x5A
+
+
+def _sentinel(numel, dtype, dev):
+    t = torch.empty(numel, dtype=dtype, device=dev)
+    t.view(torch.uint8).fill_(SENTINEL)
+    return t
+
+
+def gpu_compress(x, cap=None, ws=None, values_offset=0, dev="cuda"):
+    """Returns (bitmap uint32[W], values bits[cap], nnz, tail_ok) where tail_ok says the
+    guard words after the bitmap and the values beyond min(nnz, cap) still hold the sentinel."""
+    x = x.contiguous().reshape(-1)
+    n = x.numel()
+    cap = n if cap is None else cap
+    words = (n + 31) // 32
+    xd = x.to(dev)
+    bitmap = _sentinel(words + 4, torch.int32, dev)
+    vbuf = _sentinel(cap + values_offset + 8, x.dtype, dev)
+    values = vbuf[values_offset:values_offset + cap]
+    nnz = torch.full((1,), -7, dtype=torch.int64, device=dev)
+    if ws is None:
+        ws = bt.new_workspace(n, x.dtype, device=dev)
+    bt.bt_compress(xd, bitmap[:words], values, nnz, ws)
+    torch.cuda.synchronize()
+    nnz_h = int(nnz.item())
+    bm = bitmap.cpu().numpy().view(np.uint32)
+    vb = wl.bits(vbuf.cpu())
+    sent = np.frombuffer(bytes([SENTINEL] * vb.itemsize), dtype=vb.dtype)[0]
+    written = min(nnz_h, cap)
+    tail_ok = bool((bm[words:] == 0x5A5A5A5A).all()) and bool((vb[:values_offset] == sent).all()) and \
+        bool((vb[values_offset + written:] == sent).all())
+    return bm[:words].copy(), vb[values_offset:values_offset + cap].copy(), nnz_h, tail_ok
+
+
+def gpu_decompress(bitmap_np, values_np, n, dtype, ws=None, values_offset=0, dev="cuda"):
+    """bitmap_np uint32[W], values_np raw bits -> restored tensor bits; also checks the guard after out."""
+    words = (n + 31) // 32
+    bitmap = torch.from_numpy(bitmap_np.view(np.int32).copy()).to(dev)
+    vb = torch.from_numpy(values_np.view({2: np.int16, 4: np.int32}[values_np.itemsize]).copy()).view(dtype)
+    vbuf = _sentinel(vb.numel() + values_offset + 8, dtype, dev)
+    vbuf[values_offset:values_offset + vb.numel()] = vb.to(dev)
+    values = vbuf[values_offset:values_offset + vb.numel()]
+    pad = 16 // vb.element_size()
+    obuf = _sentinel(n + pad, dtype, dev)
+    if ws is None:
+        ws = bt.new_workspace(n, dtype, device=dev)
+    assert bitmap.numel() == words
+    bt.bt_decompress(bitmap, values, obuf[:n], ws)
+    torch.cuda.synchronize()
+    ob = wl.bits(obuf.cpu())
+    sent = np.frombuffer(bytes([SENTINEL] * ob.itemsize), dtype=ob.dtype)[0]
+    return ob[:n].copy(), bool((ob[n:] == sent).all())
+
+
+def gpu_relu_backward(bitmap_np, g, inplace=False, dev="cuda"):
+    g = g.contiguous().reshape(-1)
+    n = g.numel()
+    bitmap = torch.from_numpy(bitmap_np.view(np.int32).copy()).to(dev)
+    pad = 16 // g.element_size()
+    gbuf = _sentinel(n + pad, g.dtype, dev)
+    gbuf[:n] = g.to(dev)
+    if inplace:
+        bt.bt_relu_backward_from_bitmap(bitmap, gbuf[:n], gbuf[:n])
+        obuf = gbuf
+    else:
+        obuf = _sentinel(n + pad, g.dtype, dev)
+        bt.bt_relu_backward_from_bitmap(bitmap, gbuf[:n], obuf[:n])
+    torch.cuda.synchronize()
+    ob = wl.bits(obuf.cpu())
+    sent = np.frombuffer(bytes([SENTINEL] * ob.itemsize), dtype=ob.dtype)[0]
+    return ob[:n].copy(), bool((ob[n:] == sent).all())

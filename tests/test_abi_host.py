@@ -1,0 +1,116 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header
+declares, its host-only functions agree with the paper's numbers, and argument
+errors are reported before anything is launched (so none of this needs a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "bittrain.h")
+
+
+@pytest.fixture(scope="module")
+def bt():
+    import paper_2110_15362_amd.bittrain as bt
+    if not os.path.exists(bt.LIB_PATH):
+        from paper_2110_15362_amd import build
+        build.build()
+    bt.lib()
+    return bt
+
+
+def _declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(bt_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(bt):
+    names = _declared_functions()
+    assert {"bt_compress", "bt_compressed_size", "bt_decompress", "bt_relu_backward_from_bitmap"} <= set(names)
+    raw = ctypes.CDLL(bt.LIB_PATH)
+    for name in names:
+        assert hasattr(raw, name), name
+
+
+def test_header_compiles_as_plain_c(tmp_path):
+    import subprocess
+    src = tmp_path / "t.c"
+    src.write_text('#include "bittrain.h"\nint main(void){return (int)bt_bitmap_bytes(0);}\n')
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only",
+                           "-I", os.path.join(ROOT, "include"), str(src)])
+
+
+def test_compressed_size_matches_table1(bt):
+    golden = os.path.join(ROOT, "tests", "golden", "table1_theoretical.txt")
+    rows = 0
+    for line in open(golden):
+        if line.startswith("#") or not line.strip():
+            continue
+        _, _, _, _, n, pct, dense_mb, bitmap_mb, improv = line.split()
+        n, pct = int(n), int(pct)
+        size = bt.bt_compressed_size(n, n * pct // 100, bt.BT_F32)
+        assert abs(size / 2**20 - float(bitmap_mb)) <= 0.005 + 1e-9
+        assert abs(100 * (1 - size / (4 * n)) - float(improv)) <= 0.005 + 1e-9
+        rows += 1
+    assert rows == 30
+
+
+def test_size_helpers(bt, oracle):
+    for n in (0, 1, 31, 32, 33, 4096, 25690112):
+        assert bt.bt_bitmap_bytes(n) == 4 * ((n + 31) // 32)
+        for code, width in ((bt.BT_F32, 4), (bt.BT_F16, 2), (bt.BT_BF16, 2)):
+            for nnz in (0, n // 3, n):
+                assert bt.bt_compressed_size(n, nnz, code) == oracle.compressed_size(n, nnz, width)
+            assert bt.lib().bt_dtype_size(code) == width
+            assert bt.bt_workspace_bytes(n, code) >= 256 + 8
+    assert bt.bt_compressed_size(10, 11, bt.BT_F32) == 0
+    assert bt.bt_compressed_size(10, 1, 9) == 0
+    assert bt.bt_workspace_bytes(10, 9) == 0
+    assert bt.bt_workspace_bytes(10**6, bt.BT_F32) <= bt.bt_workspace_bytes(10**7, bt.BT_F32)
+    assert bt.status_str(0) == "ok" and bt.status_str(4) == "workspace too small"
+
+
+def test_argument_errors_are_found_on_the_host(bt):
+    L = bt.lib()
+    A = 0x10000          # a fake, well aligned "device" address: never dereferenced on an error path
+    ws_bytes = bt.bt_workspace_bytes(1000, bt.BT_F32)
+    ok_args = dict(d_in=A, n=1000, dt=bt.BT_F32, bm=A, val=A, cap=1000, nnz=A, ws=A, wsb=ws_bytes)
+
+    def compress(**kw):
+        a = dict(ok_args, **kw)
+        return L.bt_compress(a["d_in"], a["n"], a["dt"], a["bm"], a["val"], a["cap"], a["nnz"], a["ws"], a["wsb"], None)
+
+    assert compress(dt=7) == 2                      # BT_ERR_DTYPE
+    assert compress(d_in=None) == 1                 # BT_ERR_NULL
+    assert compress(bm=None) == 1
+    assert compress(val=None) == 1
+    assert compress(nnz=None) == 1
+    assert compress(ws=None) == 1
+    assert compress(d_in=A + 4) == 3                # BT_ERR_ALIGN: input needs 16 bytes
+    assert compress(bm=A + 2) == 3
+    assert compress(val=A + 2) == 3                 # fp32 values need 4 bytes
+    assert compress(nnz=A + 4) == 3
+    assert compress(ws=A + 4) == 3
+    assert compress(wsb=ws_bytes - 1) == 4          # BT_ERR_WORKSPACE
+    assert compress(n=(1 << 37) + 1) == 6           # BT_ERR_SIZE
+
+    def decompress(bm=A, val=A, n=1000, dt=bt.BT_F32, out=A, ws=A, wsb=ws_bytes):
+        return L.bt_decompress(bm, val, n, dt, out, ws, wsb, None)
+
+    assert decompress(dt=-1) == 2
+    assert decompress(bm=None) == 1 and decompress(out=None) == 1 and decompress(ws=None) == 1
+    assert decompress(out=A + 8) == 3 and decompress(val=A + 1) == 3
+    assert decompress(wsb=8) == 4
+    assert decompress(n=0, bm=None, val=None, out=None, ws=None, wsb=0) == 0     # nothing to do
+
+    def relu(bm=A, g=A, n=1000, dt=bt.BT_BF16, gi=A):
+        return L.bt_relu_backward_from_bitmap(bm, g, n, dt, gi, None)
+
+    assert relu(dt=3) == 2
+    assert relu(bm=None) == 1 and relu(g=None) == 1 and relu(gi=None) == 1
+    assert relu(g=A + 2) == 3 and relu(gi=A + 8) == 3 and relu(bm=A + 1) == 3
+    assert relu(n=0, bm=None, g=None, gi=None) == 0
+    assert L.bt_workspace_init(None, 100, None) == 1
+    assert L.bt_workspace_init(A + 1, 100, None) == 3

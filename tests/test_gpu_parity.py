@@ -1,0 +1,253 @@
+"""GPU parity: libbittrain (through its C ABI) against the CPU oracle, byte for byte.
+
+Integer / bit work throughout, so the bar is exact equality of the bitmap, the
+value array [0, nnz), nnz, the restored tensor and the ReLU-backward output."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2110_15362_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+DTYPES = ["f32", "f16", "bf16"]
+# tile = 4096 fp32 / 8192 16-bit elements; wave strip = 1024 / 2048; row = 256 / 512
+SIZES = [1, 3, 4, 5, 7, 8, 9, 31, 32, 33, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1023, 1024, 1025, 2047, 2049,
+         4095, 4096, 4097, 8191, 8192, 8193, 12305, 16384, 3 * 8192 + 17, 100003, 5 * 8192, 1000000 + 37]
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (they never fall back to the CPU)")
+    import paper_2110_15362_amd.bittrain as bt
+    bt.lib()
+    from tests import gpu_util
+    return gpu_util
+
+
+def _check_compress(gpu, oracle, x, **kw):
+    xb = wl.bits(x)
+    o_bitmap, o_values, o_nnz = oracle.compress(xb)
+    bitmap, values, nnz, tail_ok = gpu.gpu_compress(x, **kw)
+    assert nnz == o_nnz
+    assert np.array_equal(bitmap, o_bitmap)
+    cap = kw.get("cap")
+    written = o_nnz if cap is None else min(o_nnz, cap)
+    assert np.array_equal(values[:written], o_values[:written])
+    assert tail_ok, "wrote outside bitmap[0,W) or values[0,min(nnz,cap))"
+    return o_bitmap, o_values, o_nnz
+
+
+def _check_decompress(gpu, oracle, o_bitmap, o_values, n, dtype, expect_bits, **kw):
+    out, guard_ok = gpu.gpu_decompress(o_bitmap, o_values, n, dtype, **kw)
+    assert np.array_equal(out, oracle.decompress(o_bitmap, o_values, n))
+    assert np.array_equal(out, expect_bits)
+    assert guard_ok, "wrote past out[n)"
+
+
+@pytest.mark.parametrize("dt", DTYPES)
+def test_compress_sizes_and_tails(gpu, oracle, dt):
+    for i, n in enumerate(SIZES):
+        for zf in (0.5, 0.0, 1.0, 0.93):
+            x = wl.random_sparse(n, dt, zf, seed=1000 + i)
+            _check_compress(gpu, oracle, x)
+
+
+@pytest.mark.parametrize("dt", DTYPES)
+def test_decompress_sizes_and_tails(gpu, oracle, dt):
+    for i, n in enumerate(SIZES):
+        for zf in (0.5, 0.0, 1.0, 0.93):
+            x = wl.random_sparse(n, dt, zf, seed=2000 + i)
+            xb = wl.bits(x)
+            o_bitmap, o_values, _ = oracle.compress(xb)
+            _check_decompress(gpu, oracle, o_bitmap, o_values, n, x.dtype, xb)
+
+
+@pytest.mark.parametrize("dt", DTYPES)
+def test_relu_backward_sizes_and_tails(gpu, oracle, dt):
+    for i, n in enumerate(SIZES):
+        x = torch.relu(wl.random_sparse(n, dt, 0.2, seed=3000 + i))
+        g = wl.random_sparse(n, dt, 0.0, seed=4000 + i)
+        o_bitmap, _, _ = oracle.compress(wl.bits(x))
+        expect = oracle.relu_backward(o_bitmap, wl.bits(g))
+        for inplace in (False, True):
+            out, guard_ok = gpu.gpu_relu_backward(o_bitmap, g, inplace=inplace)
+            assert np.array_equal(out, expect)
+            assert guard_ok
+
+
+@pytest.mark.parametrize("dt", DTYPES)
+def test_special_bit_patterns(gpu, oracle, dt):
+    """-0.0, denormals, NaN payloads and infinities are values; the round trip is bit exact."""
+    base = wl.special_values(dt)
+    x = base.repeat(700)[:11111]
+    o_bitmap, o_values, o_nnz = _check_compress(gpu, oracle, x)
+    _check_decompress(gpu, oracle, o_bitmap, o_values, x.numel(), x.dtype, wl.bits(x))
+    # ReLU backward is a select: NaN / Inf gradients under a cleared bit give +0
+    g = base.flip(0).repeat(700)[:11111]
+    out, guard_ok = gpu.gpu_relu_backward(o_bitmap, g)
+    assert np.array_equal(out, oracle.relu_backward(o_bitmap, wl.bits(g))) and guard_ok
+
+
+def test_single_nonzero_first_and_last(gpu, oracle):
+    for n in (4096, 4097, 50000):
+        for pos in (0, n - 1, n // 2):
+            x = torch.zeros(n)
+            x[pos] = -3.25
+            o_bitmap, o_values, o_nnz = _check_compress(gpu, oracle, x)
+            assert o_nnz == 1
+            _check_decompress(gpu, oracle, o_bitmap, o_values, n, x.dtype, wl.bits(x))
+
+
+def test_values_capacity_is_respected(gpu, oracle):
+    """nnz > values_cap: nothing beyond the capacity is written, bitmap and nnz are complete."""
+    x = wl.random_sparse(70001, "f32", 0.5, seed=5)
+    for cap in (0, 1, 1000, 17000, 34999):
+        _check_compress(gpu, oracle, x, cap=cap)
+    xh = wl.random_sparse(70001, "f16", 0.3, seed=6)
+    for cap in (0, 3, 8191, 30001):
+        _check_compress(gpu, oracle, xh, cap=cap)
+
+
+@pytest.mark.parametrize("dt", DTYPES)
+def test_values_pointer_only_element_aligned(gpu, oracle, dt):
+    for off in (1, 2, 3, 5, 7):
+        x = wl.random_sparse(40000 + off, dt, 0.4, seed=70 + off)
+        o_bitmap, o_values, _ = _check_compress(gpu, oracle, x, values_offset=off)
+        _check_decompress(gpu, oracle, o_bitmap, o_values, x.numel(), x.dtype, wl.bits(x), values_offset=off)
+
+
+def test_workspace_reuse_across_calls_and_sizes(gpu, oracle):
+    """One workspace, initialised once, serves many calls of different sizes and kinds
+    (the kernels leave it ready for the next call)."""
+    import paper_2110_15362_amd.bittrain as bt
+    ws = bt.new_workspace(300000, torch.float32)
+    for rep, n in enumerate([300000, 17, 4096, 250001, 8192, 1, 300000, 123457]):
+        x = wl.random_sparse(n, "f32", 0.6, seed=900 + rep)
+        o_bitmap, o_values, _ = _check_compress(gpu, oracle, x, ws=ws)
+        _check_decompress(gpu, oracle, o_bitmap, o_values, n, x.dtype, wl.bits(x), ws=ws)
+        xh = wl.random_sparse(n, "bf16", 0.6, seed=950 + rep)
+        o_bitmap, o_values, _ = _check_compress(gpu, oracle, xh, ws=ws)
+        _check_decompress(gpu, oracle, o_bitmap, o_values, n, xh.dtype, wl.bits(xh), ws=ws)
+    hdr = ws[:16].cpu().numpy().view(np.uint32)
+    assert hdr[0] == 0 and hdr[1] == 0 and hdr[3] == 0   # ticket, done counter, error flag
+
+
+def test_empty_tensor(gpu):
+    import paper_2110_15362_amd.bittrain as bt
+    dev = "cuda"
+    x = torch.empty(0, device=dev)
+    nnz = torch.full((1,), 99, dtype=torch.int64, device=dev)
+    bitmap = torch.empty(0, dtype=torch.int32, device=dev)
+    ws = bt.new_workspace(0, torch.float32)
+    bt.bt_compress(x, bitmap, x, nnz, ws)
+    bt.bt_decompress(bitmap, x, x, ws)
+    bt.bt_relu_backward_from_bitmap(bitmap, x, x)
+    torch.cuda.synchronize()
+    assert int(nnz.item()) == 0
+
+
+def test_config1(gpu, oracle):
+    cfg = wl.config1()
+    x, g = cfg["x"], cfg["grad"]
+    o_bitmap, o_values, _ = _check_compress(gpu, oracle, x)
+    _check_decompress(gpu, oracle, o_bitmap, o_values, x.numel(), x.dtype, wl.bits(x))
+    out, ok = gpu.gpu_relu_backward(o_bitmap, g)
+    assert np.array_equal(out, oracle.relu_backward(o_bitmap, wl.bits(g))) and ok
+
+
+@pytest.mark.parametrize("z", [0.5, 0.7, 0.9])
+def test_config2_full_size(gpu, oracle, z):
+    x = wl.config2(z)["x"]
+    o_bitmap, o_values, o_nnz = _check_compress(gpu, oracle, x)
+    assert abs(1 - o_nnz / x.numel() - z) < 1e-3
+    _check_decompress(gpu, oracle, o_bitmap, o_values, x.numel(), x.dtype, wl.bits(x))
+    g = torch.randn(x.numel(), generator=torch.Generator().manual_seed(12))
+    out, ok = gpu.gpu_relu_backward(o_bitmap, g)
+    assert np.array_equal(out, oracle.relu_backward(o_bitmap, wl.bits(g))) and ok
+
+
+@pytest.mark.parametrize("variant", ["a", "b"])
+def test_config3_full_size(gpu, oracle, variant):
+    x = wl.config3(variant)["x"]
+    o_bitmap, o_values, o_nnz = _check_compress(gpu, oracle, x)
+    assert abs(1 - o_nnz / x.numel() - 0.65) < 5e-3
+    _check_decompress(gpu, oracle, o_bitmap, o_values, x.numel(), x.dtype, wl.bits(x))
+    g = torch.randn(x.numel(), generator=torch.Generator().manual_seed(13)).to(torch.bfloat16)
+    out, ok = gpu.gpu_relu_backward(o_bitmap, g)
+    assert np.array_equal(out, oracle.relu_backward(o_bitmap, wl.bits(g))) and ok
+
+
+def test_config4_resnet50_set_full_size(gpu, oracle):
+    """All 49 tensors compressed in forward order with one workspace on one stream, then
+    restored in reverse order; every bitmap, value array, nnz and restored tensor is compared."""
+    import paper_2110_15362_amd.bittrain as bt
+    dev = "cuda"
+    shapes = wl.config4_shapes()
+    n_max = max(int(np.prod(s)) for s in shapes)
+    ws = bt.new_workspace(n_max, torch.float32)
+    scratch = torch.empty(n_max, dtype=torch.float32, device=dev)      # worst-case value buffer
+    nnz_d = torch.zeros(1, dtype=torch.int64, device=dev)
+    stash, dense_bytes, comp_bytes = [], 0, 0
+    for cfg in wl.config4_tensors():
+        x = cfg["x"].reshape(-1)
+        n = x.numel()
+        o_bitmap, o_values, o_nnz = oracle.compress(wl.bits(x))
+        xd = x.to(dev)
+        bitmap = torch.empty((n + 31) // 32, dtype=torch.int32, device=dev)
+        bt.bt_compress(xd, bitmap, scratch[:n], nnz_d, ws)
+        nnz = int(nnz_d.item())
+        assert nnz == o_nnz
+        values = scratch[:nnz].clone()                                 # right-sized stash
+        assert np.array_equal(bitmap.cpu().numpy().view(np.uint32), o_bitmap), cfg["name"]
+        assert np.array_equal(wl.bits(values.cpu()), o_values), cfg["name"]
+        stash.append((bitmap, values, n, o_nnz))
+        dense_bytes += 4 * n
+        comp_bytes += bt.bt_compressed_size(n, nnz, torch.float32)
+        assert bt.bt_compressed_size(n, nnz, torch.float32) == oracle.compressed_size(n, o_nnz, 4)
+    # backward sweep: regenerate the inputs (same seed) and walk them in reverse
+    xs = [c["x"].reshape(-1) for c in wl.config4_tensors()]
+    out = torch.empty(n_max, dtype=torch.float32, device=dev)
+    for (bitmap, values, n, _), x in zip(reversed(stash), reversed(xs)):
+        bt.bt_decompress(bitmap, values, out[:n], ws)
+        assert np.array_equal(wl.bits(out[:n].cpu()), wl.bits(x))
+    assert dense_bytes == 4 * 614957056
+    saved = 1 - comp_bytes / dense_bytes
+    assert 0.66 < saved < 0.68, saved        # 70 % zeros: 1 - (0.3 + 1/32)
+
+
+@pytest.mark.parametrize("p", [0.05, 0.95])
+def test_config5_full_size(gpu, oracle, p):
+    x = wl.config5(p)["x"]
+    n = x.numel()
+    o_bitmap, o_values, o_nnz = _check_compress(gpu, oracle, x)
+    if p == 0.05:
+        assert oracle.compressed_size(n, o_nnz, 2) > 2 * n      # the compressed form is larger
+    _check_decompress(gpu, oracle, o_bitmap, o_values, n, x.dtype, wl.bits(x))
+
+
+def test_repeated_calls_are_identical(gpu, oracle):
+    """The grid scan is the only place where tiles talk to each other: 300 back-to-back
+    calls on inputs with whole empty tiles must give the same bytes every time."""
+    import paper_2110_15362_amd.bittrain as bt
+    dev = "cuda"
+    x = wl.config3("b", batch=1)["x"].reshape(-1)
+    n = x.numel()
+    o_bitmap, o_values, o_nnz = oracle.compress(wl.bits(x))
+    xd = x.to(dev)
+    ws = bt.new_workspace(n, x.dtype)
+    bitmap = torch.empty((n + 31) // 32, dtype=torch.int32, device=dev)
+    values = torch.empty(n, dtype=x.dtype, device=dev)
+    out = torch.empty_like(xd)
+    nnz = torch.zeros(1, dtype=torch.int64, device=dev)
+    ref_bitmap = torch.from_numpy(o_bitmap.view(np.int32)).to(dev)
+    ref_values = torch.from_numpy(o_values.view(np.int16)).to(dev)
+    for it in range(300):
+        bitmap.zero_(); values.zero_(); out.fill_(1.0)
+        bt.bt_compress(xd, bitmap, values, nnz, ws)
+        bt.bt_decompress(bitmap, values, out, ws)
+        assert int(nnz.item()) == o_nnz
+        assert torch.equal(bitmap, ref_bitmap)
+        assert torch.equal(values[:o_nnz].view(torch.int16), ref_values)
+        assert torch.equal(out.view(torch.int16), xd.view(torch.int16))
