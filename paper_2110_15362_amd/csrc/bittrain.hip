@@ -12,10 +12,12 @@
 //   lane    16-byte loads; per-lane non-zero mask by integer compare
 //   wave    packed DPP prefix sum of the per-lane popcounts (no LDS, no barrier)
 //   block   four wave totals through LDS
-//   grid    decoupled look-back over per-tile descriptors {epoch, status, count}
+//   grid    per-tile counts published in the workspace; one extra wave turns them
+//           into per-tile prefixes; a tile polls only its own prefix
 //
 // There is no matrix contraction anywhere, so no MFMA: the path is bound by HBM
-// bandwidth and everything here is about moving each byte once, coalesced.
+// bandwidth and everything here is about moving each byte once, coalesced, and
+// about keeping enough bytes in flight while a tile waits for its prefix.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -26,24 +28,28 @@ namespace {
 constexpr int kWaveSize = 64;
 constexpr int kWaves = 4;                 // waves per block
 constexpr int kBlock = kWaveSize * kWaves;
-constexpr int kRows = 4;                  // 16-byte loads per lane per tile
+#ifndef BT_ROWS
+#define BT_ROWS 8
+#endif
+constexpr int kRows = BT_ROWS;            // 16-byte loads per lane per tile
+constexpr int kPhaseRows = 4;             // rows that go through a wave's LDS strip at a time
 constexpr int kVecBytes = 16;
 
-// Workspace header (uint32 words); descriptors start at byte kHeaderBytes.
-constexpr int kHdrTicket = 0;   // next tile to hand out
-constexpr int kHdrDone = 1;     // tiles whose look-back has finished
-constexpr int kHdrEpoch = 2;    // tag of the current call, 24 bits
-constexpr int kHdrError = 3;    // set if a look-back gave up waiting
+// ---- workspace layout -----------------------------------------------------------------
+// Header (uint32 words), then one 768-byte record per 32 tiles.
+constexpr int kHdrSeq = 0;       // calls completed on this workspace; its low bit picks the copy in use
+constexpr int kHdrPrevTiles = 1; // tiles of the previous call (what it left behind in the other copy)
+constexpr int kHdrError = 2;     // set if a tile gave up waiting for another tile's count
 constexpr size_t kHeaderBytes = 256;
-
-// Descriptor word: [63:40] epoch, [39:38] status, [37:0] count.
-constexpr int kEpochShift = 40;
-constexpr int kStatusShift = 38;
-constexpr uint64_t kCountMask = ((uint64_t)1 << kStatusShift) - 1;
-constexpr uint32_t kEpochMask = (1u << 24) - 1;
-constexpr uint64_t kStAggregate = 1;      // count = non-zeros of this tile alone
-constexpr uint64_t kStPrefix = 2;         // count = non-zeros of tiles [0, this]
-constexpr uint32_t kSpinLimit = 1u << 20; // polls before a look-back gives up
+// Record of 32 tiles, two copies c = 0, 1 of everything, in separate 128-byte lines:
+//   [128*c, 128*c + 128)          uint32 count + 1 of each tile, written by the tile
+//   [256 + 256*c, 256*c + 512)    uint64 prefix + 1 of each tile, written by the scanner
+// 0 means "not published yet".  A call uses copy (seq & 1) and zeroes what the
+// previous call left in the other copy, so the copy the next call uses is clean
+// when it starts and no clearing launch is ever needed.
+constexpr size_t kRecordBytes = 768;
+constexpr int kTilesPerRecord = 32;
+constexpr uint32_t kSpinLimit = 1u << 20; // polls before a wait is given up
 
 template <int S> struct Geo {
     static constexpr int E = kVecBytes / S;          // elements per lane per load
@@ -52,9 +58,10 @@ template <int S> struct Geo {
     static constexpr int ROW = kWaveSize * E;        // elements per wave-wide load
     static constexpr int WAVE = kRows * ROW;         // elements per wave per tile
     static constexpr int TILE = kWaves * WAVE;       // elements per tile
-    static constexpr int LDS_WAVE = WAVE * S + kVecBytes;  // staging bytes per wave
-    static_assert(kRows <= G, "one bitmap store per wave needs rows <= lanes per word");
-    static_assert(kRows % 2 == 0, "row counts are scanned two to a register");
+    static constexpr int LDS_WAVE = kPhaseRows * ROW * S + kVecBytes;  // staging bytes per wave
+    static constexpr int RPM = 32 / E;               // rows whose E-bit lane masks share one register
+    static constexpr int MW = (kRows + RPM - 1) / RPM;   // registers that hold a lane's masks
+    static_assert(kRows % kPhaseRows == 0 && kPhaseRows % 2 == 0, "rows are scanned two to a register");
 };
 
 // ---- wave-level primitives (all 64 lanes must be active) ---------------------
@@ -75,10 +82,6 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x) {
     return x;
 }
 
-__device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
-    return (uint32_t)__builtin_amdgcn_readlane((int)wave_inclusive_sum(x), 63);
-}
-
 // OR over each aligned group of G lanes (G = 4 or 8); every lane gets the result.
 template <int G> __device__ __forceinline__ uint32_t group_or(uint32_t x) {
     x |= BT_DPP(0, x, 0xB1, 0xf, true);       // quad_perm [1,0,3,2]: lane ^ 1
@@ -97,36 +100,44 @@ __device__ __forceinline__ void wave_lds_sync() {
 // ---- per-lane helpers -----------------------------------------------------------
 
 // Bit j set <=> element j of the 16-byte vector has a non-zero bit pattern.
+// min(bits, 1) instead of a compare: a compare result lives in a scalar register
+// pair, and 8 rows x 4..8 compares in flight exhaust the scalar registers.
 template <int S> __device__ __forceinline__ uint32_t nonzero_mask(const uint4 v) {
+    const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+    uint32_t m = 0;
     if (S == 4) {
-        return (v.x != 0 ? 1u : 0u) | (v.y != 0 ? 2u : 0u) | (v.z != 0 ? 4u : 0u) | (v.w != 0 ? 8u : 0u);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) m |= min(d[i], 1u) << i;
     } else {
-        const uint32_t d[4] = {v.x, v.y, v.z, v.w};
-        uint32_t m = 0;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            m |= ((d[i] & 0xffffu) != 0 ? 1u : 0u) << (2 * i);
-            m |= ((d[i] >> 16) != 0 ? 1u : 0u) << (2 * i + 1);
+            m |= min(d[i] & 0xffffu, 1u) << (2 * i);
+            m |= min(d[i] >> 16, 1u) << (2 * i + 1);
         }
-        return m;
     }
+    return m;
 }
 
-// 16 bytes at element index e0 of a buffer of n elements; elements at or beyond n read as 0.
+// 16 bytes at element index e0 of a buffer of n > 0 elements; elements at or beyond n
+// read as 0.  Branch-free: every address is clamped into the buffer, then selected.
 template <int S> __device__ __forceinline__ uint4 load_vec_guarded(const void *base, uint64_t e0, uint64_t n) {
-    constexpr int E = Geo<S>::E;
-    if (e0 + E <= n) return *reinterpret_cast<const uint4 *>(static_cast<const char *>(base) + e0 * S);
     uint32_t d[4] = {0, 0, 0, 0};
     if (S == 4) {
         const uint32_t *p = static_cast<const uint32_t *>(base);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (e0 + j < n) d[j] = p[e0 + j];
+        for (int j = 0; j < 4; ++j) {
+            const uint64_t e = e0 + j;
+            const uint32_t v = p[e < n ? e : n - 1];
+            d[j] = e < n ? v : 0u;
+        }
     } else {
         const uint16_t *p = static_cast<const uint16_t *>(base);
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            if (e0 + j < n) d[j >> 1] |= (uint32_t)p[e0 + j] << (16 * (j & 1));
+        for (int j = 0; j < 8; ++j) {
+            const uint64_t e = e0 + j;
+            const uint32_t v = p[e < n ? e : n - 1];
+            d[j >> 1] |= (e < n ? v : 0u) << (16 * (j & 1));
+        }
     }
     return make_uint4(d[0], d[1], d[2], d[3]);
 }
@@ -163,156 +174,252 @@ __device__ __forceinline__ uint32_t bitmap_bits(const uint32_t *bitmap, uint64_t
     return m;
 }
 
-// ---- tile bookkeeping ----------------------------------------------------------------
+// ---- grid prefix ---------------------------------------------------------------------------
+//
+// The position of a tile's first value is the number of non-zero elements in all
+// tiles before it (Algorithm 1 appends in index order; Algorithm 2's counter j).
+// Tiles do not talk to each other.  Each tile publishes its count in the workspace;
+// ONE extra workgroup (workgroup 0, a single wave: the "scanner") reads the counts
+// in index order, 512 at a time, keeps the running sum, and writes every tile's
+// prefix back; a tile then polls its own prefix, one 8-byte load.  Per tile that
+// is one store and one polled load on lines shared with few other tiles.  (Having
+// every tile read its predecessors' counts itself -- a look-back window or a tree --
+// makes a few hot lines that thousands of tiles read at once, and those reads
+// queue up at one memory channel.)
+//
+// Nothing a tile waits for depends on another tile having been started: the
+// scanner is workgroup 0, started first, and only waits for counts, which tiles
+// publish before they wait for anything.  Waits are bounded anyway (kSpinLimit).
+//
+// Entries are value + 1 (0 = not published), written and read with relaxed
+// device-scope atomics: the entry is the only thing that is communicated.
 
-__device__ __forceinline__ uint64_t desc_load(const uint64_t *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ uint64_t ws_load64(const void *p) {
+    return __hip_atomic_load(static_cast<const uint64_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void desc_store(uint64_t *p, uint64_t v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ void ws_store64(void *p, uint64_t v) {
+    __hip_atomic_store(static_cast<uint64_t *>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void ws_store32(void *p, uint32_t v) {
+    __hip_atomic_store(static_cast<uint32_t *>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// count + 1 of `tile` in copy c
+__device__ __forceinline__ char *ws_count(char *ws, uint32_t tile, uint32_t copy) {
+    return ws + kHeaderBytes + (size_t)(tile >> 5) * kRecordBytes + 128u * copy + 4u * (tile & 31u);
+}
+// prefix + 1 of `tile` in copy c
+__device__ __forceinline__ char *ws_prefix(char *ws, uint32_t tile, uint32_t copy) {
+    return ws + kHeaderBytes + (size_t)(tile >> 5) * kRecordBytes + 256u + 256u * copy + 8u * (tile & 31u);
 }
 
-// Tiles are handed out by an atomic ticket, so a tile only ever waits for tiles
-// that are already running: the look-back below cannot deadlock whatever order
-// the hardware starts workgroups in.  Called by thread 0 of the block.
-__device__ __forceinline__ void take_ticket(uint32_t *hdr, uint32_t *tile, uint32_t *epoch) {
-    *tile = __hip_atomic_fetch_add(&hdr[kHdrTicket], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    *epoch = __hip_atomic_load(&hdr[kHdrEpoch], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kEpochMask;
-}
-
-// Decoupled look-back, run by one whole wave.  Publishes this tile's count, then
-// walks back over the predecessors' descriptors 64 at a time, adding aggregates
-// until it meets a tile that already knows its inclusive prefix.  Returns the
-// number of non-zero elements in all tiles before `tile`.  A descriptor carries
-// count and status in one 64-bit word, so relaxed device-scope atomics are enough:
-// no other memory is communicated between tiles.  Descriptors of earlier calls
-// carry another epoch and read as "not there yet", so nothing is cleared per call.
-__device__ __forceinline__ uint64_t look_back(uint64_t *desc, uint32_t *hdr, uint32_t tile, uint32_t epoch,
-                                              uint32_t aggregate, int lane) {
-    const uint64_t tag = (uint64_t)epoch << kEpochShift;
-    if (tile == 0) {
-        if (lane == 0) desc_store(&desc[0], tag | (kStPrefix << kStatusShift) | aggregate);
-        return 0;
+__device__ __forceinline__ bool spin_expired(uint32_t *hdr, uint32_t &spins) {
+    // bounded wait: give up after kSpinLimit polls, or soon after anyone has given up
+    ++spins;
+    if (spins > kSpinLimit ||
+        ((spins & 255u) == 0 && __hip_atomic_load(&hdr[kHdrError], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+        __hip_atomic_store(&hdr[kHdrError], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return true;
     }
-    if (lane == 0) desc_store(&desc[tile], tag | (kStAggregate << kStatusShift) | aggregate);
+    __builtin_amdgcn_s_sleep(1);
+    return false;
+}
 
-    uint64_t exclusive = 0;
-    int64_t pos = (int64_t)tile - 1;   // lane 0 looks at the nearest predecessor
+// The scanner: one wave.  Each pass looks at 512 counts starting at the frontier
+// (rounded down to a multiple of 8, so that a lane's 8 counts are one 32-byte
+// chunk), takes the leading run of published ones, turns it into prefixes with a
+// wave prefix sum, writes them, and moves the frontier.  When all counts are in it
+// writes the grand total (nnz) and advances the header for the next call: by then
+// every tile has published its count, hence has read the header.
+__device__ __forceinline__ void scan_counts(char *ws, const uint32_t n_tiles, uint64_t *nnz_out) {
+    const uint32_t lane = threadIdx.x & (kWaveSize - 1);
+    uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
+    const uint32_t seq = hdr[kHdrSeq];
+    const uint32_t cur = seq & 1u;
+    uint32_t frontier = 0;     // tiles [0, frontier) have their prefix
+    uint64_t running = 0;      // non-zeros in tiles [0, frontier)
     uint32_t spins = 0;
-    bool gave_up = false;
-    for (;;) {
-        const int64_t idx = pos - lane;
-        uint64_t d = 0;
-        uint32_t st = 0;
-        uint64_t need = 0;
-        uint64_t have_prefix = 0;
+    while (frontier < n_tiles) {
+        const uint32_t w0 = frontier & ~7u;
+        const uint32_t first = w0 + 8u * lane;          // this lane's 8 tiles
+        uint32_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (first < n_tiles) {                             // the record of `first` exists; all 8 slots are inside it
+            const char *p = ws_count(ws, first, cur);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint64_t v = ws_load64(p + 8 * i);
+                c[2 * i] = (uint32_t)v;
+                c[2 * i + 1] = (uint32_t)(v >> 32);
+            }
+        }
+        // leading run of published counts, as a window-relative end index
+        uint32_t lead = 0;     // number of leading slots of this lane that are usable
+        bool open = true;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t t = first + j;
+            const bool usable = t < frontier || (t < n_tiles && c[j] != 0);   // already done, or published
+            open = open && usable;
+            lead += open ? 1u : 0u;
+        }
+        const uint64_t full = __ballot(lead == 8u);
+        const int stop_lane = full == ~0ull ? 64 : (int)__ffsll((unsigned long long)~full) - 1;
+        uint32_t end = 512u;
+        if (stop_lane < 64) end = 8u * (uint32_t)stop_lane + (uint32_t)__builtin_amdgcn_readlane((int)lead, stop_lane);
+        const uint32_t new_frontier = w0 + end;
+        if (new_frontier <= frontier) {
+            if (spin_expired(hdr, spins)) return;
+            continue;
+        }
+        // prefixes of tiles [frontier, new_frontier)
+        uint32_t mine = 0;
+        uint32_t before[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t t = first + j;
+            before[j] = mine;
+            mine += (t >= frontier && t < new_frontier) ? c[j] - 1u : 0u;
+        }
+        const uint32_t incl = wave_inclusive_sum(mine);
+        const uint64_t lane_base = running + (incl - mine);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t t = first + j;
+            if (t >= frontier && t < new_frontier) ws_store64(ws_prefix(ws, t, cur), lane_base + before[j] + 1);
+        }
+        running += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        frontier = new_frontier;
+    }
+    if (lane == 0) {
+        if (nnz_out != nullptr) *nnz_out = running;           // length(B.values)
+        __hip_atomic_store(&hdr[kHdrPrevTiles], n_tiles, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&hdr[kHdrSeq], seq + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+struct PrefixShared {
+    uint32_t wave_total[kWaves];
+    uint64_t tile_prefix;
+};
+
+// Run by every thread of a tile's block: publishes the tile's count, waits for the
+// scanner's answer, and returns the number of non-zeros before this wave's part
+// of the tile (wave-uniform).  Contains two block barriers.
+__device__ __forceinline__ uint64_t tile_prefix(char *ws, PrefixShared &sh, const uint32_t tile,
+                                                const uint32_t n_tiles, const uint32_t wave_total) {
+    const int tid = threadIdx.x;
+    const uint32_t lane = tid & (kWaveSize - 1), wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);
+    uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
+    // written at the end of the previous call; constant until every tile of this call has published
+    const uint32_t seq = hdr[kHdrSeq];
+    const uint32_t prev_tiles = hdr[kHdrPrevTiles];
+    const uint32_t cur = seq & 1u, other = cur ^ 1u;
+
+    if (lane == 0) sh.wave_total[wave] = wave_total;
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t tile_total = sh.wave_total[0] + sh.wave_total[1] + sh.wave_total[2] + sh.wave_total[3];
+        ws_store32(ws_count(ws, tile, cur), tile_total + 1);
+    }
+    // zero what the previous call left in the other copy: entries [0, prev_tiles)
+    for (uint32_t i = tile + (uint32_t)tid * n_tiles; i < prev_tiles; i += kBlock * n_tiles) {
+        ws_store32(ws_count(ws, i, other), 0);
+        ws_store64(ws_prefix(ws, i, other), 0);
+    }
+    if (tid == 0) {
+        uint64_t v;
+        uint32_t spins = 0;
         for (;;) {
-            if (idx >= 0) {
-                d = desc_load(&desc[idx]);
-                st = ((uint32_t)(d >> kEpochShift) == epoch) ? (uint32_t)(d >> kStatusShift) & 3u : 0u;
-            } else {
-                d = 0;                      // before tile 0: an inclusive prefix of 0
-                st = (uint32_t)kStPrefix;
-            }
-            have_prefix = __ballot(st == (uint32_t)kStPrefix);
-            const uint64_t missing = __ballot(st == 0u);
-            // lanes 0 .. first prefix lane (all 64 if there is none) must be published
-            const uint64_t first = have_prefix & (~have_prefix + 1);
-            need = have_prefix ? (first | (first - 1)) : ~(uint64_t)0;
-            if ((missing & need) == 0) break;
-            // bounded wait: give up after kSpinLimit polls, or soon after any tile has given up
-            ++spins;
-            if (spins > kSpinLimit ||
-                ((spins & 255u) == 0 &&
-                 __hip_atomic_load(&hdr[kHdrError], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
-                gave_up = true;
-                break;
-            }
-            __builtin_amdgcn_s_sleep(1);
+            v = ws_load64(ws_prefix(ws, tile, cur));
+            if (v != 0) break;
+            if (spin_expired(hdr, spins)) { v = 1; break; }
         }
-        if (gave_up) break;
-        const bool mine = (need >> lane) & 1;
-        const uint32_t agg = (mine && st == (uint32_t)kStAggregate) ? (uint32_t)(d & kCountMask) : 0u;
-        exclusive += wave_sum(agg);
-        if (have_prefix) {
-            const int fl = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)have_prefix) - 1);
-            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)d, fl);
-            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(d >> 32), fl);
-            exclusive += (((uint64_t)hi << 32) | lo) & kCountMask;
-            break;
-        }
-        pos -= kWaveSize;
+        sh.tile_prefix = v - 1;
     }
-    if (gave_up) {
-        if (lane == 0) __hip_atomic_store(&hdr[kHdrError], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return exclusive;
-    }
-    if (lane == 0) desc_store(&desc[tile], tag | (kStPrefix << kStatusShift) | (exclusive + aggregate));
-    return exclusive;
+    __syncthreads();
+    uint64_t prefix = sh.tile_prefix;
+    for (uint32_t w = 0; w < wave; ++w) prefix += sh.wave_total[w];
+    // the same value in every lane: tell the compiler, so that addresses built on it stay scalar
+    prefix = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(prefix >> 32)) << 32) |
+             (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)prefix);
+    return prefix;
 }
 
-// Called once per tile (one lane) after its look-back.  The tile that finishes
-// last puts the header back into the state the next call expects: ticket and
-// done counter at 0, epoch advanced.  When the 24-bit epoch wraps, every
-// descriptor is cleared so a tag can never be mistaken for one of 2^24 calls ago.
-__device__ __forceinline__ void tile_done(uint32_t *hdr, uint64_t *desc, uint32_t n_tiles, uint32_t desc_capacity,
-                                          uint32_t epoch) {
-    const uint32_t before = __hip_atomic_fetch_add(&hdr[kHdrDone], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (before + 1 != n_tiles) return;
-    const uint32_t next = (epoch + 1) & kEpochMask;
-    if (next == 0)
-        for (uint32_t i = 0; i < desc_capacity; ++i) desc_store(&desc[i], 0);
-    __hip_atomic_store(&hdr[kHdrTicket], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(&hdr[kHdrDone], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(&hdr[kHdrEpoch], next, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+// A lane's E-bit non-zero masks of all rows, packed RPM rows to a register.
+#define BT_MASK(S_, mp, k) (((mp)[(k) / Geo<S_>::RPM] >> (Geo<S_>::E * ((k) % Geo<S_>::RPM))) & ((1u << Geo<S_>::E) - 1u))
 
-// Per-row popcounts -> exclusive rank of each lane inside its row, and row totals.
-// Two rows share a register (16-bit fields; a row holds at most 512 non-zeros).
-__device__ __forceinline__ void rank_rows(const uint32_t (&m)[kRows], uint32_t (&lane_rank)[kRows],
-                                          uint32_t (&row_total)[kRows]) {
+// Per-row popcounts -> exclusive rank of each lane inside its row (two rows per
+// register, 16-bit fields: a row holds at most 512 non-zeros) and the row totals
+// (same packing, wave-uniform).
+template <int S>
+__device__ __forceinline__ void rank_rows(const uint32_t (&mp)[Geo<S>::MW], uint32_t (&rank2)[kRows / 2],
+                                          uint32_t (&total2)[kRows / 2]) {
 #pragma unroll
     for (int k = 0; k < kRows; k += 2) {
-        const uint32_t packed = (uint32_t)__popc(m[k]) | ((uint32_t)__popc(m[k + 1]) << 16);
+        const uint32_t packed = (uint32_t)__popc(BT_MASK(S, mp, k)) | ((uint32_t)__popc(BT_MASK(S, mp, k + 1)) << 16);
         const uint32_t incl = wave_inclusive_sum(packed);
-        const uint32_t excl = incl - packed;
-        const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-        lane_rank[k] = excl & 0xffffu;
-        lane_rank[k + 1] = excl >> 16;
-        row_total[k] = tot & 0xffffu;
-        row_total[k + 1] = tot >> 16;
+        rank2[k / 2] = incl - packed;
+        total2[k / 2] = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    }
+}
+#define BT_FIELD(arr2, k) (((arr2)[(k) / 2] >> (16 * ((k) & 1))) & 0xffffu)
+
+// Copy `cnt` elements between a wave's LDS strip and global memory with aligned
+// 16-byte accesses.  LDS element `pad + i` corresponds to global element g0 + i,
+// where pad makes LDS byte 0 line up with a 16-byte boundary of the global buffer.
+// The first and last vector go element by element, so nothing outside
+// [g0, g0 + cnt) is touched.  TO_GLOBAL: LDS -> global, else global -> LDS.
+template <int S, bool TO_GLOBAL>
+__device__ __forceinline__ void strip_copy(unsigned char *strip, char *g0_ptr, const uint32_t pad, const uint32_t cnt,
+                                           const int lane) {
+    constexpr int E = Geo<S>::E;
+    if (cnt == 0) return;
+    char *gvec = g0_ptr - (size_t)pad * S;      // 16-byte aligned; may start before g0
+    const uint32_t lo_valid = pad, hi_valid = pad + cnt;
+    const uint32_t n_vec = (hi_valid + E - 1) / E;
+    for (uint32_t v = lane; v < n_vec; v += kWaveSize) {
+        const uint32_t lo = v * E, hi = lo + E;
+        if (lo >= lo_valid && hi <= hi_valid) {
+            uint4 *gp = reinterpret_cast<uint4 *>(gvec + (size_t)lo * S);
+            uint4 *lp = reinterpret_cast<uint4 *>(strip + (size_t)lo * S);
+            if (TO_GLOBAL) *gp = *lp; else *lp = *gp;
+        } else {
+#pragma unroll
+            for (int j = 0; j < E; ++j) {
+                const uint32_t e = lo + j;
+                if (e >= lo_valid && e < hi_valid) {
+                    if (S == 4) {
+                        uint32_t *gp = reinterpret_cast<uint32_t *>(gvec) + e, *lp = reinterpret_cast<uint32_t *>(strip) + e;
+                        if (TO_GLOBAL) *gp = *lp; else *lp = *gp;
+                    } else {
+                        uint16_t *gp = reinterpret_cast<uint16_t *>(gvec) + e, *lp = reinterpret_cast<uint16_t *>(strip) + e;
+                        if (TO_GLOBAL) *gp = *lp; else *lp = *gp;
+                    }
+                }
+            }
+        }
     }
 }
 
 // ---- Algorithm 1: dense -> bitmap -------------------------------------------------------
 
 template <int S>
-__global__ __launch_bounds__(kBlock) void compress_kernel(const void *__restrict__ in, const uint64_t n,
+__global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restrict__ in, const uint64_t n,
                                                           uint32_t *__restrict__ bitmap, void *__restrict__ values,
                                                           const uint64_t values_cap, uint64_t *__restrict__ nnz_out,
-                                                          uint32_t *hdr, uint64_t *desc, const uint32_t n_tiles,
-                                                          const uint32_t desc_capacity) {
+                                                          char *ws, const uint32_t n_tiles) {
     using G = Geo<S>;
     constexpr int E = G::E;
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * G::LDS_WAVE];
-    __shared__ uint32_t s_wave_total[kWaves];
-    __shared__ uint32_t s_tile, s_epoch;
-    __shared__ uint64_t s_tile_base;
+    __shared__ PrefixShared s_prefix;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
-    const int wave = tid >> 6;
-
-    if (tid == 0) {
-        uint32_t t, e;
-        take_ticket(hdr, &t, &e);
-        s_tile = t;
-        s_epoch = e;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in a scalar register
+    if (blockIdx.x == 0) {                   // workgroup 0 is the scanner
+        if (wave == 0) scan_counts(ws, n_tiles, nnz_out);
+        return;
     }
-    __syncthreads();
-    const uint32_t tile = s_tile;
-    const uint32_t epoch = s_epoch;
-    if (tile >= n_tiles) return;   // cannot happen with grid == n_tiles; keeps every access in bounds
+    const uint32_t tile = blockIdx.x - 1;
 
     const uint64_t n_words = (n + 31) >> 5;
     const uint64_t wave_e0 = (uint64_t)tile * G::TILE + (uint64_t)wave * G::WAVE;
@@ -330,103 +437,79 @@ __global__ __launch_bounds__(kBlock) void compress_kernel(const void *__restrict
     }
 
     // (2) Algorithm 1's test "T[i] == 0", on the bit pattern, and the ranks
-    uint32_t m[kRows], lane_rank[kRows], row_total[kRows];
+    uint32_t mp[G::MW], rank2[kRows / 2], total2[kRows / 2];
 #pragma unroll
-    for (int k = 0; k < kRows; ++k) m[k] = nonzero_mask<S>(x[k]);
-    rank_rows(m, lane_rank, row_total);
+    for (int i = 0; i < G::MW; ++i) mp[i] = 0;
+#pragma unroll
+    for (int k = 0; k < kRows; ++k) mp[k / G::RPM] |= nonzero_mask<S>(x[k]) << (E * (k % G::RPM));
+    // Keep the masks as values of their own: otherwise the compiler keeps one compare
+    // result (a scalar register pair) per element alive until the values are written.
+#pragma unroll
+    for (int i = 0; i < G::MW; ++i) asm volatile("" : "+v"(mp[i]));
+    rank_rows<S>(mp, rank2, total2);
     uint32_t wave_total = 0;
-    uint32_t row_base[kRows];
 #pragma unroll
-    for (int k = 0; k < kRows; ++k) {
-        row_base[k] = wave_total;
-        wave_total += row_total[k];
-    }
+    for (int k = 0; k < kRows; ++k) wave_total += BT_FIELD(total2, k);
 
     // (3) "push bit to B.bitmap": G lanes OR their E-bit masks into one 32-bit word,
-    //     then lane (g*G + i) stores the word of row i, group g: one store per wave.
+    //     then lane (g*G + i) stores the word of row r0 + i, group g: one store per G rows.
     {
         const int g = lane / G::G, i = lane % G::G;
-        uint32_t word = 0;
 #pragma unroll
-        for (int k = 0; k < kRows; ++k) {
-            const uint32_t w = group_or<G::G>(m[k] << (uint32_t)(E * i));
-            if (i == k) word = w;
-        }
-        const uint64_t widx = (wave_e0 >> 5) + (uint64_t)i * G::WPR + (uint64_t)g;
-        if (i < kRows && widx < n_words) bitmap[widx] = word;
-    }
-
-    // (4) block total, grid prefix
-    if (lane == 0) s_wave_total[wave] = wave_total;
-    __syncthreads();
-    if (wave == 0) {
-        const uint32_t tile_total = s_wave_total[0] + s_wave_total[1] + s_wave_total[2] + s_wave_total[3];
-        const uint64_t base = look_back(desc, hdr, tile, epoch, tile_total, lane);
-        if (lane == 0) {
-            s_tile_base = base;
-            if (tile == n_tiles - 1) *nnz_out = base + tile_total;   // length(B.values)
-            tile_done(hdr, desc, n_tiles, desc_capacity, epoch);
+        for (int r0 = 0; r0 < kRows; r0 += G::G) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int k = r0; k < r0 + G::G && k < kRows; ++k) {
+                const uint32_t w = group_or<G::G>(BT_MASK(S, mp, k) << (uint32_t)(E * i));
+                if (i == k - r0) word = w;
+            }
+            const uint64_t widx = (wave_e0 >> 5) + (uint64_t)(r0 + i) * G::WPR + (uint64_t)g;
+            if (r0 + i < kRows && widx < n_words) bitmap[widx] = word;
         }
     }
-    __syncthreads();
-    uint64_t wave_base = s_tile_base;
-    for (int w = 0; w < wave; ++w) wave_base += s_wave_total[w];
 
-    // (5) "push T[i] to B.values": compact this wave's non-zeros into its LDS strip,
-    //     shifted so that LDS byte 0 maps to a 16-byte aligned address of `values`,
-    //     then write the strip out with aligned 16-byte stores.
+    // (4) block total -> count for the scanner -> this wave's position in B.values
+    uint64_t g0 = tile_prefix(ws, s_prefix, tile, n_tiles, wave_total);   // index in B.values of this wave's next value
+
+    // (5) "push T[i] to B.values": kPhaseRows rows at a time, compact this wave's
+    //     non-zeros into its LDS strip, then write the strip out with aligned stores.
     unsigned char *strip = s_stage + wave * G::LDS_WAVE;
-    char *gdst = static_cast<char *>(values) + wave_base * S;                 // first value of this wave
-    const uint32_t pad = (uint32_t)(reinterpret_cast<uintptr_t>(gdst) & (kVecBytes - 1)) / S;   // elements
-    if (S == 4) {
-        uint32_t *l = reinterpret_cast<uint32_t *>(strip);
 #pragma unroll
-        for (int k = 0; k < kRows; ++k) {
-            uint32_t r = pad + row_base[k] + lane_rank[k];
+    for (int r0 = 0; r0 < kRows; r0 += kPhaseRows) {
+        char *gdst = static_cast<char *>(values) + g0 * S;
+        const uint32_t pad = (uint32_t)(reinterpret_cast<uintptr_t>(gdst) & (kVecBytes - 1)) / S;   // elements
+        if (r0 != 0) wave_lds_sync();   // the previous phase's reads are done before the strip is reused
+        uint32_t row_start = pad;
+#pragma unroll
+        for (int k = r0; k < r0 + kPhaseRows; ++k) {
+            uint32_t r = row_start + BT_FIELD(rank2, k);
+            const uint32_t mk = BT_MASK(S, mp, k);
             const uint32_t d[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
+            if (S == 4) {
+                uint32_t *l = reinterpret_cast<uint32_t *>(strip);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (m[k] & (1u << j)) l[r] = d[j];
-                r += (m[k] >> j) & 1u;
-            }
-        }
-    } else {
-        uint16_t *l = reinterpret_cast<uint16_t *>(strip);
+                for (int j = 0; j < 4; ++j) {
+                    if (mk & (1u << j)) l[r] = d[j];
+                    r += (mk >> j) & 1u;
+                }
+            } else {
+                uint16_t *l = reinterpret_cast<uint16_t *>(strip);
 #pragma unroll
-        for (int k = 0; k < kRows; ++k) {
-            uint32_t r = pad + row_base[k] + lane_rank[k];
-            const uint32_t d[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if (m[k] & (1u << j)) l[r] = (uint16_t)(d[j >> 1] >> (16 * (j & 1)));
-                r += (m[k] >> j) & 1u;
-            }
-        }
-    }
-    wave_lds_sync();
-
-    // capacity clamp: never write at or beyond values_cap
-    uint32_t cnt = wave_total;
-    if (wave_base >= values_cap) cnt = 0;
-    else if (values_cap - wave_base < cnt) cnt = (uint32_t)(values_cap - wave_base);
-    if (cnt == 0) return;
-    char *gvec = gdst - (size_t)pad * S;                    // 16-byte aligned; may start before the first value
-    const uint32_t lo_valid = pad, hi_valid = pad + cnt;    // LDS element range to write out
-    const uint32_t n_vec = (hi_valid + E - 1) / E;
-    for (uint32_t v = lane; v < n_vec; v += kWaveSize) {
-        const uint32_t lo = v * E, hi = lo + E;
-        if (lo >= lo_valid && hi <= hi_valid) {
-            *reinterpret_cast<uint4 *>(gvec + (size_t)lo * S) = *reinterpret_cast<const uint4 *>(strip + (size_t)lo * S);
-        } else {
-#pragma unroll
-            for (int j = 0; j < E; ++j) {
-                const uint32_t e = lo + j;
-                if (e >= lo_valid && e < hi_valid) {
-                    if (S == 4) reinterpret_cast<uint32_t *>(gvec)[e] = reinterpret_cast<const uint32_t *>(strip)[e];
-                    else reinterpret_cast<uint16_t *>(gvec)[e] = reinterpret_cast<const uint16_t *>(strip)[e];
+                for (int j = 0; j < 8; ++j) {
+                    if (mk & (1u << j)) l[r] = (uint16_t)(d[j >> 1] >> (16 * (j & 1)));
+                    r += (mk >> j) & 1u;
                 }
             }
+            row_start += BT_FIELD(total2, k);
         }
+        wave_lds_sync();
+        const uint32_t phase_total = row_start - pad;
+        // capacity clamp: never write at or beyond values_cap
+        uint32_t cnt = phase_total;
+        if (g0 >= values_cap) cnt = 0;
+        else if (values_cap - g0 < cnt) cnt = (uint32_t)(values_cap - g0);
+        strip_copy<S, true>(strip, gdst, pad, cnt, lane);
+        g0 += phase_total;
     }
 }
 
@@ -435,109 +518,79 @@ __global__ __launch_bounds__(kBlock) void compress_kernel(const void *__restrict
 template <int S>
 __global__ __launch_bounds__(kBlock) void decompress_kernel(const uint32_t *__restrict__ bitmap,
                                                             const void *__restrict__ values, const uint64_t n,
-                                                            void *__restrict__ out, uint32_t *hdr, uint64_t *desc,
-                                                            const uint32_t n_tiles, const uint32_t desc_capacity) {
+                                                            void *__restrict__ out, char *ws, const uint32_t n_tiles) {
     using G = Geo<S>;
     constexpr int E = G::E;
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * G::LDS_WAVE];
-    __shared__ uint32_t s_wave_total[kWaves];
-    __shared__ uint32_t s_tile, s_epoch;
-    __shared__ uint64_t s_tile_base;
+    __shared__ PrefixShared s_prefix;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
-    const int wave = tid >> 6;
-
-    if (tid == 0) {
-        uint32_t t, e;
-        take_ticket(hdr, &t, &e);
-        s_tile = t;
-        s_epoch = e;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in a scalar register
+    if (blockIdx.x == 0) {                   // workgroup 0 is the scanner
+        if (wave == 0) scan_counts(ws, n_tiles, nullptr);
+        return;
     }
-    __syncthreads();
-    const uint32_t tile = s_tile;
-    const uint32_t epoch = s_epoch;
-    if (tile >= n_tiles) return;
+    const uint32_t tile = blockIdx.x - 1;
 
     const uint64_t n_words = (n + 31) >> 5;
     const uint64_t wave_e0 = (uint64_t)tile * G::TILE + (uint64_t)wave * G::WAVE;
 
     // (1) this lane's bits of "B.bitmap[i] is set", and Algorithm 2's counter j as ranks
-    uint32_t m[kRows], lane_rank[kRows], row_total[kRows];
+    uint32_t mp[G::MW], rank2[kRows / 2], total2[kRows / 2];
+#pragma unroll
+    for (int i = 0; i < G::MW; ++i) mp[i] = 0;
 #pragma unroll
     for (int k = 0; k < kRows; ++k)
-        m[k] = bitmap_bits<S>(bitmap, wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E, n, n_words);
-    rank_rows(m, lane_rank, row_total);
+        mp[k / G::RPM] |= bitmap_bits<S>(bitmap, wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E, n, n_words)
+                          << (E * (k % G::RPM));
+    rank_rows<S>(mp, rank2, total2);
     uint32_t wave_total = 0;
-    uint32_t row_base[kRows];
 #pragma unroll
-    for (int k = 0; k < kRows; ++k) {
-        row_base[k] = wave_total;
-        wave_total += row_total[k];
-    }
+    for (int k = 0; k < kRows; ++k) wave_total += BT_FIELD(total2, k);
 
-    // (2) block total, grid prefix
-    if (lane == 0) s_wave_total[wave] = wave_total;
-    __syncthreads();
-    if (wave == 0) {
-        const uint32_t tile_total = s_wave_total[0] + s_wave_total[1] + s_wave_total[2] + s_wave_total[3];
-        const uint64_t base = look_back(desc, hdr, tile, epoch, tile_total, lane);
-        if (lane == 0) {
-            s_tile_base = base;
-            tile_done(hdr, desc, n_tiles, desc_capacity, epoch);
-        }
-    }
-    __syncthreads();
-    uint64_t wave_base = s_tile_base;
-    for (int w = 0; w < wave; ++w) wave_base += s_wave_total[w];
+    // (2) block total -> count for the scanner -> this wave's value of j
+    uint64_t g0 = tile_prefix(ws, s_prefix, tile, n_tiles, wave_total);   // Algorithm 2's j for this wave
 
-    // (3) bring this wave's values[wave_base .. +wave_total) into its LDS strip with
-    //     aligned 16-byte loads (first and last vector element by element: nothing
-    //     outside the wave's own range is ever read)
+    // (3) kPhaseRows rows at a time: bring values[g0 .. g0 + cnt) into the LDS strip with
+    //     aligned loads, then "push B.values[j] / push 0.0 to T": expand from LDS by rank
+    //     and store 16 bytes per lane.
     unsigned char *strip = s_stage + wave * G::LDS_WAVE;
-    const char *gsrc = static_cast<const char *>(values) + wave_base * S;
-    const uint32_t pad = (uint32_t)(reinterpret_cast<uintptr_t>(gsrc) & (kVecBytes - 1)) / S;
-    const char *gvec = gsrc - (size_t)pad * S;
-    const uint32_t lo_valid = pad, hi_valid = pad + wave_total;
-    const uint32_t n_vec = wave_total ? (hi_valid + E - 1) / E : 0;
-    for (uint32_t v = lane; v < n_vec; v += kWaveSize) {
-        const uint32_t lo = v * E, hi = lo + E;
-        if (lo >= lo_valid && hi <= hi_valid) {
-            *reinterpret_cast<uint4 *>(strip + (size_t)lo * S) = *reinterpret_cast<const uint4 *>(gvec + (size_t)lo * S);
-        } else {
 #pragma unroll
-            for (int j = 0; j < E; ++j) {
-                const uint32_t e = lo + j;
-                if (e >= lo_valid && e < hi_valid) {
-                    if (S == 4) reinterpret_cast<uint32_t *>(strip)[e] = reinterpret_cast<const uint32_t *>(gvec)[e];
-                    else reinterpret_cast<uint16_t *>(strip)[e] = reinterpret_cast<const uint16_t *>(gvec)[e];
+    for (int r0 = 0; r0 < kRows; r0 += kPhaseRows) {
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int k = r0; k < r0 + kPhaseRows; ++k) cnt += BT_FIELD(total2, k);
+        char *gsrc = const_cast<char *>(static_cast<const char *>(values)) + g0 * S;
+        const uint32_t pad = (uint32_t)(reinterpret_cast<uintptr_t>(gsrc) & (kVecBytes - 1)) / S;
+        if (r0 != 0) wave_lds_sync();
+        strip_copy<S, false>(strip, gsrc, pad, cnt, lane);
+        wave_lds_sync();
+        uint32_t row_start = pad;
+#pragma unroll
+        for (int k = r0; k < r0 + kPhaseRows; ++k) {
+            uint32_t r = row_start + BT_FIELD(rank2, k);
+            const uint32_t mk = BT_MASK(S, mp, k);
+            uint32_t d[4] = {0, 0, 0, 0};
+            if (S == 4) {
+                const uint32_t *l = reinterpret_cast<const uint32_t *>(strip);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (mk & (1u << j)) d[j] = l[r];
+                    r += (mk >> j) & 1u;
+                }
+            } else {
+                const uint16_t *l = reinterpret_cast<const uint16_t *>(strip);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if (mk & (1u << j)) d[j >> 1] |= (uint32_t)l[r] << (16 * (j & 1));
+                    r += (mk >> j) & 1u;
                 }
             }
+            store_vec_guarded<S>(out, wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E, n, make_uint4(d[0], d[1], d[2], d[3]));
+            row_start += BT_FIELD(total2, k);
         }
-    }
-    wave_lds_sync();
-
-    // (4) "push B.values[j] / push 0.0 to T": expand from LDS by rank, store 16 bytes per lane
-#pragma unroll
-    for (int k = 0; k < kRows; ++k) {
-        uint32_t r = pad + row_base[k] + lane_rank[k];
-        uint32_t d[4] = {0, 0, 0, 0};
-        if (S == 4) {
-            const uint32_t *l = reinterpret_cast<const uint32_t *>(strip);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (m[k] & (1u << j)) d[j] = l[r];
-                r += (m[k] >> j) & 1u;
-            }
-        } else {
-            const uint16_t *l = reinterpret_cast<const uint16_t *>(strip);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if (m[k] & (1u << j)) d[j >> 1] |= (uint32_t)l[r] << (16 * (j & 1));
-                r += (m[k] >> j) & 1u;
-            }
-        }
-        store_vec_guarded<S>(out, wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E, n, make_uint4(d[0], d[1], d[2], d[3]));
+        g0 += cnt;
     }
 }
 
@@ -551,16 +604,18 @@ __global__ __launch_bounds__(kBlock) void relu_backward_kernel(const uint32_t *_
                                                                void *grad_in) {
     using G = Geo<S>;
     constexpr int E = G::E;
+    constexpr int kR = 4;                               // 16-byte vectors per lane
+    constexpr int kTile = kBlock * kR * E;              // elements per block
     const int lane = threadIdx.x & (kWaveSize - 1);
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint64_t n_words = (n + 31) >> 5;
-    const uint64_t wave_e0 = (uint64_t)blockIdx.x * G::TILE + (uint64_t)wave * G::WAVE;
-    const bool full = ((uint64_t)blockIdx.x + 1) * G::TILE <= n;
+    const uint64_t wave_e0 = (uint64_t)blockIdx.x * kTile + (uint64_t)wave * (kR * G::ROW);
+    const bool full = ((uint64_t)blockIdx.x + 1) * kTile <= n;
 
-    uint4 g[kRows];
-    uint32_t m[kRows];
+    uint4 g[kR];
+    uint32_t m[kR];
 #pragma unroll
-    for (int k = 0; k < kRows; ++k) {
+    for (int k = 0; k < kR; ++k) {
         const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
         if (full) {
             g[k] = *reinterpret_cast<const uint4 *>(static_cast<const char *>(grad_out) + e0 * S);
@@ -571,7 +626,7 @@ __global__ __launch_bounds__(kBlock) void relu_backward_kernel(const uint32_t *_
         }
     }
 #pragma unroll
-    for (int k = 0; k < kRows; ++k) {
+    for (int k = 0; k < kR; ++k) {
         const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
         uint32_t d[4] = {g[k].x, g[k].y, g[k].z, g[k].w};
         if (S == 4) {
@@ -616,6 +671,11 @@ uint64_t tiles_for(uint64_t n, int s) {
     return (n + t - 1) / t;
 }
 
+uint64_t relu_blocks_for(uint64_t n, int s) {
+    const uint64_t t = (uint64_t)kBlock * 4 * (kVecBytes / s);
+    return (n + t - 1) / t;
+}
+
 bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
 bt_status launched() { return hipGetLastError() == hipSuccess ? BT_OK : BT_ERR_HIP; }
@@ -625,7 +685,7 @@ bt_status check_common(uint64_t n, bt_dtype dt, const void *d_ws, size_t ws_byte
     if (n > BT_MAX_ELEMENTS) return BT_ERR_SIZE;
     if (n == 0) return BT_OK;
     if (d_ws == nullptr) return BT_ERR_NULL;
-    if (misaligned(d_ws, 8)) return BT_ERR_ALIGN;
+    if (misaligned(d_ws, 128)) return BT_ERR_ALIGN;
     if (ws_bytes < bt_workspace_bytes(n, dt)) return BT_ERR_WORKSPACE;
     return BT_OK;
 }
@@ -647,9 +707,9 @@ size_t bt_compressed_size(uint64_t n, uint64_t nnz, bt_dtype dtype) {
 size_t bt_workspace_bytes(uint64_t n, bt_dtype dtype) {
     const int s = elem_size(dtype);
     if (s == 0) return 0;
-    uint64_t tiles = tiles_for(n, s);
-    if (tiles == 0) tiles = 1;
-    return kHeaderBytes + (size_t)tiles * sizeof(uint64_t);
+    uint64_t records = (tiles_for(n, s) + kTilesPerRecord - 1) / kTilesPerRecord;
+    if (records == 0) records = 1;
+    return kHeaderBytes + (size_t)records * kRecordBytes;
 }
 
 const char *bt_status_str(bt_status status) {
@@ -667,7 +727,7 @@ const char *bt_status_str(bt_status status) {
 
 bt_status bt_workspace_init(void *d_workspace, size_t workspace_bytes, bt_stream stream) {
     if (d_workspace == nullptr) return BT_ERR_NULL;
-    if (misaligned(d_workspace, 8)) return BT_ERR_ALIGN;
+    if (misaligned(d_workspace, 128)) return BT_ERR_ALIGN;
     const uint64_t count = workspace_bytes / 8;
     if (count == 0) return BT_OK;
     const unsigned blocks = (unsigned)((count + 255) / 256);
@@ -693,15 +753,13 @@ bt_status bt_compress(const void *d_in, uint64_t n, bt_dtype dtype, uint32_t *d_
     if (misaligned(d_in, 16) || misaligned(d_bitmap, 4) || misaligned(d_values, (size_t)s)) return BT_ERR_ALIGN;
 
     const uint32_t n_tiles = (uint32_t)tiles_for(n, s);
-    uint32_t *hdr = static_cast<uint32_t *>(d_workspace);
-    uint64_t *desc = reinterpret_cast<uint64_t *>(static_cast<char *>(d_workspace) + kHeaderBytes);
-    const uint32_t desc_cap = (uint32_t)((workspace_bytes - kHeaderBytes) / 8);
+    char *ws = static_cast<char *>(d_workspace);
     if (s == 4)
-        compress_kernel<4><<<dim3(n_tiles), dim3(kBlock), 0, hs>>>(d_in, n, d_bitmap, d_values, values_cap, d_nnz, hdr,
-                                                                   desc, n_tiles, desc_cap);
+        compress_kernel<4><<<dim3(n_tiles + 1), dim3(kBlock), 0, hs>>>(d_in, n, d_bitmap, d_values, values_cap, d_nnz, ws,
+                                                                   n_tiles);
     else
-        compress_kernel<2><<<dim3(n_tiles), dim3(kBlock), 0, hs>>>(d_in, n, d_bitmap, d_values, values_cap, d_nnz, hdr,
-                                                                   desc, n_tiles, desc_cap);
+        compress_kernel<2><<<dim3(n_tiles + 1), dim3(kBlock), 0, hs>>>(d_in, n, d_bitmap, d_values, values_cap, d_nnz, ws,
+                                                                   n_tiles);
     return launched();
 }
 
@@ -716,15 +774,11 @@ bt_status bt_decompress(const uint32_t *d_bitmap, const void *d_values, uint64_t
 
     hipStream_t hs = (hipStream_t)stream;
     const uint32_t n_tiles = (uint32_t)tiles_for(n, s);
-    uint32_t *hdr = static_cast<uint32_t *>(d_workspace);
-    uint64_t *desc = reinterpret_cast<uint64_t *>(static_cast<char *>(d_workspace) + kHeaderBytes);
-    const uint32_t desc_cap = (uint32_t)((workspace_bytes - kHeaderBytes) / 8);
+    char *ws = static_cast<char *>(d_workspace);
     if (s == 4)
-        decompress_kernel<4><<<dim3(n_tiles), dim3(kBlock), 0, hs>>>(d_bitmap, d_values, n, d_out, hdr, desc, n_tiles,
-                                                                     desc_cap);
+        decompress_kernel<4><<<dim3(n_tiles + 1), dim3(kBlock), 0, hs>>>(d_bitmap, d_values, n, d_out, ws, n_tiles);
     else
-        decompress_kernel<2><<<dim3(n_tiles), dim3(kBlock), 0, hs>>>(d_bitmap, d_values, n, d_out, hdr, desc, n_tiles,
-                                                                     desc_cap);
+        decompress_kernel<2><<<dim3(n_tiles + 1), dim3(kBlock), 0, hs>>>(d_bitmap, d_values, n, d_out, ws, n_tiles);
     return launched();
 }
 
@@ -737,11 +791,11 @@ bt_status bt_relu_backward_from_bitmap(const uint32_t *d_bitmap, const void *d_g
     if (d_bitmap == nullptr || d_grad_out == nullptr || d_grad_in == nullptr) return BT_ERR_NULL;
     if (misaligned(d_grad_out, 16) || misaligned(d_grad_in, 16) || misaligned(d_bitmap, 4)) return BT_ERR_ALIGN;
     hipStream_t hs = (hipStream_t)stream;
-    const uint32_t n_tiles = (uint32_t)tiles_for(n, s);
+    const uint32_t blocks = (uint32_t)relu_blocks_for(n, s);
     if (s == 4)
-        relu_backward_kernel<4><<<dim3(n_tiles), dim3(kBlock), 0, hs>>>(d_bitmap, d_grad_out, n, d_grad_in);
+        relu_backward_kernel<4><<<dim3(blocks), dim3(kBlock), 0, hs>>>(d_bitmap, d_grad_out, n, d_grad_in);
     else
-        relu_backward_kernel<2><<<dim3(n_tiles), dim3(kBlock), 0, hs>>>(d_bitmap, d_grad_out, n, d_grad_in);
+        relu_backward_kernel<2><<<dim3(blocks), dim3(kBlock), 0, hs>>>(d_bitmap, d_grad_out, n, d_grad_in);
     return launched();
 }
 

@@ -131,7 +131,8 @@ def test_workspace_reuse_across_calls_and_sizes(gpu, oracle):
         o_bitmap, o_values, _ = _check_compress(gpu, oracle, xh, ws=ws)
         _check_decompress(gpu, oracle, o_bitmap, o_values, n, xh.dtype, wl.bits(xh), ws=ws)
     hdr = ws[:16].cpu().numpy().view(np.uint32)
-    assert hdr[0] == 0 and hdr[1] == 0 and hdr[3] == 0   # ticket, done counter, error flag
+    assert hdr[0] == 32          # calls completed on this workspace (8 sizes x 4 calls)
+    assert hdr[2] == 0           # no tile ever gave up waiting for another tile's count
 
 
 def test_empty_tensor(gpu):
