@@ -180,7 +180,7 @@ __device__ __forceinline__ uint32_t bitmap_bits(const uint32_t *bitmap, uint64_t
 // tiles before it (Algorithm 1 appends in index order; Algorithm 2's counter j).
 // Tiles do not talk to each other.  Each tile publishes its count in the workspace;
 // ONE extra workgroup (workgroup 0, a single wave: the "scanner") reads the counts
-// in index order, 512 at a time, keeps the running sum, and writes every tile's
+// in index order, up to 512 at a time, keeps the running sum, and writes every tile's
 // prefix back; a tile then polls its own prefix, one 8-byte load.  Per tile that
 // is one store and one polled load on lines shared with few other tiles.  (Having
 // every tile read its predecessors' counts itself -- a look-back window or a tree --
@@ -224,12 +224,15 @@ __device__ __forceinline__ bool spin_expired(uint32_t *hdr, uint32_t &spins) {
     return false;
 }
 
-// The scanner: one wave.  Each pass looks at 512 counts starting at the frontier
-// (rounded down to a multiple of 8, so that a lane's 8 counts are one 32-byte
-// chunk), takes the leading run of published ones, turns it into prefixes with a
-// wave prefix sum, writes them, and moves the frontier.  When all counts are in it
-// writes the grand total (nnz) and advances the header for the next call: by then
-// every tile has published its count, hence has read the header.
+// The scanner: one wave.  Each pass looks at kScanRows x 64 counts starting at the
+// frontier rounded down to a multiple of 64; lane l of row j looks at tile
+// w0 + 64*j + l, so every load and store of a row is one contiguous run.  The pass
+// takes the leading run of published counts, turns it into prefixes (a wave prefix
+// sum per row, carried from row to row), writes them, and moves the frontier.
+// When all counts are in it writes the grand total (nnz) and advances the header
+// for the next call: by then every tile has published its count, hence has read
+// the header.
+constexpr int kScanRows = 8;
 __device__ __forceinline__ void scan_counts(char *ws, const uint32_t n_tiles, uint64_t *nnz_out) {
     const uint32_t lane = threadIdx.x & (kWaveSize - 1);
     uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
@@ -239,54 +242,51 @@ __device__ __forceinline__ void scan_counts(char *ws, const uint32_t n_tiles, ui
     uint64_t running = 0;      // non-zeros in tiles [0, frontier)
     uint32_t spins = 0;
     while (frontier < n_tiles) {
-        const uint32_t w0 = frontier & ~7u;
-        const uint32_t first = w0 + 8u * lane;          // this lane's 8 tiles
-        uint32_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (first < n_tiles) {                             // the record of `first` exists; all 8 slots are inside it
-            const char *p = ws_count(ws, first, cur);
+        const uint32_t w0 = frontier & ~63u;
+        uint32_t c[kScanRows];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint64_t v = ws_load64(p + 8 * i);
-                c[2 * i] = (uint32_t)v;
-                c[2 * i + 1] = (uint32_t)(v >> 32);
+        for (int j = 0; j < kScanRows; ++j) {
+            const uint32_t t = w0 + 64u * j + lane;
+            c[j] = 0;
+            if (t < n_tiles)
+                c[j] = __hip_atomic_load(reinterpret_cast<const uint32_t *>(ws_count(ws, t, cur)), __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+        }
+        // Look at every row before writing anything: on this hardware one counter tracks
+        // loads and stores alike, so a load waited for after a store also waits for that
+        // store to reach memory.
+        uint64_t usable_lanes[kScanRows];
+#pragma unroll
+        for (int j = 0; j < kScanRows; ++j) {
+            const uint32_t t = w0 + 64u * j + lane;
+            usable_lanes[j] = __ballot(t < frontier || (t < n_tiles && c[j] != 0));   // done before, or published
+        }
+        // rows are consumed in order while every tile of the row is usable
+        bool open = true;
+        uint32_t new_frontier = frontier;
+#pragma unroll
+        for (int j = 0; j < kScanRows; ++j) {
+            const uint32_t row0 = w0 + 64u * j;
+            const uint32_t t = row0 + lane;
+            if (open && row0 < n_tiles) {
+                const uint64_t bad = ~usable_lanes[j];                             // lanes that stop the run
+                const uint32_t run = bad == 0 ? 64u : (uint32_t)__ffsll((unsigned long long)bad) - 1u;
+                const uint32_t row_end = row0 + run;                               // tiles [row0, row_end) usable
+                if (row_end > new_frontier) {
+                    const bool fresh = t >= frontier && t < row_end;
+                    const uint32_t mine = fresh ? c[j] - 1u : 0u;
+                    const uint32_t incl = wave_inclusive_sum(mine);
+                    if (fresh) ws_store64(ws_prefix(ws, t, cur), running + (incl - mine) + 1);
+                    running += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+                    new_frontier = row_end;
+                }
+                open = run == 64u;
             }
         }
-        // leading run of published counts, as a window-relative end index
-        uint32_t lead = 0;     // number of leading slots of this lane that are usable
-        bool open = true;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t t = first + j;
-            const bool usable = t < frontier || (t < n_tiles && c[j] != 0);   // already done, or published
-            open = open && usable;
-            lead += open ? 1u : 0u;
-        }
-        const uint64_t full = __ballot(lead == 8u);
-        const int stop_lane = full == ~0ull ? 64 : (int)__ffsll((unsigned long long)~full) - 1;
-        uint32_t end = 512u;
-        if (stop_lane < 64) end = 8u * (uint32_t)stop_lane + (uint32_t)__builtin_amdgcn_readlane((int)lead, stop_lane);
-        const uint32_t new_frontier = w0 + end;
-        if (new_frontier <= frontier) {
+        if (new_frontier == frontier) {
             if (spin_expired(hdr, spins)) return;
             continue;
         }
-        // prefixes of tiles [frontier, new_frontier)
-        uint32_t mine = 0;
-        uint32_t before[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t t = first + j;
-            before[j] = mine;
-            mine += (t >= frontier && t < new_frontier) ? c[j] - 1u : 0u;
-        }
-        const uint32_t incl = wave_inclusive_sum(mine);
-        const uint64_t lane_base = running + (incl - mine);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t t = first + j;
-            if (t >= frontier && t < new_frontier) ws_store64(ws_prefix(ws, t, cur), lane_base + before[j] + 1);
-        }
-        running += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
         frontier = new_frontier;
     }
     if (lane == 0) {
@@ -451,25 +451,38 @@ __global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restr
 #pragma unroll
     for (int k = 0; k < kRows; ++k) wave_total += BT_FIELD(total2, k);
 
-    // (3) "push bit to B.bitmap": G lanes OR their E-bit masks into one 32-bit word,
-    //     then lane (g*G + i) stores the word of row r0 + i, group g: one store per G rows.
+    // (3) "push bit to B.bitmap": G lanes OR their E-bit masks into one 32-bit word;
+    //     lane (g*G + i) keeps the word of row r0 + i, group g: one store per G rows.
+    //     The store itself waits until after (4): a store in flight would delay the
+    //     polling loads there, which share its completion counter.
+    constexpr int kWordRegs = (kRows + G::G - 1) / G::G;
+    uint32_t word[kWordRegs];
     {
-        const int g = lane / G::G, i = lane % G::G;
+        const int i = lane % G::G;
 #pragma unroll
         for (int r0 = 0; r0 < kRows; r0 += G::G) {
-            uint32_t word = 0;
+            word[r0 / G::G] = 0;
 #pragma unroll
             for (int k = r0; k < r0 + G::G && k < kRows; ++k) {
                 const uint32_t w = group_or<G::G>(BT_MASK(S, mp, k) << (uint32_t)(E * i));
-                if (i == k - r0) word = w;
+                if (i == k - r0) word[r0 / G::G] = w;
+                // finish this row's word now: left alone, the compiler sinks the selects below
+                // the wait in (4) and keeps one partial result per row alive across it
+                asm volatile("" : "+v"(word[r0 / G::G]));
             }
-            const uint64_t widx = (wave_e0 >> 5) + (uint64_t)(r0 + i) * G::WPR + (uint64_t)g;
-            if (r0 + i < kRows && widx < n_words) bitmap[widx] = word;
         }
     }
 
     // (4) block total -> count for the scanner -> this wave's position in B.values
     uint64_t g0 = tile_prefix(ws, s_prefix, tile, n_tiles, wave_total);   // index in B.values of this wave's next value
+    {
+        const int g = lane / G::G, i = lane % G::G;
+#pragma unroll
+        for (int r0 = 0; r0 < kRows; r0 += G::G) {
+            const uint64_t widx = (wave_e0 >> 5) + (uint64_t)(r0 + i) * G::WPR + (uint64_t)g;
+            if (r0 + i < kRows && widx < n_words) bitmap[widx] = word[r0 / G::G];
+        }
+    }
 
     // (5) "push T[i] to B.values": kPhaseRows rows at a time, compact this wave's
     //     non-zeros into its LDS strip, then write the strip out with aligned stores.
@@ -554,8 +567,11 @@ __global__ __launch_bounds__(kBlock) void decompress_kernel(const uint32_t *__re
 
     // (3) kPhaseRows rows at a time: bring values[g0 .. g0 + cnt) into the LDS strip with
     //     aligned loads, then "push B.values[j] / push 0.0 to T": expand from LDS by rank
-    //     and store 16 bytes per lane.
+    //     into registers.  The dense rows are stored only after the last phase has loaded:
+    //     loads and stores share one completion counter, so a load issued after a store
+    //     would also wait for that store to reach memory.
     unsigned char *strip = s_stage + wave * G::LDS_WAVE;
+    uint4 dense[kRows];
 #pragma unroll
     for (int r0 = 0; r0 < kRows; r0 += kPhaseRows) {
         uint32_t cnt = 0;
@@ -587,10 +603,19 @@ __global__ __launch_bounds__(kBlock) void decompress_kernel(const uint32_t *__re
                     r += (mk >> j) & 1u;
                 }
             }
-            store_vec_guarded<S>(out, wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E, n, make_uint4(d[0], d[1], d[2], d[3]));
+            dense[k] = make_uint4(d[0], d[1], d[2], d[3]);
             row_start += BT_FIELD(total2, k);
         }
         g0 += cnt;
+    }
+    if ((uint64_t)(tile + 1) * G::TILE <= n) {
+        uint4 *p = reinterpret_cast<uint4 *>(static_cast<char *>(out) + wave_e0 * S) + lane;
+#pragma unroll
+        for (int k = 0; k < kRows; ++k) p[k * kWaveSize] = dense[k];
+    } else {
+#pragma unroll
+        for (int k = 0; k < kRows; ++k)
+            store_vec_guarded<S>(out, wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E, n, dense[k]);
     }
 }
 
