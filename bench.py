@@ -26,6 +26,21 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E peak
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_config2_z50.txt")
+
+
+def measured_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size), or None."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            parts = line.split()
+            if len(parts) >= 2 and parts[0] == kernel + "_total_bytes":
+                return int(float(parts[1]))
+    except OSError:
+        pass
+    return None
+
 
 
 def parse():
@@ -36,6 +51,10 @@ def parse():
     ap.add_argument("--sets", type=int, default=8, help="independent buffer sets rotated through (cold-cache timing)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--only-z50", action="store_true", help="skip the 70 % and 90 % sparsity rows")
+    ap.add_argument("--cold-only", action="store_true",
+                    help="skip the same-buffer (warm) timings, so that a profiler's per-kernel average is the cold one")
+    ap.add_argument("--no-step", action="store_true",
+                    help="skip the combined-step loop (in it decompress reads what compress just wrote, i.e. warm data)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of the input tensor, as a known-size reference for counters")
     return ap.parse_args()
@@ -126,14 +145,14 @@ def main():
         for name, fn, alg in (("compress", compress, alg_codec), ("decompress", decompress, alg_codec),
                               ("relu_backward", relu, alg_relu)):
             cold = timed(fn, args.steps, args.warmup)
-            warm = timed(lambda i, fn=fn: fn(0), args.steps, args.warmup)
+            warm = cold if args.cold_only else timed(lambda i, fn=fn: fn(0), args.steps, args.warmup)
             row[name] = {"us_cold": round(cold, 2), "us_warm": round(warm, 2),
                          "input_GBps_cold": round(n * s / cold / 1e3, 1), "input_GBps_warm": round(n * s / warm / 1e3, 1),
                          "algorithmic_bytes": alg,
                          "roofline_frac_cold": round(alg / cold / 1e3 / HBM_PEAK_GBPS, 4),
                          "roofline_frac_warm": round(alg / warm / 1e3 / HBM_PEAK_GBPS, 4)}
         if z == 0.5:
-            t_step = timed(step, args.steps, args.warmup)
+            t_step = float("nan") if args.no_step else timed(step, args.steps, args.warmup)
             headline = {"n": n, "s": s, "nnz": nnz, "t_step_us": t_step, "row": row, "alg_codec": alg_codec}
             if args.copy_calibration:
                 timed(lambda i: outs[i % K].copy_(xs[i % K]), 10, 2)
@@ -146,7 +165,7 @@ def main():
     dom = max(("compress", "decompress"), key=lambda k: row[k]["us_cold"])
     achieved = row[dom]["algorithmic_bytes"] / row[dom]["us_cold"] / 1e3
     roofline = {"bound": "hbm", "kernel": dom + "_kernel<4>", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(dom),
                 "algorithmic_bytes_per_launch": row[dom]["algorithmic_bytes"],
                 "avg_launch_us": row[dom]["us_cold"], "cache": "cold (8 rotating buffer sets)",
                 "frac_warm": row[dom]["roofline_frac_warm"]}

@@ -70,8 +70,9 @@ size_t bt_compressed_size(uint64_t n, uint64_t nnz, bt_dtype dtype);
 size_t bt_bitmap_bytes(uint64_t n);
 
 /* Bytes of scratch that bt_compress / bt_decompress need for a tensor of n
- * elements: a 256-byte header plus one 8-byte descriptor per tile of the
- * single-pass grid scan.  Monotone in n; 0 for an unknown dtype. */
+ * elements: a 256-byte header plus 24 bytes per tile of the single-pass grid
+ * scan (a tile is 8192 four-byte or 16384 two-byte elements), in records of 32
+ * tiles.  Monotone in n; 0 for an unknown dtype. */
 size_t bt_workspace_bytes(uint64_t n, bt_dtype dtype);
 
 /* Size in bytes of one element, 0 for an unknown dtype. */
@@ -86,7 +87,7 @@ const char *bt_status_str(bt_status status);
  * first use, and again if a kernel using it was aborted.  After that the
  * kernels leave the workspace ready for the next call themselves, so
  * bt_compress and bt_decompress are one launch each.
- * d_workspace: 8-byte aligned.  Errors: BT_ERR_NULL, BT_ERR_ALIGN, BT_ERR_HIP. */
+ * d_workspace: 128-byte aligned.  Errors: BT_ERR_NULL, BT_ERR_ALIGN, BT_ERR_HIP. */
 bt_status bt_workspace_init(void *d_workspace, size_t workspace_bytes, bt_stream stream);
 
 /* Algorithm 1 (dense -> bitmap), as one fused pass over the input.
@@ -101,9 +102,10 @@ bt_status bt_workspace_init(void *d_workspace, size_t workspace_bytes, bt_stream
  *               The worst case is n.
  *   d_nnz       one uint64, 8-byte aligned, written by the kernel: valid once
  *               `stream` has reached this call.
- *   d_workspace bt_workspace_bytes(n, dtype) bytes, 8-byte aligned, initialised
+ *   d_workspace bt_workspace_bytes(n, dtype) bytes, 128-byte aligned, initialised
  *               once with bt_workspace_init.  A workspace must not be shared by
- *               two calls that can be in flight at the same time.
+ *               two calls that can be in flight at the same time: calls that use
+ *               one workspace must be ordered (same stream, or events).
  * Input and outputs must not overlap.  "delete T" of Algorithm 1 is the caller
  * dropping d_in after this call is enqueued.  n == 0 only writes *d_nnz = 0.
  * Errors: BT_ERR_NULL, BT_ERR_DTYPE, BT_ERR_ALIGN, BT_ERR_SIZE, BT_ERR_WORKSPACE,

@@ -38,6 +38,10 @@ constexpr int kPhaseRows = 4;             // rows that go through a wave's LDS s
 #endif
 constexpr int kLoadAhead = BT_LOAD_AHEAD; // rows a wave has in flight while it reads its tile
 constexpr int kVecBytes = 16;
+#ifndef BT_RELU_ROWS
+#define BT_RELU_ROWS 1
+#endif
+constexpr int kReluRows = BT_RELU_ROWS;   // 16-byte vectors per lane in the ReLU-backward stream
 
 // ---- workspace layout -----------------------------------------------------------------
 // Header (uint32 words), then one 768-byte record per 32 tiles.
@@ -699,7 +703,7 @@ __global__ __launch_bounds__(kBlock) void relu_backward_kernel(const uint32_t *_
                                                                void *grad_in) {
     using G = Geo<S>;
     constexpr int E = G::E;
-    constexpr int kR = 4;                               // 16-byte vectors per lane
+    constexpr int kR = kReluRows;                       // 16-byte vectors per lane
     constexpr int kTile = kBlock * kR * E;              // elements per block
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -767,7 +771,7 @@ uint64_t tiles_for(uint64_t n, int s) {
 }
 
 uint64_t relu_blocks_for(uint64_t n, int s) {
-    const uint64_t t = (uint64_t)kBlock * 4 * (kVecBytes / s);
+    const uint64_t t = (uint64_t)kBlock * kReluRows * (kVecBytes / s);
     return (n + t - 1) / t;
 }
 
