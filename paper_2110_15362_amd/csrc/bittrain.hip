@@ -107,6 +107,35 @@ __device__ __forceinline__ void wave_lds_sync() {
 
 // ---- per-lane helpers -----------------------------------------------------------
 
+// Bulk data is touched exactly once per call, so most of it is moved with the
+// "non-temporal" hint: it then does not displace what the caches hold.  Measured per
+// kernel on MI355X (fp32, 25.7 M elements, cold / warm microseconds):
+//   compress    plain 38.1/31.3   nt loads 34.2/32.8   nt stores 35.0/30.0   both 33.3/31.3
+//   decompress  plain 35.6/27.6   nt loads 36.3/32.8   nt stores 34.4/27.3   both 35.0/34.2
+//   relu bwd    plain 37.2        nt loads 36.6        nt stores 35.4        both 34.7
+// so compress and the ReLU stream use both hints (their input is dead after the call:
+// "delete T" in Algorithm 1), decompress only the store hint.
+typedef uint32_t bt_u4 __attribute__((ext_vector_type(4)));
+template <bool NT> __device__ __forceinline__ uint4 stream_load(const uint4 *p) {
+    if (NT) {
+        const bt_u4 v = __builtin_nontemporal_load(reinterpret_cast<const bt_u4 *>(p));
+        return make_uint4(v.x, v.y, v.z, v.w);
+    }
+    return *p;
+}
+template <bool NT> __device__ __forceinline__ void stream_store(uint4 *p, const uint4 v) {
+    if (NT) {
+        bt_u4 t;
+        t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
+        __builtin_nontemporal_store(t, reinterpret_cast<bt_u4 *>(p));
+    } else {
+        *p = v;
+    }
+}
+constexpr bool kCompressNtLoad = true, kCompressNtStore = true;
+constexpr bool kDecompressNtLoad = false, kDecompressNtStore = true;
+constexpr bool kReluNtLoad = true, kReluNtStore = true;
+
 // Bit j set <=> element j of the 16-byte vector has a non-zero bit pattern.
 // min(bits, 1) instead of a compare: a compare result lives in a scalar register
 // pair, and 8 rows x 4..8 compares in flight exhaust the scalar registers.
@@ -389,7 +418,7 @@ __device__ __forceinline__ void strip_store(const unsigned char *strip, char *g0
     for (uint32_t v = lane; v < n_vec; v += kWaveSize) {
         const uint32_t lo = v * E, hi = lo + E;
         if (lo >= lo_valid && hi <= hi_valid) {
-            *reinterpret_cast<uint4 *>(gvec + (size_t)lo * S) = *reinterpret_cast<const uint4 *>(strip + (size_t)lo * S);
+            stream_store<kCompressNtStore>(reinterpret_cast<uint4 *>(gvec + (size_t)lo * S), *reinterpret_cast<const uint4 *>(strip + (size_t)lo * S));
         } else {
 #pragma unroll
             for (int j = 0; j < E; ++j) {
@@ -427,7 +456,7 @@ __device__ __forceinline__ void strip_fetch(const char *g0_ptr, const uint32_t p
     for (int i = 0; i < 4; ++i) {
         const uint32_t v = 1u + (uint32_t)lane + (uint32_t)kWaveSize * i;
         f.inner[i] = make_uint4(0, 0, 0, 0);
-        if (v + 1 < n_vec) f.inner[i] = *reinterpret_cast<const uint4 *>(gvec + (size_t)v * kVecBytes);
+        if (v + 1 < n_vec) f.inner[i] = stream_load<kDecompressNtLoad>(reinterpret_cast<const uint4 *>(gvec + (size_t)v * kVecBytes));
     }
     f.edge = 0;
     if (lane < 2 * E && n_vec != 0) {
@@ -496,7 +525,7 @@ __global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restr
     if (full) {
         const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const char *>(in) + wave_e0 * S) + lane;
 #pragma unroll
-        for (int k = 0; k < kLoadAhead && k < kRows; ++k) x[k] = p[k * kWaveSize];
+        for (int k = 0; k < kLoadAhead && k < kRows; ++k) x[k] = stream_load<kCompressNtLoad>(p + k * kWaveSize);
 #pragma unroll
         for (int k = 0; k < kRows; ++k) {
             uint32_t mk = nonzero_mask<S>(x[k]);
@@ -504,7 +533,7 @@ __global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restr
             mp[k / G::RPM] |= mk << (E * (k % G::RPM));
             if (k + kLoadAhead < kRows) {
                 __builtin_amdgcn_sched_barrier(0);   // do not ask for the next row any earlier
-                x[k + kLoadAhead] = p[(k + kLoadAhead) * kWaveSize];
+                x[k + kLoadAhead] = stream_load<kCompressNtLoad>(p + (k + kLoadAhead) * kWaveSize);
             }
         }
     } else {
@@ -686,7 +715,7 @@ __global__ __launch_bounds__(kBlock) void decompress_kernel(const uint32_t *__re
             }
             const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
             const uint4 o = make_uint4(d[0], d[1], d[2], d[3]);
-            if (full) *reinterpret_cast<uint4 *>(static_cast<char *>(out) + e0 * S) = o;
+            if (full) stream_store<kDecompressNtStore>(reinterpret_cast<uint4 *>(static_cast<char *>(out) + e0 * S), o);
             else store_vec_guarded<S>(out, e0, n, o);
             row_start += BT_FIELD(total2, k);
         }
@@ -717,7 +746,7 @@ __global__ __launch_bounds__(kBlock) void relu_backward_kernel(const uint32_t *_
     for (int k = 0; k < kR; ++k) {
         const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
         if (full) {
-            g[k] = *reinterpret_cast<const uint4 *>(static_cast<const char *>(grad_out) + e0 * S);
+            g[k] = stream_load<kReluNtLoad>(reinterpret_cast<const uint4 *>(static_cast<const char *>(grad_out) + e0 * S));
             m[k] = (bitmap[e0 >> 5] >> (uint32_t)(e0 & 31)) & ((1u << E) - 1u);
         } else {
             g[k] = load_vec_guarded<S>(grad_out, e0, n);
@@ -740,7 +769,7 @@ __global__ __launch_bounds__(kBlock) void relu_backward_kernel(const uint32_t *_
             }
         }
         const uint4 o = make_uint4(d[0], d[1], d[2], d[3]);
-        if (full) *reinterpret_cast<uint4 *>(static_cast<char *>(grad_in) + e0 * S) = o;
+        if (full) stream_store<kReluNtStore>(reinterpret_cast<uint4 *>(static_cast<char *>(grad_in) + e0 * S), o);
         else store_vec_guarded<S>(grad_in, e0, n, o);
     }
 }
