@@ -55,9 +55,94 @@ def parse():
                     help="skip the same-buffer (warm) timings, so that a profiler's per-kernel average is the cold one")
     ap.add_argument("--no-step", action="store_true",
                     help="skip the combined-step loop (in it decompress reads what compress just wrote, i.e. warm data)")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="also time configurations 1, 3, 4 and 5 (adds about a minute; reported under `other_configs`)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of the input tensor, as a known-size reference for counters")
     return ap.parse_args()
+
+
+def other_configs(bt, wl, torch, dev, timed, args):
+    """Configurations 1, 3, 4 and 5: cold per-op times and roofline fractions.  Large tensors
+    get fewer buffer sets (each set of configuration 5 is 1.6 GB) but still more than the
+    256 MB last-level cache between two uses of a buffer."""
+    rows = []
+
+    def one(name, x, sets, steps):
+        x = x.reshape(-1)
+        n, s = x.numel(), x.element_size()
+        words = (n + 31) // 32
+        xs = [x.to(dev) for _ in range(sets)]
+        bitmaps = [torch.empty(words, dtype=torch.int32, device=dev) for _ in range(sets)]
+        values = [torch.empty(n, dtype=x.dtype, device=dev) for _ in range(sets)]
+        outs = [torch.empty(n, dtype=x.dtype, device=dev) for _ in range(sets)]
+        nnz_d = torch.zeros(1, dtype=torch.int64, device=dev)
+        ws = bt.new_workspace(n, x.dtype, device=dev)
+        for k in range(sets):
+            bt.bt_compress(xs[k], bitmaps[k], values[k], nnz_d, ws)
+        torch.cuda.synchronize()
+        nnz = int(nnz_d.item())
+        alg = n * s + 4 * words + nnz * s
+        tc = timed(lambda i: bt.bt_compress(xs[i % sets], bitmaps[i % sets], values[i % sets], nnz_d, ws), steps, 3)
+        td = timed(lambda i: bt.bt_decompress(bitmaps[i % sets], values[i % sets], outs[i % sets], ws), steps, 3)
+        tr = timed(lambda i: bt.bt_relu_backward_from_bitmap(bitmaps[i % sets], xs[i % sets], outs[i % sets]), steps, 3)
+        comp = bt.bt_compressed_size(n, nnz, x.dtype)
+        rows.append({"config": name, "n": n, "dtype": str(x.dtype).replace("torch.", ""), "zero_fraction": round(1 - nnz / n, 4),
+                     "compression_ratio": round(n * s / comp, 4), "buffer_sets": sets,
+                     "compress_us": round(tc, 2), "decompress_us": round(td, 2), "relu_backward_us": round(tr, 2),
+                     "compress_roofline_frac": round(alg / tc / 1e3 / HBM_PEAK_GBPS, 4),
+                     "decompress_roofline_frac": round(alg / td / 1e3 / HBM_PEAK_GBPS, 4),
+                     "relu_backward_roofline_frac": round((2 * n * s + 4 * words) / tr / 1e3 / HBM_PEAK_GBPS, 4)})
+
+    one("1: fp32 [1,64,56,56] relu(randn) (launch-latency bound)", wl.config1()["x"], 64, 200)
+    one("3a: bf16 [8,2048,4096] dead feature columns", wl.config3("a")["x"], 8, 50)
+    one("3b: bf16 [8,2048,4096] dead rows (whole empty tiles)", wl.config3("b")["x"], 8, 50)
+    draws = None
+    for p in (0.05, 0.95):
+        c = wl.config5(p, draws=draws)
+        draws = c["draws"]
+        one("5: fp16 [256,64,112,112] zero probability %.2f" % p, c["x"], 3, 20)
+    del draws
+
+    # configuration 4: the 49 ResNet-50 activations, compressed in forward order and restored in
+    # reverse order on one stream with one workspace; value buffers right-sized from nnz
+    shapes = wl.config4_shapes()
+    n_max = max(int(__import__("math").prod(sh)) for sh in shapes)
+    ws = bt.new_workspace(n_max, torch.float32, device=dev)
+    scratch = torch.empty(n_max, dtype=torch.float32, device=dev)
+    nnz_d = torch.zeros(1, dtype=torch.int64, device=dev)
+    xs, stash, dense_bytes, comp_bytes = [], [], 0, 0
+    for cfg in wl.config4_tensors():
+        xd = cfg["x"].reshape(-1).to(dev)
+        n = xd.numel()
+        bitmap = torch.empty((n + 31) // 32, dtype=torch.int32, device=dev)
+        bt.bt_compress(xd, bitmap, scratch[:n], nnz_d, ws)
+        nnz = int(nnz_d.item())
+        xs.append(xd)
+        stash.append((bitmap, torch.empty(nnz, dtype=torch.float32, device=dev), n))
+        dense_bytes += 4 * n
+        comp_bytes += bt.bt_compressed_size(n, nnz, torch.float32)
+    outs = [torch.empty_like(xd) for xd in xs]
+
+    def forward(i):
+        for xd, (bitmap, values, n) in zip(xs, stash):
+            bt.bt_compress(xd, bitmap, values, nnz_d, ws)
+
+    def backward(i):
+        for out, (bitmap, values, n) in zip(reversed(outs), reversed(stash)):
+            bt.bt_decompress(bitmap, values, out, ws)
+
+    tf = timed(forward, 5, 1)
+    tb = timed(backward, 5, 1)
+    alg = dense_bytes + comp_bytes
+    rows.append({"config": "4: ResNet-50 activation set, batch 64, fp32, 49 tensors, 70 % zeros",
+                 "n": dense_bytes // 4, "dense_bytes": dense_bytes, "compressed_bytes": comp_bytes,
+                 "bytes_saved": dense_bytes - comp_bytes, "saved_pct": round(100 * (1 - comp_bytes / dense_bytes), 2),
+                 "compress_all_us": round(tf, 1), "decompress_all_us": round(tb, 1),
+                 "compress_roofline_frac": round(alg / tf / 1e3 / HBM_PEAK_GBPS, 4),
+                 "decompress_roofline_frac": round(alg / tb / 1e3 / HBM_PEAK_GBPS, 4),
+                 "note": "5 GB working set: every tensor is cold when its turn comes"})
+    return rows
 
 
 def main():
@@ -159,6 +244,10 @@ def main():
         ops.append(row)
         del xs, gs, bitmaps, values, outs, gins
 
+    other = None
+    if args.all_configs:
+        other = other_configs(bt, wl, torch, dev, timed, args)
+
     n, s, row = headline["n"], headline["s"], headline["row"]
     t_step = headline["t_step_us"]
     # dominant kernel of the step: the slower of the two codec kernels (the ReLU kernel is a plain stream)
@@ -203,6 +292,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "ops": ops,
+        "other_configs": other,
         "paper_context": "BitTrain reports footprint only (Jetson Nano, fp32): 34.20% on-board / 46.88% theoretical "
                          "reduction at 50% non-zeros, 56.27% / 71.88% at 25% non-zeros (Table 1); no throughput",
     }

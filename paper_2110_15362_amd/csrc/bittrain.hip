@@ -58,6 +58,14 @@ constexpr size_t kHeaderBytes = 256;
 constexpr size_t kRecordBytes = 768;
 constexpr int kTilesPerRecord = 32;
 constexpr uint32_t kSpinLimit = 1u << 20; // polls before a wait is given up
+#ifndef BT_SCANNER_SLEEP
+#define BT_SCANNER_SLEEP 1
+#endif
+#ifndef BT_TILE_SLEEP
+#define BT_TILE_SLEEP 16
+#endif
+constexpr int kScannerSleep = BT_SCANNER_SLEEP;   // pause between two polls, in units of 64 clocks
+constexpr int kTileSleep = BT_TILE_SLEEP;
 
 template <int S> struct Geo {
     static constexpr int E = kVecBytes / S;          // elements per lane per load
@@ -249,7 +257,7 @@ __device__ __forceinline__ char *ws_prefix(char *ws, uint32_t tile, uint32_t cop
     return ws + kHeaderBytes + (size_t)(tile >> 5) * kRecordBytes + 256u + 256u * copy + 8u * (tile & 31u);
 }
 
-__device__ __forceinline__ bool spin_expired(uint32_t *hdr, uint32_t &spins) {
+template <int SLEEP> __device__ __forceinline__ bool spin_expired(uint32_t *hdr, uint32_t &spins) {
     // bounded wait: give up after kSpinLimit polls, or soon after anyone has given up
     ++spins;
     if (spins > kSpinLimit ||
@@ -257,7 +265,7 @@ __device__ __forceinline__ bool spin_expired(uint32_t *hdr, uint32_t &spins) {
         __hip_atomic_store(&hdr[kHdrError], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return true;
     }
-    __builtin_amdgcn_s_sleep(1);
+    __builtin_amdgcn_s_sleep(SLEEP);   // units of 64 clocks
     return false;
 }
 
@@ -324,7 +332,7 @@ __device__ __forceinline__ void scan_counts(char *ws, const uint32_t n_tiles, ui
             }
         }
         if (new_frontier == frontier) {
-            if (spin_expired(hdr, spins)) return;
+            if (spin_expired<kScannerSleep>(hdr, spins)) return;
             continue;
         }
         frontier = new_frontier;
@@ -371,7 +379,7 @@ __device__ __forceinline__ uint64_t tile_prefix(char *ws, PrefixShared &sh, cons
         for (;;) {
             v = ws_load64(ws_prefix(ws, tile, cur));
             if (v != 0) break;
-            if (spin_expired(hdr, spins)) { v = 1; break; }
+            if (spin_expired<kTileSleep>(hdr, spins)) { v = 1; break; }
         }
         sh.tile_prefix = v - 1;
     }
