@@ -114,3 +114,20 @@ def test_argument_errors_are_found_on_the_host(bt):
     assert relu(n=0, bm=None, g=None, gi=None) == 0
     assert L.bt_workspace_init(None, 100, None) == 1
     assert L.bt_workspace_init(A + 1, 100, None) == 3
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode == 2
+    assert "single-GPU" in res.stderr
+
+
+def test_workspace_bytes_cover_every_tile(bt):
+    # 256-byte header + one 768-byte record per 32 tiles of 32 KiB of dense data
+    for code, elems_per_tile in ((bt.BT_F32, 8192), (bt.BT_F16, 16384), (bt.BT_BF16, 16384)):
+        for tiles in (1, 32, 33, 3136, 100000):
+            n = tiles * elems_per_tile
+            assert bt.bt_workspace_bytes(n, code) == 256 + 768 * ((tiles + 31) // 32)
+            assert bt.bt_workspace_bytes(n + 1, code) == 256 + 768 * ((tiles + 1 + 31) // 32)

@@ -135,6 +135,43 @@ def test_workspace_reuse_across_calls_and_sizes(gpu, oracle):
     assert hdr[2] == 0           # no tile ever gave up waiting for another tile's count
 
 
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_tile_record_and_scan_window_boundaries(gpu, oracle, dt):
+    """Sizes around the bookkeeping granularities: a tile (8192 fp32 / 16384 16-bit elements), a
+    workspace record (32 tiles), a scanner row (64 tiles) and a scanner pass (512 tiles)."""
+    tile = 8192 if dt == "f32" else 16384
+    sizes = []
+    for tiles in (1, 31, 32, 33, 63, 64, 65, 511, 512, 513, 1025):
+        sizes += [tiles * tile - 1, tiles * tile, tiles * tile + 1]
+    for i, n in enumerate(sizes):
+        x = wl.random_sparse(n, dt, 0.5 if i % 3 else 0.97, seed=6000 + i)
+        o_bitmap, o_values, _ = _check_compress(gpu, oracle, x)
+        _check_decompress(gpu, oracle, o_bitmap, o_values, n, x.dtype, wl.bits(x))
+
+
+def test_workspace_reuse_large_small_large(gpu, oracle):
+    """What a call leaves in the workspace must never be mistaken for the next call's
+    counts, whatever the order of sizes (more tiles, fewer tiles, more again)."""
+    import paper_2110_15362_amd.bittrain as bt
+    ws = bt.new_workspace(8192 * 1300, torch.float32)
+    for rep, tiles in enumerate([1300, 3, 700, 1, 1299, 64, 65, 1300, 513]):
+        n = 8192 * tiles - 5 * rep
+        x = wl.random_sparse(n, "f32", 0.3 + 0.07 * rep, seed=7000 + rep)
+        o_bitmap, o_values, _ = _check_compress(gpu, oracle, x, ws=ws)
+        _check_decompress(gpu, oracle, o_bitmap, o_values, n, x.dtype, wl.bits(x), ws=ws)
+        _check_decompress(gpu, oracle, o_bitmap, o_values, n, x.dtype, wl.bits(x), ws=ws)
+    assert ws[:16].cpu().numpy().view(np.uint32)[2] == 0
+
+
+def test_all_zero_and_all_nonzero_large(gpu, oracle):
+    n = 8192 * 700 + 123
+    for x in (torch.zeros(n), torch.full((n,), -1.5), torch.zeros(n, dtype=torch.float16),
+              torch.full((n,), 0.25, dtype=torch.bfloat16)):
+        o_bitmap, o_values, o_nnz = _check_compress(gpu, oracle, x)
+        assert o_nnz in (0, n)
+        _check_decompress(gpu, oracle, o_bitmap, o_values, n, x.dtype, wl.bits(x))
+
+
 def test_empty_tensor(gpu):
     import paper_2110_15362_amd.bittrain as bt
     dev = "cuda"
