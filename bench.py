@@ -104,6 +104,26 @@ def other_configs(bt, wl, torch, dev, timed, args):
         one("5: fp16 [256,64,112,112] zero probability %.2f" % p, c["x"], 3, 20)
     del draws
 
+    # Section 4.3 fused into Algorithm 1 (next-step row): pre-activations of configuration 2, thresholds of the paper
+    pre = wl.config2(0.5)["base"].reshape(-1)
+    n, sets = pre.numel(), 8
+    xs = [pre.to(dev) for _ in range(sets)]
+    bitmaps = [torch.empty((n + 31) // 32, dtype=torch.int32, device=dev) for _ in range(sets)]
+    values = [torch.empty(n, dtype=pre.dtype, device=dev) for _ in range(sets)]
+    nnz_d = torch.zeros(1, dtype=torch.int64, device=dev)
+    ws = bt.new_workspace(n, pre.dtype, device=dev)
+    for thr in (0.0, 0.01, 0.05, 0.1):
+        bt.bt_compress_pruned(xs[0], thr, bitmaps[0], values[0], nnz_d, ws)
+        torch.cuda.synchronize()
+        nnz = int(nnz_d.item())
+        alg = n * 4 + 4 * ((n + 31) // 32) + nnz * 4
+        t = timed(lambda i: bt.bt_compress_pruned(xs[i % sets], thr, bitmaps[i % sets], values[i % sets], nnz_d, ws), 100, 5)
+        rows.append({"config": "fused prune+compress of N(0,1) pre-activations [32,256,56,56] fp32, threshold %.2f" % thr,
+                     "n": n, "zero_fraction": round(1 - nnz / n, 4),
+                     "compression_ratio": round(n * 4 / bt.bt_compressed_size(n, nnz, pre.dtype), 4),
+                     "compress_us": round(t, 2), "compress_roofline_frac": round(alg / t / 1e3 / HBM_PEAK_GBPS, 4)})
+    del xs, bitmaps, values
+
     # configuration 4: the 49 ResNet-50 activations, compressed in forward order and restored in
     # reverse order on one stream with one workspace; value buffers right-sized from nnz
     shapes = wl.config4_shapes()

@@ -115,6 +115,22 @@ bt_status bt_compress(const void *d_in, uint64_t n, bt_dtype dtype,
                       uint64_t *d_nnz,
                       void *d_workspace, size_t workspace_bytes, bt_stream stream);
 
+/* Activation pruning (Section 4.3) fused into Algorithm 1: one pass that stores an
+ * element only where its value exceeds `threshold` and treats it as zero elsewhere
+ * (the paper's thresholds are 0, 0.01, 0.05 and 0.1).  The comparison is strict and is
+ * made in single precision after widening fp16 / bf16 exactly; a NaN exceeds nothing
+ * and is dropped.  The result is exactly bt_compress of the pruned tensor (so a +0.0
+ * that survives a negative threshold is still not stored).  The bitmap marks the kept
+ * elements, d_values holds their original
+ * bit patterns in index order, *d_nnz their number.  With threshold 0 on a
+ * pre-activation tensor x this is compress(ReLU(x)) without ever writing ReLU(x):
+ * bt_decompress then yields ReLU(x) and bt_relu_backward_from_bitmap its backward.
+ * All arguments, requirements and errors as for bt_compress. */
+bt_status bt_compress_pruned(const void *d_in, uint64_t n, bt_dtype dtype, float threshold,
+                             uint32_t *d_bitmap, void *d_values, uint64_t values_cap,
+                             uint64_t *d_nnz,
+                             void *d_workspace, size_t workspace_bytes, bt_stream stream);
+
 /* Algorithm 2 (bitmap -> dense).
  *   d_bitmap    ceil(n/32) words as written by bt_compress (bits at positions
  *               >= n are ignored).

@@ -23,6 +23,12 @@
  *   - the element is defined by its width only (2, 4 or 8 bytes): fp16 and
  *     bf16 are the same codec.
  *
+ * Activation pruning (Section 4.3) is bt_oracle_prune: an element is kept where its
+ * value exceeds the threshold (strictly; the comparison is made in single precision
+ * after widening half / bfloat16 exactly; a NaN exceeds nothing) and becomes +0
+ * elsewhere.  With threshold 0 on a pre-activation tensor this is ReLU.  Pruning
+ * followed by Algorithm 1 is what the fused GPU call is checked against.
+ *
  * Parity pins (tests/test_oracle_*.py): the theoretical columns of Table 1,
  * hand-built tensors, numpy.packbits / boolean indexing, enumeration of all
  * 2^16 zero patterns of a 16-element tensor, every n in [0,130], closed forms
@@ -128,4 +134,57 @@ int bt_oracle_relu_backward(const uint32_t *bitmap, const void *grad_out,
         store_bits(o, i, width, keep ? load_bits(g, i, width) : 0);
     }
     return 0;
+}
+
+/* ---- activation pruning (Section 4.3) ---------------------------------------- */
+
+/* dtype codes of this file only: 0 = fp32, 1 = fp16, 2 = bfloat16 */
+static float widen_to_f32(uint64_t bits, int dtype)
+{
+    uint32_t u;
+    float f;
+    if (dtype == 0) {
+        u = (uint32_t)bits;
+    } else if (dtype == 2) {
+        u = (uint32_t)bits << 16;                       /* bfloat16 is the top half of fp32 */
+    } else {
+        uint32_t sign = ((uint32_t)bits >> 15) & 1u;
+        uint32_t exp = ((uint32_t)bits >> 10) & 0x1Fu;
+        uint32_t man = (uint32_t)bits & 0x3FFu;
+        if (exp == 0x1F) {                              /* infinity or NaN */
+            u = (sign << 31) | 0x7F800000u | (man << 13);
+        } else if (exp != 0) {                          /* normal: rebias 15 -> 127 */
+            u = (sign << 31) | ((exp + 112u) << 23) | (man << 13);
+        } else if (man == 0) {                          /* zero */
+            u = sign << 31;
+        } else {                                        /* subnormal: man * 2^-24, normal in fp32 */
+            int shift = 0;
+            while ((man & 0x400u) == 0) { man <<= 1; ++shift; }
+            man &= 0x3FFu;
+            u = (sign << 31) | ((uint32_t)(113 - shift) << 23) | (man << 13);
+        }
+    }
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/* out[i] = T[i] where value(T[i]) > threshold, +0 (all-zero bits) elsewhere.
+ * Returns the number of kept elements, or UINT64_MAX for an unknown dtype. */
+uint64_t bt_oracle_prune(const void *T, uint64_t n, int dtype, float threshold, void *out)
+{
+    if (dtype < 0 || dtype > 2) return UINT64_MAX;
+    const int width = dtype == 0 ? 4 : 2;
+    const unsigned char *t = (const unsigned char *)T;
+    unsigned char *o = (unsigned char *)out;
+    uint64_t kept = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        uint64_t bits = load_bits(t, i, width);
+        if (widen_to_f32(bits, dtype) > threshold) {
+            store_bits(o, i, width, bits);
+            kept += 1;
+        } else {
+            store_bits(o, i, width, 0);
+        }
+    }
+    return kept;
 }

@@ -41,6 +41,8 @@ def _load():
         lib.bt_oracle_decompress.argtypes = [vp, vp, u64, ci, vp]
         lib.bt_oracle_relu_backward.restype = ci
         lib.bt_oracle_relu_backward.argtypes = [vp, vp, u64, ci, vp]
+        lib.bt_oracle_prune.restype = u64
+        lib.bt_oracle_prune.argtypes = [vp, u64, ci, ctypes.c_float, vp]
         _lib = lib
     return _lib
 
@@ -99,3 +101,24 @@ def relu_backward(bitmap, grad_out):
     rc = _load().bt_oracle_relu_backward(_ptr(bitmap), _ptr(g), n, g.dtype.itemsize, _ptr(out))
     assert rc == 0
     return out
+
+
+DTYPE_CODES = {"f32": 0, "f16": 1, "bf16": 2}
+
+
+def prune(T, dtype, threshold):
+    """Section 4.3: keep elements whose value exceeds the threshold, +0 elsewhere.
+    T holds raw bits (uint32 for "f32", uint16 for "f16" / "bf16")."""
+    T = _flat(T)
+    code = DTYPE_CODES[dtype]
+    assert T.dtype.itemsize == (4 if code == 0 else 2)
+    out = np.empty_like(T)
+    out.view(np.uint8)[:] = 0xA5
+    kept = int(_load().bt_oracle_prune(_ptr(T), T.size, code, float(np.float32(threshold)), _ptr(out)))
+    assert kept <= T.size
+    return out
+
+
+def compress_pruned(T, dtype, threshold):
+    """Pruning followed by Algorithm 1: (bitmap, values, nnz)."""
+    return compress(prune(T, dtype, threshold))

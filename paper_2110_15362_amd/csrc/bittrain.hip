@@ -163,6 +163,38 @@ template <int S> __device__ __forceinline__ uint32_t nonzero_mask(const uint4 v)
     return m;
 }
 
+// Which elements of the 16-byte vector are stored.  KEEP = kKeepNonZero: Algorithm 1's
+// test (non-zero bit pattern).  Otherwise activation pruning (Section 4.3) followed by
+// that test, in one pass: an element survives pruning where its value exceeds
+// `threshold`, compared in single precision after widening (exact for half and
+// bfloat16; a NaN exceeds nothing), and is then stored if its bit pattern is non-zero
+// (a +0.0 that survives a negative threshold is still a zero for Algorithm 1).
+enum { kKeepNonZero = 0, kKeepAboveF32 = 1, kKeepAboveF16 = 2, kKeepAboveBF16 = 3 };
+template <int S, int KEEP> __device__ __forceinline__ uint32_t keep_mask(const uint4 v, const float threshold) {
+    if (KEEP == kKeepNonZero) return nonzero_mask<S>(v);
+    const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+    uint32_t m = 0;
+    if (KEEP == kKeepAboveF32) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) m |= (__uint_as_float(d[i]) > threshold ? 1u : 0u) << i;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float lo, hi;
+            if (KEEP == kKeepAboveBF16) {
+                lo = __uint_as_float(d[i] << 16);
+                hi = __uint_as_float(d[i] & 0xffff0000u);
+            } else {
+                lo = (float)__builtin_bit_cast(_Float16, (uint16_t)(d[i] & 0xffffu));
+                hi = (float)__builtin_bit_cast(_Float16, (uint16_t)(d[i] >> 16));
+            }
+            m |= (lo > threshold ? 1u : 0u) << (2 * i);
+            m |= (hi > threshold ? 1u : 0u) << (2 * i + 1);
+        }
+    }
+    return m & nonzero_mask<S>(v);
+}
+
 // 16 bytes at element index e0 of a buffer of n > 0 elements; elements at or beyond n
 // read as 0.  Branch-free: every address is clamped into the buffer, then selected.
 template <int S> __device__ __forceinline__ uint4 load_vec_guarded(const void *base, uint64_t e0, uint64_t n) {
@@ -497,11 +529,11 @@ __device__ __forceinline__ void strip_commit(unsigned char *strip, const uint32_
 
 // ---- Algorithm 1: dense -> bitmap -------------------------------------------------------
 
-template <int S>
+template <int S, int KEEP>
 __global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restrict__ in, const uint64_t n,
                                                           uint32_t *__restrict__ bitmap, void *__restrict__ values,
                                                           const uint64_t values_cap, uint64_t *__restrict__ nnz_out,
-                                                          char *ws, const uint32_t n_tiles) {
+                                                          char *ws, const uint32_t n_tiles, const float threshold) {
     using G = Geo<S>;
     constexpr int E = G::E;
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * G::LDS_WAVE];
@@ -536,7 +568,7 @@ __global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restr
         for (int k = 0; k < kLoadAhead && k < kRows; ++k) x[k] = stream_load<kCompressNtLoad>(p + k * kWaveSize);
 #pragma unroll
         for (int k = 0; k < kRows; ++k) {
-            uint32_t mk = nonzero_mask<S>(x[k]);
+            uint32_t mk = keep_mask<S, KEEP>(x[k], threshold);
             asm volatile("" : "+v"(mk));             // row k has arrived: its mask exists from here on
             mp[k / G::RPM] |= mk << (E * (k % G::RPM));
             if (k + kLoadAhead < kRows) {
@@ -547,8 +579,11 @@ __global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restr
     } else {
 #pragma unroll
         for (int k = 0; k < kRows; ++k) {
-            x[k] = load_vec_guarded<S>(in, wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E, n);
-            mp[k / G::RPM] |= nonzero_mask<S>(x[k]) << (E * (k % G::RPM));
+            const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
+            x[k] = load_vec_guarded<S>(in, e0, n);
+            // elements at or beyond n read as 0, which a negative threshold would keep: mask them
+            const uint32_t in_range = e0 >= n ? 0u : (n - e0 >= (uint64_t)E ? (1u << E) - 1u : (1u << (uint32_t)(n - e0)) - 1u);
+            mp[k / G::RPM] |= (keep_mask<S, KEEP>(x[k], threshold) & in_range) << (E * (k % G::RPM));
         }
     }
     // Keep the masks as values of their own: otherwise the compiler keeps one compare
@@ -871,9 +906,9 @@ bt_status bt_workspace_init(void *d_workspace, size_t workspace_bytes, bt_stream
     return launched();
 }
 
-bt_status bt_compress(const void *d_in, uint64_t n, bt_dtype dtype, uint32_t *d_bitmap, void *d_values,
-                      uint64_t values_cap, uint64_t *d_nnz, void *d_workspace, size_t workspace_bytes,
-                      bt_stream stream) {
+static bt_status compress_common(const void *d_in, uint64_t n, bt_dtype dtype, bool prune, float threshold,
+                                 uint32_t *d_bitmap, void *d_values, uint64_t values_cap, uint64_t *d_nnz,
+                                 void *d_workspace, size_t workspace_bytes, bt_stream stream) {
     const bt_status st = check_common(n, dtype, d_workspace, workspace_bytes);
     if (st != BT_OK) return st;
     if (d_nnz == nullptr) return BT_ERR_NULL;
@@ -890,13 +925,35 @@ bt_status bt_compress(const void *d_in, uint64_t n, bt_dtype dtype, uint32_t *d_
 
     const uint32_t n_tiles = (uint32_t)tiles_for(n, s);
     char *ws = static_cast<char *>(d_workspace);
-    if (s == 4)
-        compress_kernel<4><<<dim3(n_tiles + 1), dim3(kBlock), 0, hs>>>(d_in, n, d_bitmap, d_values, values_cap, d_nnz, ws,
-                                                                   n_tiles);
-    else
-        compress_kernel<2><<<dim3(n_tiles + 1), dim3(kBlock), 0, hs>>>(d_in, n, d_bitmap, d_values, values_cap, d_nnz, ws,
-                                                                   n_tiles);
+    const dim3 grid(n_tiles + 1), block(kBlock);
+#define BT_LAUNCH_COMPRESS(S_, KEEP_) \
+    compress_kernel<S_, KEEP_><<<grid, block, 0, hs>>>(d_in, n, d_bitmap, d_values, values_cap, d_nnz, ws, n_tiles, threshold)
+    if (!prune) {
+        if (s == 4) BT_LAUNCH_COMPRESS(4, kKeepNonZero);
+        else BT_LAUNCH_COMPRESS(2, kKeepNonZero);
+    } else if (dtype == BT_F32) {
+        BT_LAUNCH_COMPRESS(4, kKeepAboveF32);
+    } else if (dtype == BT_F16) {
+        BT_LAUNCH_COMPRESS(2, kKeepAboveF16);
+    } else {
+        BT_LAUNCH_COMPRESS(2, kKeepAboveBF16);
+    }
+#undef BT_LAUNCH_COMPRESS
     return launched();
+}
+
+bt_status bt_compress(const void *d_in, uint64_t n, bt_dtype dtype, uint32_t *d_bitmap, void *d_values,
+                      uint64_t values_cap, uint64_t *d_nnz, void *d_workspace, size_t workspace_bytes,
+                      bt_stream stream) {
+    return compress_common(d_in, n, dtype, false, 0.0f, d_bitmap, d_values, values_cap, d_nnz, d_workspace,
+                           workspace_bytes, stream);
+}
+
+bt_status bt_compress_pruned(const void *d_in, uint64_t n, bt_dtype dtype, float threshold, uint32_t *d_bitmap,
+                             void *d_values, uint64_t values_cap, uint64_t *d_nnz, void *d_workspace,
+                             size_t workspace_bytes, bt_stream stream) {
+    return compress_common(d_in, n, dtype, true, threshold, d_bitmap, d_values, values_cap, d_nnz, d_workspace,
+                           workspace_bytes, stream);
 }
 
 bt_status bt_decompress(const uint32_t *d_bitmap, const void *d_values, uint64_t n, bt_dtype dtype, void *d_out,

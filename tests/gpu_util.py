@@ -15,7 +15,7 @@ def _sentinel(numel, dtype, dev):
     return t
 
 
-def gpu_compress(x, cap=None, ws=None, values_offset=0, dev="cuda"):
+def gpu_compress(x, cap=None, ws=None, values_offset=0, dev="cuda", threshold=None):
     """Returns (bitmap uint32[W], values bits[cap], nnz, tail_ok) where tail_ok says the
     guard words after the bitmap and the values beyond min(nnz, cap) still hold the sentinel."""
     x = x.contiguous().reshape(-1)
@@ -29,7 +29,10 @@ def gpu_compress(x, cap=None, ws=None, values_offset=0, dev="cuda"):
     nnz = torch.full((1,), -7, dtype=torch.int64, device=dev)
     if ws is None:
         ws = bt.new_workspace(n, x.dtype, device=dev)
-    bt.bt_compress(xd, bitmap[:words], values, nnz, ws)
+    if threshold is None:
+        bt.bt_compress(xd, bitmap[:words], values, nnz, ws)
+    else:
+        bt.bt_compress_pruned(xd, threshold, bitmap[:words], values, nnz, ws)
     torch.cuda.synchronize()
     nnz_h = int(nnz.item())
     bm = bitmap.cpu().numpy().view(np.uint32)

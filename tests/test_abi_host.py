@@ -28,7 +28,8 @@ def _declared_functions():
 
 def test_every_declared_symbol_is_exported(bt):
     names = _declared_functions()
-    assert {"bt_compress", "bt_compressed_size", "bt_decompress", "bt_relu_backward_from_bitmap"} <= set(names)
+    assert {"bt_compress", "bt_compressed_size", "bt_decompress", "bt_relu_backward_from_bitmap",
+            "bt_compress_pruned"} <= set(names)
     raw = ctypes.CDLL(bt.LIB_PATH)
     for name in names:
         assert hasattr(raw, name), name

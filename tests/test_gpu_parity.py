@@ -289,3 +289,47 @@ def test_repeated_calls_are_identical(gpu, oracle):
         assert torch.equal(bitmap, ref_bitmap)
         assert torch.equal(values[:o_nnz].view(torch.int16), ref_values)
         assert torch.equal(out.view(torch.int16), xd.view(torch.int16))
+
+
+# ---- activation pruning fused into compression (Section 4.3) ------------------------------
+
+
+def _check_compress_pruned(gpu, oracle, x, dt, thr, **kw):
+    o_bitmap, o_values, o_nnz = oracle.compress_pruned(wl.bits(x), dt, thr)
+    bitmap, values, nnz, tail_ok = gpu.gpu_compress(x, threshold=thr, **kw)
+    assert nnz == o_nnz
+    assert np.array_equal(bitmap, o_bitmap)
+    assert np.array_equal(values[:o_nnz], o_values)
+    assert tail_ok
+    return o_bitmap, o_values, o_nnz
+
+
+@pytest.mark.parametrize("dt", DTYPES)
+def test_compress_pruned_thresholds_and_tails(gpu, oracle, dt):
+    """The paper's thresholds (0, 0.01, 0.05, 0.1) plus a negative and an infinite one, on
+    pre-activation tensors (no ReLU applied), at sizes that cover tiles and ragged tails."""
+    for i, n in enumerate([1, 7, 33, 4097, 8192, 8193, 16385, 3 * 16384 + 5, 100003, 600001]):
+        x = wl.random_sparse(n, dt, 0.1, seed=8000 + i)      # N(0,1) with a few exact zeros
+        for thr in (0.0, 0.01, 0.05, 0.1, -0.5, float("inf")):
+            o_bitmap, o_values, o_nnz = _check_compress_pruned(gpu, oracle, x, dt, thr)
+        # decompressing the threshold-0 form gives ReLU(x) bit for bit (ReLU(-0.0) = +0 here)
+        o_bitmap, o_values, o_nnz = oracle.compress_pruned(wl.bits(x), dt, 0.0)
+        relu_bits = wl.bits(torch.where(x.float() > 0, x, torch.zeros_like(x)))
+        _check_decompress(gpu, oracle, o_bitmap, o_values, n, x.dtype, relu_bits)
+
+
+@pytest.mark.parametrize("dt", DTYPES)
+def test_compress_pruned_special_values(gpu, oracle, dt):
+    """Denormals, -0.0, infinities and NaNs against thresholds that are themselves tiny:
+    the comparison is the IEEE single-precision one on both sides."""
+    x = wl.special_values(dt).repeat(1100)[:17000]
+    tiny = {"f32": 1e-45, "f16": 6e-8, "bf16": 1e-40}[dt]
+    for thr in (0.0, tiny, -tiny, 1.0, float("-inf"), float("nan")):
+        _check_compress_pruned(gpu, oracle, x, dt, thr)
+
+
+def test_compress_pruned_config2_full_size(gpu, oracle):
+    x = wl.config2(0.5)["base"]                      # the pre-activation draw: N(0,1), no zeros
+    for thr in (0.0, 0.1):
+        o_bitmap, o_values, o_nnz = _check_compress_pruned(gpu, oracle, x, "f32", thr)
+        assert abs(o_nnz / x.numel() - (0.5 if thr == 0.0 else 0.4602)) < 2e-3

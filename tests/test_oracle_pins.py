@@ -229,3 +229,54 @@ def test_workload_recipes_round_trip(oracle):
         bitmap, values, nnz = oracle.compress(xb)
         assert nnz == 12 and bitmap.tolist() == [0b1100101111111110]
         assert np.array_equal(oracle.decompress(bitmap, values, 16), xb)
+
+
+# ---- activation pruning (Section 4.3) -----------------------------------------------------
+
+
+def _f16_bits_to_f32(bits):
+    return bits.view(np.float16).astype(np.float32)
+
+
+def _bf16_bits_to_f32(bits):
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+@pytest.mark.parametrize("thr", [0.0, 1e-6, 0.01, 0.05, 0.1, -2.0, float("inf")])
+def test_prune_every_16_bit_pattern(oracle, thr):
+    """All 65536 half and bfloat16 patterns: kept exactly where numpy's widened value
+    exceeds the threshold; NaNs (for which no comparison holds) are dropped."""
+    allbits = np.arange(65536, dtype=np.uint16)
+    with np.errstate(invalid="ignore"):
+        for dt, widen in (("f16", _f16_bits_to_f32), ("bf16", _bf16_bits_to_f32)):
+            expect = np.where(widen(allbits) > np.float32(thr), allbits, 0).astype(np.uint16)
+            assert np.array_equal(oracle.prune(allbits, dt, thr), expect)
+
+
+def test_prune_fp32_special_values(oracle):
+    f = np.array([0.0, -0.0, 1e-45, -1e-45, 0.01, 0.0100001, -0.5, np.inf, -np.inf, np.nan, 0.1, 3.0], dtype=np.float32)
+    bits = f.view(np.uint32)
+    kept0 = oracle.prune(bits, "f32", 0.0).view(np.float32)
+    assert kept0.view(np.uint32).tolist() == np.array([0, 0, 1e-45, 0, 0.01, 0.0100001, 0, np.inf, 0, 0, 0.1, 3.0], np.float32).view(np.uint32).tolist()
+    kept = oracle.prune(bits, "f32", 0.01).view(np.float32)     # strict: 0.01 itself is pruned
+    assert kept.view(np.uint32).tolist() == np.array([0, 0, 0, 0, 0, 0.0100001, 0, np.inf, 0, 0, 0.1, 3.0], np.float32).view(np.uint32).tolist()
+    assert not oracle.prune(bits, "f32", float("nan")).any()    # nothing exceeds NaN
+    everything = oracle.prune(bits, "f32", float("-inf")).view(np.uint32)
+    assert everything.tolist() == np.where(np.isnan(f) | np.isneginf(f), 0, bits).tolist()
+
+
+def test_prune_with_threshold_zero_is_relu(oracle):
+    """Section 4.3 with threshold 0 on a pre-activation tensor: pruning then Algorithm 1
+    equals Algorithm 1 on ReLU(x), and decompressing gives ReLU(x)."""
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal(50000).astype(np.float32)
+    relu = np.maximum(x, np.float32(0))
+    b1, v1, n1 = oracle.compress_pruned(x.view(np.uint32), "f32", 0.0)
+    b2, v2, n2 = oracle.compress(relu.view(np.uint32))
+    assert n1 == n2 and np.array_equal(b1, b2) and np.array_equal(v1, v2)
+    assert np.array_equal(oracle.decompress(b1, v1, x.size).view(np.float32), relu)
+    # thresholds of the paper raise the sparsity monotonically
+    kept = [oracle.compress_pruned(x.view(np.uint32), "f32", t)[2] for t in (0.0, 0.01, 0.05, 0.1)]
+    assert kept == sorted(kept, reverse=True) and kept[0] > kept[-1]
+    for t, k in zip((0.0, 0.01, 0.05, 0.1), kept):
+        assert k == int((x > np.float32(t)).sum())
