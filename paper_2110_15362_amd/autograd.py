@@ -1,0 +1,131 @@
+"""BitTrain as PyTorch autograd plumbing (the integration the paper describes in its
+implementation details and names as future work): activations saved for backward are
+kept in the bitmap format between the forward and the backward pass.
+
+Two pieces, both thin: every byte of codec work is done by libbittrain's kernels.
+
+* ``BitmapStash`` -- a ``torch.autograd.graph.saved_tensors_hooks`` context.  Packing a
+  saved activation runs ``bt_compress`` into a reusable worst-case scratch buffer, reads
+  nnz (one host synchronisation per tensor: that is the price of right-sizing) and keeps
+  only ``values[:nnz]`` and the bitmap; if that is not smaller than the dense tensor the
+  tensor is kept as it is.  Unpacking runs ``bt_decompress``.  The round trip is
+  bit-exact, so gradients are identical to those of the unhooked graph.
+* ``bitmap_relu`` -- a ReLU whose backward is served by
+  ``bt_relu_backward_from_bitmap`` and which saves nothing but the bitmap of its output
+  (1/32 of an fp32 activation): compression with a value capacity of 0.
+"""
+import torch
+
+from . import bittrain as bt
+
+_SUPPORTED = (torch.float32, torch.float16, torch.bfloat16)
+
+
+class _DeviceState:
+    """Per-device reusable buffers: workspace, worst-case value scratch, nnz scalar."""
+
+    def __init__(self, device):
+        self.device = device
+        self.ws = None
+        self.ws_elems = {}
+        self.scratch = {}
+        self.nnz = torch.zeros(1, dtype=torch.int64, device=device)
+
+    def workspace(self, n, dtype):
+        need = bt.bt_workspace_bytes(n, dtype)
+        if self.ws is None or self.ws.numel() < need:
+            self.ws = torch.empty(max(need, 1 << 16), dtype=torch.uint8, device=self.device)
+            bt.bt_workspace_init(self.ws)
+        return self.ws
+
+    def value_scratch(self, n, dtype):
+        buf = self.scratch.get(dtype)
+        if buf is None or buf.numel() < n:
+            buf = torch.empty(n, dtype=dtype, device=self.device)
+            self.scratch[dtype] = buf
+        return buf[:n]
+
+
+_states = {}
+
+
+def _state(device):
+    st = _states.get(device)
+    if st is None:
+        st = _states[device] = _DeviceState(device)
+    return st
+
+
+class _Packed:
+    __slots__ = ("bitmap", "values", "shape", "dtype", "device")
+
+    def __init__(self, bitmap, values, shape, dtype, device):
+        self.bitmap, self.values, self.shape, self.dtype, self.device = bitmap, values, shape, dtype, device
+
+
+class BitmapStash(torch.autograd.graph.saved_tensors_hooks):
+    """``with BitmapStash(): loss = model(x)`` keeps saved activations compressed.
+
+    min_numel: smaller tensors are left alone (a call costs a few microseconds).
+    ``stats`` counts dense and stored bytes of everything that went through the hooks.
+    """
+
+    def __init__(self, min_numel=4096):
+        self.min_numel = min_numel
+        self.stats = {"tensors": 0, "compressed": 0, "dense_bytes": 0, "stored_bytes": 0}
+        super().__init__(self._pack, self._unpack)
+
+    def _pack(self, t):
+        if (not t.is_cuda or t.dtype not in _SUPPORTED or t.numel() < self.min_numel or not t.is_contiguous()
+                or isinstance(t, torch.nn.Parameter)):
+            return t
+        st = _state(t.device)
+        n = t.numel()
+        self.stats["tensors"] += 1
+        self.stats["dense_bytes"] += n * t.element_size()
+        bitmap = torch.empty((n + 31) // 32, dtype=torch.int32, device=t.device)
+        scratch = st.value_scratch(n, t.dtype)
+        bt.bt_compress(t.detach(), bitmap, scratch, st.nnz, st.workspace(n, t.dtype))
+        nnz = int(st.nnz.item())                                   # host sync: needed to right-size
+        if bt.bt_compressed_size(n, nnz, t.dtype) >= n * t.element_size():
+            self.stats["stored_bytes"] += n * t.element_size()
+            return t                                               # too dense: the bitmap form would be larger
+        self.stats["compressed"] += 1
+        self.stats["stored_bytes"] += bt.bt_compressed_size(n, nnz, t.dtype)
+        return _Packed(bitmap, scratch[:nnz].clone(), t.shape, t.dtype, t.device)
+
+    def _unpack(self, obj):
+        if not isinstance(obj, _Packed):
+            return obj
+        st = _state(obj.device)
+        out = torch.empty(obj.shape, dtype=obj.dtype, device=obj.device)
+        bt.bt_decompress(obj.bitmap, obj.values, out, st.workspace(out.numel(), obj.dtype))
+        return out
+
+
+class _BitmapReLU(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x):
+        y = torch.relu(x)
+        if not (y.is_cuda and y.dtype in _SUPPORTED and y.is_contiguous()):
+            raise TypeError("bitmap_relu needs a contiguous float32/float16/bfloat16 device tensor")
+        st = _state(y.device)
+        n = y.numel()
+        bitmap = torch.empty((n + 31) // 32, dtype=torch.int32, device=y.device)
+        empty = torch.empty(0, dtype=y.dtype, device=y.device)
+        # capacity 0: only the bitmap (and nnz) are produced, no value is written
+        bt.bt_compress(y, bitmap, empty, st.nnz, st.workspace(n, y.dtype))
+        ctx.bitmap = bitmap
+        return y
+
+    @staticmethod
+    def backward(ctx, grad_out):
+        grad_out = grad_out.contiguous()
+        grad_in = torch.empty_like(grad_out)
+        bt.bt_relu_backward_from_bitmap(ctx.bitmap, grad_out, grad_in)
+        return grad_in
+
+
+def bitmap_relu(x):
+    """ReLU that keeps only the 1-bit-per-element mask of its output for backward."""
+    return _BitmapReLU.apply(x)
