@@ -51,6 +51,9 @@ typedef enum {
     BT_ERR_SIZE = 6       /* n is beyond BT_MAX_ELEMENTS */
 } bt_status;
 
+/* Largest number of tensors in one batched call. */
+#define BT_MAX_BATCH 64
+
 /* Largest n any call accepts (2^37 elements). */
 #define BT_MAX_ELEMENTS ((uint64_t)1 << 37)
 
@@ -155,6 +158,52 @@ bt_status bt_decompress(const uint32_t *d_bitmap, const void *d_values, uint64_t
 bt_status bt_relu_backward_from_bitmap(const uint32_t *d_bitmap, const void *d_grad_out,
                                        uint64_t n, bt_dtype dtype, void *d_grad_in,
                                        bt_stream stream);
+
+/* ---- many tensors in one launch ------------------------------------------------
+ *
+ * A training step stores every layer's activation (Section 3.2 applies the format
+ * to all of them; Table 1 lists a network's layers).  Compressing them one call
+ * each pays one launch and one pipeline fill-and-drain per tensor, which dominates
+ * for the small layers; the batched calls run Algorithm 1 / Algorithm 2 on all the
+ * tensors of a list in one launch per BT_MAX_BATCH tensors.  The result for each
+ * tensor is exactly what the single-tensor call gives.  The item arrays are HOST
+ * memory and are read before the call returns; the pointers inside them are device
+ * pointers with the meaning, alignment and overlap rules of the single-tensor calls.
+ * All tensors of a call share one dtype. */
+
+typedef struct {
+    const void *d_in;    /* n elements, 16-byte aligned (may be NULL when n == 0) */
+    uint64_t n;
+    uint32_t *d_bitmap;  /* ceil(n/32) words */
+    void *d_values;      /* room for values_cap elements */
+    uint64_t values_cap;
+    uint64_t *d_nnz;     /* one uint64 per tensor, 8-byte aligned, required also when n == 0 */
+} bt_compress_item;
+
+typedef struct {
+    const uint32_t *d_bitmap;
+    const void *d_values;
+    uint64_t n;
+    void *d_out;         /* n elements, 16-byte aligned */
+} bt_decompress_item;
+
+/* Workspace bytes a batched call on tensors of n[0..count) elements needs (host
+ * function; n is a host array).  Never less than bt_workspace_bytes(0, dtype); 0 for
+ * an unknown dtype or n == NULL with count != 0. */
+size_t bt_batch_workspace_bytes(const uint64_t *n, size_t count, bt_dtype dtype);
+
+/* Algorithm 1 on every tensor of items[0..count).  All items are checked before
+ * anything is launched.  d_workspace: bt_batch_workspace_bytes(...) bytes, 128-byte
+ * aligned, initialised once with bt_workspace_init; the same workspace may serve
+ * single-tensor and batched calls alike, in stream order.  count == 0 does nothing.
+ * Errors: as bt_compress (the first offending item decides). */
+bt_status bt_compress_batch(const bt_compress_item *items, size_t count, bt_dtype dtype,
+                            void *d_workspace, size_t workspace_bytes, bt_stream stream);
+
+/* Algorithm 2 on every tensor of items[0..count); otherwise as bt_compress_batch and
+ * bt_decompress. */
+bt_status bt_decompress_batch(const bt_decompress_item *items, size_t count, bt_dtype dtype,
+                              void *d_workspace, size_t workspace_bytes, bt_stream stream);
 
 #ifdef __cplusplus
 }

@@ -30,6 +30,18 @@ class BitTrainError(RuntimeError):
         super().__init__("%s failed: %s (%s)" % (call, STATUS_NAMES.get(status, status), status_str(status)))
 
 
+class CompressItem(ctypes.Structure):
+    """bt_compress_item of the C header."""
+    _fields_ = [("d_in", ctypes.c_void_p), ("n", ctypes.c_uint64), ("d_bitmap", ctypes.c_void_p),
+                ("d_values", ctypes.c_void_p), ("values_cap", ctypes.c_uint64), ("d_nnz", ctypes.c_void_p)]
+
+
+class DecompressItem(ctypes.Structure):
+    """bt_decompress_item of the C header."""
+    _fields_ = [("d_bitmap", ctypes.c_void_p), ("d_values", ctypes.c_void_p), ("n", ctypes.c_uint64),
+                ("d_out", ctypes.c_void_p)]
+
+
 def lib():
     """The loaded library; raises if it has not been built."""
     global _lib
@@ -53,6 +65,12 @@ def lib():
         L.bt_decompress.argtypes = [vp, vp, u64, ci, vp, vp, sz, vp]
         L.bt_relu_backward_from_bitmap.restype = ci
         L.bt_relu_backward_from_bitmap.argtypes = [vp, vp, u64, ci, vp, vp]
+        L.bt_batch_workspace_bytes.restype = sz
+        L.bt_batch_workspace_bytes.argtypes = [ctypes.POINTER(u64), sz, ci]
+        L.bt_compress_batch.restype = ci
+        L.bt_compress_batch.argtypes = [ctypes.POINTER(CompressItem), sz, ci, vp, sz, vp]
+        L.bt_decompress_batch.restype = ci
+        L.bt_decompress_batch.argtypes = [ctypes.POINTER(DecompressItem), sz, ci, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -171,3 +189,71 @@ def bt_relu_backward_from_bitmap(bitmap, grad_out, grad_in, stream=None):
         raise ValueError("bitmap must hold ceil(n/32) 32-bit words")
     _check("bt_relu_backward_from_bitmap", lib().bt_relu_backward_from_bitmap(
         _ptr(bitmap), _ptr(grad_out), grad_out.numel(), dtype_code(grad_out.dtype), _ptr(grad_in), _stream(stream)))
+
+
+def bt_batch_workspace_bytes(ns, dtype):
+    ns = list(ns)
+    arr = (ctypes.c_uint64 * max(len(ns), 1))(*ns)
+    return int(lib().bt_batch_workspace_bytes(arr, len(ns), dtype if isinstance(dtype, int) else dtype_code(dtype)))
+
+
+def new_batch_workspace(ns, dtype, device="cuda", stream=None):
+    """Allocate and initialise a workspace for batched calls on tensors of these sizes."""
+    ws = torch.empty(bt_batch_workspace_bytes(ns, dtype), dtype=torch.uint8, device=device)
+    bt_workspace_init(ws, stream)
+    return ws
+
+
+def _bytes(t):
+    return t.numel() * t.element_size()
+
+
+def compress_items(xs, bitmaps, values, nnz):
+    """The host item array of bt_compress_batch for lists of device tensors; nnz is one
+    int64 tensor with an entry per tensor.  Build it once and reuse it while the buffers live."""
+    if not (len(xs) == len(bitmaps) == len(values)) or nnz.numel() < len(xs) or nnz.element_size() != 8:
+        raise ValueError("one bitmap, one value buffer and one 64-bit nnz entry per tensor")
+    _dev(nnz, "nnz")
+    items = (CompressItem * max(len(xs), 1))()
+    for i, (x, b, v) in enumerate(zip(xs, bitmaps, values)):
+        for t, name in ((x, "x"), (b, "bitmap"), (v, "values")):
+            _dev(t, name)
+        if v.dtype != x.dtype or x.dtype != xs[0].dtype:
+            raise TypeError("all tensors and value buffers of a batch share one dtype")
+        if b.element_size() != 4 or _bytes(b) < bt_bitmap_bytes(x.numel()):
+            raise ValueError("bitmap %d must hold ceil(n/32) 32-bit words" % i)
+        items[i] = CompressItem(x.data_ptr(), x.numel(), b.data_ptr(), v.data_ptr(), v.numel(),
+                                nnz.data_ptr() + 8 * i)
+    return items
+
+
+def decompress_items(bitmaps, values, outs):
+    """The host item array of bt_decompress_batch for lists of device tensors."""
+    if not (len(outs) == len(bitmaps) == len(values)):
+        raise ValueError("one bitmap and one value buffer per tensor")
+    items = (DecompressItem * max(len(outs), 1))()
+    for i, (b, v, o) in enumerate(zip(bitmaps, values, outs)):
+        for t, name in ((b, "bitmap"), (v, "values"), (o, "out")):
+            _dev(t, name)
+        if v.dtype != o.dtype or o.dtype != outs[0].dtype:
+            raise TypeError("all tensors and value buffers of a batch share one dtype")
+        if b.element_size() != 4 or _bytes(b) < bt_bitmap_bytes(o.numel()):
+            raise ValueError("bitmap %d must hold ceil(n/32) 32-bit words" % i)
+        items[i] = DecompressItem(b.data_ptr(), v.data_ptr(), o.numel(), o.data_ptr())
+    return items
+
+
+def bt_compress_batch(items, count, dtype, workspace, stream=None):
+    """Algorithm 1 on every tensor of `items` (from compress_items) in one launch per 64 tensors."""
+    _dev(workspace, "workspace")
+    _check("bt_compress_batch", lib().bt_compress_batch(
+        items, count, dtype if isinstance(dtype, int) else dtype_code(dtype), _ptr(workspace), _bytes(workspace),
+        _stream(stream)))
+
+
+def bt_decompress_batch(items, count, dtype, workspace, stream=None):
+    """Algorithm 2 on every tensor of `items` (from decompress_items)."""
+    _dev(workspace, "workspace")
+    _check("bt_decompress_batch", lib().bt_decompress_batch(
+        items, count, dtype if isinstance(dtype, int) else dtype_code(dtype), _ptr(workspace), _bytes(workspace),
+        _stream(stream)))

@@ -306,29 +306,43 @@ template <int SLEEP> __device__ __forceinline__ bool spin_expired(uint32_t *hdr,
 // w0 + 64*j + l, so every load and store of a row is one contiguous run.  The pass
 // takes the leading run of published counts, turns it into prefixes (a wave prefix
 // sum per row, carried from row to row), writes them, and moves the frontier.
-// When all counts are in it writes the grand total (nnz) and advances the header
-// for the next call: by then every tile has published its count, hence has read
-// the header.
+// When a tensor's counts are all in it writes the tensor's total (nnz); at the end it
+// advances the header for the next call.
 #ifndef BT_SCAN_ROWS
 #define BT_SCAN_ROWS 8
 #endif
 constexpr int kScanRows = BT_SCAN_ROWS;
-__device__ __forceinline__ void scan_counts(char *ws, const uint32_t n_tiles, uint64_t *nnz_out) {
+// What the scanner has to know about the tensors of one call.  A call on one tensor
+// has one segment, slots == tiles.  A batched call lays its tensors end to end in
+// the slot (= workspace entry) numbering, each starting at a multiple of 64 slots, so
+// that a scanner row never spans two tensors; the slots between a tensor's last tile
+// and the next tensor's first slot belong to no tile, and their workgroups publish a
+// count of zero.  Prefixes restart at 0 with every tensor, and each tensor's total
+// goes to its nnz.
+struct Segments {
+    uint32_t count;           // tensors
+    const uint32_t *start;    // count + 1 entries: first slot of tensor i; start[count] = slots of the call
+    uint64_t *const *nnz;     // where tensor i's number of stored values goes; the array or an entry may be null
+};
+
+__device__ __forceinline__ void scan_counts(char *ws, const Segments seg) {
     const uint32_t lane = threadIdx.x & (kWaveSize - 1);
     uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
     const uint32_t seq = hdr[kHdrSeq];
     const uint32_t cur = seq & 1u;
-    uint32_t frontier = 0;     // tiles [0, frontier) have their prefix
-    uint64_t running = 0;      // non-zeros in tiles [0, frontier)
+    const uint32_t n_slots = seg.start[seg.count];
+    uint32_t frontier = 0;     // slots [0, frontier) are done
+    uint32_t item = 0;         // tensor that slot `frontier` belongs to
+    uint64_t running = 0;      // stored values of tensor `item` in its tiles before `frontier`
     uint32_t spins = 0;
-    while (frontier < n_tiles) {
+    while (frontier < n_slots) {
         const uint32_t w0 = frontier & ~63u;
         uint32_t c[kScanRows];
 #pragma unroll
         for (int j = 0; j < kScanRows; ++j) {
             const uint32_t t = w0 + 64u * j + lane;
             c[j] = 0;
-            if (t < n_tiles)
+            if (t < n_slots)
                 c[j] = __hip_atomic_load(reinterpret_cast<const uint32_t *>(ws_count(ws, t, cur)), __ATOMIC_RELAXED,
                                          __HIP_MEMORY_SCOPE_AGENT);
         }
@@ -339,26 +353,30 @@ __device__ __forceinline__ void scan_counts(char *ws, const uint32_t n_tiles, ui
 #pragma unroll
         for (int j = 0; j < kScanRows; ++j) {
             const uint32_t t = w0 + 64u * j + lane;
-            usable_lanes[j] = __ballot(t < frontier || (t < n_tiles && c[j] != 0));   // done before, or published
+            usable_lanes[j] = __ballot(t < frontier || (t < n_slots && c[j] != 0));   // done before, or published
         }
-        // rows are consumed in order while every tile of the row is usable
+        // rows are consumed in order while every slot of the row is usable
         bool open = true;
         uint32_t new_frontier = frontier;
 #pragma unroll
         for (int j = 0; j < kScanRows; ++j) {
             const uint32_t row0 = w0 + 64u * j;
             const uint32_t t = row0 + lane;
-            if (open && row0 < n_tiles) {
+            if (open && row0 < n_slots) {
                 const uint64_t bad = ~usable_lanes[j];                             // lanes that stop the run
                 const uint32_t run = bad == 0 ? 64u : (uint32_t)__ffsll((unsigned long long)bad) - 1u;
-                const uint32_t row_end = row0 + run;                               // tiles [row0, row_end) usable
+                const uint32_t row_end = row0 + run;                               // slots [row0, row_end) usable
                 if (row_end > new_frontier) {
+                    while (item + 1 < seg.count && row0 >= seg.start[item + 1]) ++item;
+                    if (row0 == seg.start[item] && new_frontier <= row0) running = 0;   // a new tensor begins
                     const bool fresh = t >= frontier && t < row_end;
                     const uint32_t mine = fresh ? c[j] - 1u : 0u;
                     const uint32_t incl = wave_inclusive_sum(mine);
                     if (fresh) ws_store64(ws_prefix(ws, t, cur), running + (incl - mine) + 1);
                     running += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
                     new_frontier = row_end;
+                    if (row_end == seg.start[item + 1] && lane == 0 && seg.nnz != nullptr && seg.nnz[item] != nullptr)
+                        *seg.nnz[item] = running;                                  // length(B.values) of this tensor
                 }
                 open = run == 64u;
             }
@@ -370,8 +388,8 @@ __device__ __forceinline__ void scan_counts(char *ws, const uint32_t n_tiles, ui
         frontier = new_frontier;
     }
     if (lane == 0) {
-        if (nnz_out != nullptr) *nnz_out = running;           // length(B.values)
-        __hip_atomic_store(&hdr[kHdrPrevTiles], n_tiles, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // every tile has published its count by now, hence has read the header: advance it
+        __hip_atomic_store(&hdr[kHdrPrevTiles], n_slots, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(&hdr[kHdrSeq], seq + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
@@ -381,35 +399,63 @@ struct PrefixShared {
     uint64_t tile_prefix;
 };
 
-// Run by every thread of a tile's block: publishes the tile's count, waits for the
-// scanner's answer, and returns the number of non-zeros before this wave's part
-// of the tile (wave-uniform).  Contains two block barriers.
-__device__ __forceinline__ uint64_t tile_prefix(char *ws, PrefixShared &sh, const uint32_t tile,
-                                                const uint32_t n_tiles, const uint32_t wave_total) {
+// What a workgroup reads from the header before it publishes anything.  The scanner
+// rewrites the header once every slot of the call has published, so a workgroup must
+// not read it after its own publication.
+struct Epoch {
+    uint32_t cur;          // copy of the entries this call uses
+    uint32_t prev_slots;   // entries the previous call used in the other copy
+};
+
+__device__ __forceinline__ Epoch read_epoch(const char *ws) {
+    const uint32_t *hdr = reinterpret_cast<const uint32_t *>(ws);
+    return Epoch{hdr[kHdrSeq] & 1u, hdr[kHdrPrevTiles]};
+}
+
+// Zero what the previous call left in the other copy of the workspace entries: slots
+// [0, prev_slots), shared out over the threads of all slots of this call.
+__device__ __forceinline__ void zero_previous(char *ws, const Epoch ep, const uint32_t slot, const uint32_t n_slots) {
+    const uint32_t other = ep.cur ^ 1u;
+    for (uint32_t i = slot + (uint32_t)threadIdx.x * n_slots; i < ep.prev_slots; i += kBlock * n_slots) {
+        ws_store32(ws_count(ws, i, other), 0);
+        ws_store64(ws_prefix(ws, i, other), 0);
+    }
+}
+
+// A slot of a batched call that belongs to no tile: it publishes an empty count, so
+// that the scanner knows its workgroup has read the header, and does its share of
+// the clean-up.
+__device__ __forceinline__ void idle_slot(char *ws, const uint32_t slot, const uint32_t n_slots) {
+    const Epoch ep = read_epoch(ws);
+    __syncthreads();       // every thread has read the header
+    if (threadIdx.x == 0) ws_store32(ws_count(ws, slot, ep.cur), 1);
+    zero_previous(ws, ep, slot, n_slots);
+}
+
+// Run by every thread of a tile's block: publishes the tile's count in its slot, waits
+// for the scanner's answer, and returns the number of stored values of this tensor
+// before this wave's part of the tile (wave-uniform).  Contains two block barriers.
+__device__ __forceinline__ uint64_t tile_prefix(char *ws, PrefixShared &sh, const uint32_t slot,
+                                                const uint32_t n_slots, const uint32_t wave_total) {
     const int tid = threadIdx.x;
     const uint32_t lane = tid & (kWaveSize - 1), wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);
     uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
-    // written at the end of the previous call; constant until every tile of this call has published
-    const uint32_t seq = hdr[kHdrSeq];
-    const uint32_t prev_tiles = hdr[kHdrPrevTiles];
-    const uint32_t cur = seq & 1u, other = cur ^ 1u;
+    // written at the end of the previous call; constant until every slot of this call has published
+    const Epoch ep = read_epoch(ws);
+    const uint32_t cur = ep.cur;
 
     if (lane == 0) sh.wave_total[wave] = wave_total;
     __syncthreads();
     if (tid == 0) {
         const uint32_t tile_total = sh.wave_total[0] + sh.wave_total[1] + sh.wave_total[2] + sh.wave_total[3];
-        ws_store32(ws_count(ws, tile, cur), tile_total + 1);
+        ws_store32(ws_count(ws, slot, cur), tile_total + 1);
     }
-    // zero what the previous call left in the other copy: entries [0, prev_tiles)
-    for (uint32_t i = tile + (uint32_t)tid * n_tiles; i < prev_tiles; i += kBlock * n_tiles) {
-        ws_store32(ws_count(ws, i, other), 0);
-        ws_store64(ws_prefix(ws, i, other), 0);
-    }
+    zero_previous(ws, ep, slot, n_slots);
     if (tid == 0) {
         uint64_t v;
         uint32_t spins = 0;
         for (;;) {
-            v = ws_load64(ws_prefix(ws, tile, cur));
+            v = ws_load64(ws_prefix(ws, slot, cur));
             if (v != 0) break;
             if (spin_expired<kTileSleep>(hdr, spins)) { v = 1; break; }
         }
@@ -529,24 +575,19 @@ __device__ __forceinline__ void strip_commit(unsigned char *strip, const uint32_
 
 // ---- Algorithm 1: dense -> bitmap -------------------------------------------------------
 
+// One tile of one tensor: `tile` counts the tensor's own tiles (it addresses the data),
+// `slot` is the tile's entry in the workspace (equal to `tile` unless the call is batched).
 template <int S, int KEEP>
-__global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restrict__ in, const uint64_t n,
-                                                          uint32_t *__restrict__ bitmap, void *__restrict__ values,
-                                                          const uint64_t values_cap, uint64_t *__restrict__ nnz_out,
-                                                          char *ws, const uint32_t n_tiles, const float threshold) {
+__device__ __forceinline__ void compress_tile(const void *__restrict__ in, const uint64_t n,
+                                              uint32_t *__restrict__ bitmap, void *__restrict__ values,
+                                              const uint64_t values_cap, char *ws, const uint32_t tile,
+                                              const uint32_t slot, const uint32_t n_slots, const float threshold,
+                                              unsigned char *s_stage, PrefixShared &s_prefix) {
     using G = Geo<S>;
     constexpr int E = G::E;
-    __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * G::LDS_WAVE];
-    __shared__ PrefixShared s_prefix;
-
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in a scalar register
-    if (blockIdx.x == 0) {                   // workgroup 0 is the scanner
-        if (wave == 0) scan_counts(ws, n_tiles, nnz_out);
-        return;
-    }
-    const uint32_t tile = blockIdx.x - 1;
 
     const uint64_t n_words = (n + 31) >> 5;
     const uint64_t wave_e0 = (uint64_t)tile * G::TILE + (uint64_t)wave * G::WAVE;
@@ -618,7 +659,7 @@ __global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restr
     }
 
     // (4) block total -> count for the scanner -> this wave's position in B.values
-    uint64_t g0 = tile_prefix(ws, s_prefix, tile, n_tiles, wave_total);   // index in B.values of this wave's next value
+    uint64_t g0 = tile_prefix(ws, s_prefix, slot, n_slots, wave_total);   // index in B.values of this wave's next value
     {
         const int g = lane / G::G, i = lane % G::G;
 #pragma unroll
@@ -670,25 +711,87 @@ __global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restr
     }
 }
 
-// ---- Algorithm 2: bitmap -> dense ---------------------------------------------------------
-
-template <int S>
-__global__ __launch_bounds__(kBlock) void decompress_kernel(const uint32_t *__restrict__ bitmap,
-                                                            const void *__restrict__ values, const uint64_t n,
-                                                            void *__restrict__ out, char *ws, const uint32_t n_tiles) {
-    using G = Geo<S>;
-    constexpr int E = G::E;
-    __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * G::LDS_WAVE];
+// bt_compress / bt_compress_pruned: one tensor.  Workgroup 0 is the scanner, workgroup
+// t + 1 is tile t.
+template <int S, int KEEP>
+__global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restrict__ in, const uint64_t n,
+                                                          uint32_t *__restrict__ bitmap, void *__restrict__ values,
+                                                          const uint64_t values_cap, uint64_t *__restrict__ nnz_out,
+                                                          char *ws, const uint32_t n_tiles, const float threshold) {
+    __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
     __shared__ PrefixShared s_prefix;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWaveSize - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in a scalar register
-    if (blockIdx.x == 0) {                   // workgroup 0 is the scanner
-        if (wave == 0) scan_counts(ws, n_tiles, nullptr);
+    if (blockIdx.x == 0) {
+        if (threadIdx.x < kWaveSize) {
+            const uint32_t start[2] = {0, n_tiles};
+            uint64_t *const nnz[1] = {nnz_out};
+            scan_counts(ws, Segments{1, start, nnz});
+        }
         return;
     }
     const uint32_t tile = blockIdx.x - 1;
+    compress_tile<S, KEEP>(in, n, bitmap, values, values_cap, ws, tile, tile, n_tiles, threshold, s_stage, s_prefix);
+}
+
+// Several tensors in one launch (bt_compress_batch): the kernel arguments carry the
+// per-tensor pointers; a workgroup finds its tensor by binary search over the slot
+// starts.  Slots that belong to no tile only do their share of the workspace clean-up.
+constexpr int kMaxBatch = BT_MAX_BATCH;
+struct BatchLayout {
+    uint32_t count;
+    uint32_t start[kMaxBatch + 1];
+    uint32_t tiles[kMaxBatch];
+};
+struct CompressBatch {
+    BatchLayout lay;
+    const void *in[kMaxBatch];
+    uint32_t *bitmap[kMaxBatch];
+    void *values[kMaxBatch];
+    uint64_t cap[kMaxBatch];
+    uint64_t *nnz[kMaxBatch];
+    uint64_t n[kMaxBatch];
+};
+
+__device__ __forceinline__ uint32_t batch_item_of(const BatchLayout &lay, const uint32_t slot) {
+    uint32_t lo = 0, hi = lay.count;          // start[lo] <= slot < start[hi]
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (slot >= lay.start[mid]) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+template <int S>
+__global__ __launch_bounds__(kBlock, 8) void compress_batch_kernel(const CompressBatch b, char *ws) {
+    __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
+    __shared__ PrefixShared s_prefix;
+    const uint32_t n_slots = b.lay.start[b.lay.count];
+    if (blockIdx.x == 0) {
+        if (threadIdx.x < kWaveSize) scan_counts(ws, Segments{b.lay.count, b.lay.start, b.nnz});
+        return;
+    }
+    const uint32_t slot = blockIdx.x - 1;
+    const uint32_t i = batch_item_of(b.lay, slot);
+    const uint32_t tile = slot - b.lay.start[i];
+    if (tile >= b.lay.tiles[i]) {
+        idle_slot(ws, slot, n_slots);
+        return;
+    }
+    compress_tile<S, kKeepNonZero>(b.in[i], b.n[i], b.bitmap[i], b.values[i], b.cap[i], ws, tile, slot, n_slots, 0.0f,
+                                   s_stage, s_prefix);
+}
+
+// ---- Algorithm 2: bitmap -> dense ---------------------------------------------------------
+
+template <int S>
+__device__ __forceinline__ void decompress_tile(const uint32_t *__restrict__ bitmap, const void *__restrict__ values,
+                                                const uint64_t n, void *__restrict__ out, char *ws,
+                                                const uint32_t tile, const uint32_t slot, const uint32_t n_slots,
+                                                unsigned char *s_stage, PrefixShared &s_prefix) {
+    using G = Geo<S>;
+    constexpr int E = G::E;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWaveSize - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in a scalar register
 
     const uint64_t n_words = (n + 31) >> 5;
     const uint64_t wave_e0 = (uint64_t)tile * G::TILE + (uint64_t)wave * G::WAVE;
@@ -707,7 +810,7 @@ __global__ __launch_bounds__(kBlock) void decompress_kernel(const uint32_t *__re
     for (int k = 0; k < kRows; ++k) wave_total += BT_FIELD(total2, k);
 
     // (2) block total -> count for the scanner -> this wave's value of j
-    uint64_t g0 = tile_prefix(ws, s_prefix, tile, n_tiles, wave_total);   // Algorithm 2's j for this wave
+    uint64_t g0 = tile_prefix(ws, s_prefix, slot, n_slots, wave_total);   // Algorithm 2's j for this wave
 
     // (3) Ask for the values of every phase (kPhaseRows rows each) first, so that all of
     //     them are in flight together; then, phase by phase, put them into the LDS strip
@@ -763,6 +866,50 @@ __global__ __launch_bounds__(kBlock) void decompress_kernel(const uint32_t *__re
             row_start += BT_FIELD(total2, k);
         }
     }
+}
+
+template <int S>
+__global__ __launch_bounds__(kBlock) void decompress_kernel(const uint32_t *__restrict__ bitmap,
+                                                            const void *__restrict__ values, const uint64_t n,
+                                                            void *__restrict__ out, char *ws, const uint32_t n_tiles) {
+    __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
+    __shared__ PrefixShared s_prefix;
+    if (blockIdx.x == 0) {
+        if (threadIdx.x < kWaveSize) {
+            const uint32_t start[2] = {0, n_tiles};
+            scan_counts(ws, Segments{1, start, nullptr});
+        }
+        return;
+    }
+    const uint32_t tile = blockIdx.x - 1;
+    decompress_tile<S>(bitmap, values, n, out, ws, tile, tile, n_tiles, s_stage, s_prefix);
+}
+
+struct DecompressBatch {
+    BatchLayout lay;
+    const uint32_t *bitmap[kMaxBatch];
+    const void *values[kMaxBatch];
+    void *out[kMaxBatch];
+    uint64_t n[kMaxBatch];
+};
+
+template <int S>
+__global__ __launch_bounds__(kBlock) void decompress_batch_kernel(const DecompressBatch b, char *ws) {
+    __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
+    __shared__ PrefixShared s_prefix;
+    const uint32_t n_slots = b.lay.start[b.lay.count];
+    if (blockIdx.x == 0) {
+        if (threadIdx.x < kWaveSize) scan_counts(ws, Segments{b.lay.count, b.lay.start, nullptr});
+        return;
+    }
+    const uint32_t slot = blockIdx.x - 1;
+    const uint32_t i = batch_item_of(b.lay, slot);
+    const uint32_t tile = slot - b.lay.start[i];
+    if (tile >= b.lay.tiles[i]) {
+        idle_slot(ws, slot, n_slots);
+        return;
+    }
+    decompress_tile<S>(b.bitmap[i], b.values[i], b.n[i], b.out[i], ws, tile, slot, n_slots, s_stage, s_prefix);
 }
 
 // ---- ReLU backward from the bitmap -----------------------------------------------------------
@@ -861,6 +1008,57 @@ bt_status check_common(uint64_t n, bt_dtype dt, const void *d_ws, size_t ws_byte
     return BT_OK;
 }
 
+// Slots a tensor of n elements takes in a batched launch: its tiles rounded up to whole
+// scanner rows; an empty tensor still takes one row, so that the scanner writes its nnz.
+uint64_t batch_slots_for(uint64_t n, int s) {
+    const uint64_t tiles = tiles_for(n, s);
+    return ((tiles == 0 ? 1 : tiles) + kWaveSize - 1) / kWaveSize * kWaveSize;
+}
+
+size_t workspace_bytes_for_slots(uint64_t slots) {
+    uint64_t records = (slots + kTilesPerRecord - 1) / kTilesPerRecord;
+    if (records == 0) records = 1;
+    return kHeaderBytes + (size_t)records * kRecordBytes;
+}
+
+// Tensors [first, first + lay.count) of a batch, laid end to end.  `n_of(i)` is tensor i's element count.
+template <class NOf>
+void lay_out(BatchLayout &lay, size_t first, size_t count, int s, NOf n_of) {
+    lay.count = (uint32_t)count;
+    uint64_t at = 0;
+    for (size_t i = 0; i < count; ++i) {
+        const uint64_t n = n_of(first + i);
+        lay.start[i] = (uint32_t)at;
+        lay.tiles[i] = (uint32_t)tiles_for(n, s);
+        at += batch_slots_for(n, s);
+    }
+    for (size_t i = count; i <= (size_t)kMaxBatch; ++i) lay.start[i] = (uint32_t)at;
+    for (size_t i = count; i < (size_t)kMaxBatch; ++i) lay.tiles[i] = 0;
+}
+
+// Largest workspace any launch of the batch needs (a batch of more than kMaxBatch
+// tensors is cut into consecutive launches of kMaxBatch, which reuse the workspace).
+template <class NOf>
+size_t batch_workspace_bytes(size_t count, int s, NOf n_of) {
+    size_t need = workspace_bytes_for_slots(0);
+    for (size_t first = 0; first < count; first += kMaxBatch) {
+        const size_t c = count - first < (size_t)kMaxBatch ? count - first : (size_t)kMaxBatch;
+        uint64_t slots = 0;
+        for (size_t i = 0; i < c; ++i) slots += batch_slots_for(n_of(first + i), s);
+        const size_t b = workspace_bytes_for_slots(slots);
+        if (b > need) need = b;
+    }
+    return need;
+}
+
+bt_status check_batch_common(const void *items, size_t count, bt_dtype dt, const void *d_ws) {
+    if (elem_size(dt) == 0) return BT_ERR_DTYPE;
+    if (count == 0) return BT_OK;
+    if (items == nullptr || d_ws == nullptr) return BT_ERR_NULL;
+    if (misaligned(d_ws, 128)) return BT_ERR_ALIGN;
+    return BT_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -878,9 +1076,7 @@ size_t bt_compressed_size(uint64_t n, uint64_t nnz, bt_dtype dtype) {
 size_t bt_workspace_bytes(uint64_t n, bt_dtype dtype) {
     const int s = elem_size(dtype);
     if (s == 0) return 0;
-    uint64_t records = (tiles_for(n, s) + kTilesPerRecord - 1) / kTilesPerRecord;
-    if (records == 0) records = 1;
-    return kHeaderBytes + (size_t)records * kRecordBytes;
+    return workspace_bytes_for_slots(tiles_for(n, s));
 }
 
 const char *bt_status_str(bt_status status) {
@@ -990,6 +1186,93 @@ bt_status bt_relu_backward_from_bitmap(const uint32_t *d_bitmap, const void *d_g
     else
         relu_backward_kernel<2><<<dim3(blocks), dim3(kBlock), 0, hs>>>(d_bitmap, d_grad_out, n, d_grad_in);
     return launched();
+}
+
+size_t bt_batch_workspace_bytes(const uint64_t *n, size_t count, bt_dtype dtype) {
+    const int s = elem_size(dtype);
+    if (s == 0 || (n == nullptr && count != 0)) return 0;
+    return batch_workspace_bytes(count, s, [n](size_t i) { return n[i] > BT_MAX_ELEMENTS ? BT_MAX_ELEMENTS : n[i]; });
+}
+
+bt_status bt_compress_batch(const bt_compress_item *items, size_t count, bt_dtype dtype, void *d_workspace,
+                            size_t workspace_bytes, bt_stream stream) {
+    const bt_status st = check_batch_common(items, count, dtype, d_workspace);
+    if (st != BT_OK || count == 0) return st;
+    const int s = elem_size(dtype);
+    for (size_t i = 0; i < count; ++i) {
+        const bt_compress_item &it = items[i];
+        if (it.n > BT_MAX_ELEMENTS) return BT_ERR_SIZE;
+        if (it.d_nnz == nullptr) return BT_ERR_NULL;
+        if (misaligned(it.d_nnz, 8)) return BT_ERR_ALIGN;
+        if (it.n == 0) continue;
+        if (it.d_in == nullptr || it.d_bitmap == nullptr) return BT_ERR_NULL;
+        if (it.d_values == nullptr && it.values_cap != 0) return BT_ERR_NULL;
+        if (misaligned(it.d_in, 16) || misaligned(it.d_bitmap, 4) || misaligned(it.d_values, (size_t)s))
+            return BT_ERR_ALIGN;
+    }
+    const auto n_of = [items](size_t i) { return items[i].n; };
+    if (workspace_bytes < batch_workspace_bytes(count, s, n_of)) return BT_ERR_WORKSPACE;
+
+    hipStream_t hs = (hipStream_t)stream;
+    char *ws = static_cast<char *>(d_workspace);
+    for (size_t first = 0; first < count; first += kMaxBatch) {
+        const size_t c = count - first < (size_t)kMaxBatch ? count - first : (size_t)kMaxBatch;
+        CompressBatch b;
+        lay_out(b.lay, first, c, s, n_of);
+        for (size_t i = 0; i < (size_t)kMaxBatch; ++i) {
+            const bt_compress_item it = i < c ? items[first + i] : bt_compress_item{nullptr, 0, nullptr, nullptr, 0, nullptr};
+            b.in[i] = it.d_in;
+            b.n[i] = it.n;
+            b.bitmap[i] = it.d_bitmap;
+            b.values[i] = it.d_values;
+            b.cap[i] = it.values_cap;
+            b.nnz[i] = it.d_nnz;
+        }
+        const dim3 grid(b.lay.start[c] + 1), block(kBlock);
+        if (s == 4) compress_batch_kernel<4><<<grid, block, 0, hs>>>(b, ws);
+        else compress_batch_kernel<2><<<grid, block, 0, hs>>>(b, ws);
+        const bt_status ls = launched();
+        if (ls != BT_OK) return ls;
+    }
+    return BT_OK;
+}
+
+bt_status bt_decompress_batch(const bt_decompress_item *items, size_t count, bt_dtype dtype, void *d_workspace,
+                              size_t workspace_bytes, bt_stream stream) {
+    const bt_status st = check_batch_common(items, count, dtype, d_workspace);
+    if (st != BT_OK || count == 0) return st;
+    const int s = elem_size(dtype);
+    for (size_t i = 0; i < count; ++i) {
+        const bt_decompress_item &it = items[i];
+        if (it.n > BT_MAX_ELEMENTS) return BT_ERR_SIZE;
+        if (it.n == 0) continue;
+        if (it.d_bitmap == nullptr || it.d_out == nullptr) return BT_ERR_NULL;   // d_values may be NULL when nnz == 0
+        if (misaligned(it.d_out, 16) || misaligned(it.d_bitmap, 4) || misaligned(it.d_values, (size_t)s))
+            return BT_ERR_ALIGN;
+    }
+    const auto n_of = [items](size_t i) { return items[i].n; };
+    if (workspace_bytes < batch_workspace_bytes(count, s, n_of)) return BT_ERR_WORKSPACE;
+
+    hipStream_t hs = (hipStream_t)stream;
+    char *ws = static_cast<char *>(d_workspace);
+    for (size_t first = 0; first < count; first += kMaxBatch) {
+        const size_t c = count - first < (size_t)kMaxBatch ? count - first : (size_t)kMaxBatch;
+        DecompressBatch b;
+        lay_out(b.lay, first, c, s, n_of);
+        for (size_t i = 0; i < (size_t)kMaxBatch; ++i) {
+            const bt_decompress_item it = i < c ? items[first + i] : bt_decompress_item{nullptr, nullptr, 0, nullptr};
+            b.bitmap[i] = it.d_bitmap;
+            b.values[i] = it.d_values;
+            b.n[i] = it.n;
+            b.out[i] = it.d_out;
+        }
+        const dim3 grid(b.lay.start[c] + 1), block(kBlock);
+        if (s == 4) decompress_batch_kernel<4><<<grid, block, 0, hs>>>(b, ws);
+        else decompress_batch_kernel<2><<<grid, block, 0, hs>>>(b, ws);
+        const bt_status ls = launched();
+        if (ls != BT_OK) return ls;
+    }
+    return BT_OK;
 }
 
 }  // extern "C"

@@ -29,7 +29,7 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported(bt):
     names = _declared_functions()
     assert {"bt_compress", "bt_compressed_size", "bt_decompress", "bt_relu_backward_from_bitmap",
-            "bt_compress_pruned"} <= set(names)
+            "bt_compress_pruned", "bt_compress_batch", "bt_decompress_batch", "bt_batch_workspace_bytes"} <= set(names)
     raw = ctypes.CDLL(bt.LIB_PATH)
     for name in names:
         assert hasattr(raw, name), name
@@ -115,6 +115,73 @@ def test_argument_errors_are_found_on_the_host(bt):
     assert relu(n=0, bm=None, g=None, gi=None) == 0
     assert L.bt_workspace_init(None, 100, None) == 1
     assert L.bt_workspace_init(A + 1, 100, None) == 3
+
+
+def test_batch_workspace_bytes_and_host_errors(bt):
+    L = bt.lib()
+    f32, f16 = bt.BT_F32, bt.BT_F16
+    tile = {f32: 8192, f16: 16384}
+
+    def expect(ns, code):
+        # every tensor takes its tiles rounded up to whole rows of 64 slots (at least one row);
+        # 24 bytes per slot in records of 32 slots, plus the 256-byte header; launches of 64 tensors
+        need = 256 + 768
+        for first in range(0, len(ns), 64):
+            slots = sum(max(1, -(-(-(-n // tile[code])) // 64)) * 64 for n in ns[first:first + 64])
+            need = max(need, 256 + 768 * -(-slots // 32))
+        return need
+
+    for code in (f32, f16):
+        t = tile[code]
+        for ns in ([], [0], [1], [t], [64 * t], [64 * t + 1], [5, 0, 200 * t, 3 * t + 1],
+                   [t + 1] * 64, [t + 1] * 65, [1] * 130 + [1000 * t]):
+            assert bt.bt_batch_workspace_bytes(ns, code) == expect(ns, code), (code, ns)
+        # a batch of one tensor never needs less than the single-tensor call
+        for n in (1, t, 63 * t, 64 * t + 1, 25690112):
+            assert bt.bt_batch_workspace_bytes([n], code) >= bt.bt_workspace_bytes(n, code)
+    assert bt.bt_batch_workspace_bytes([10], 9) == 0
+    assert L.bt_batch_workspace_bytes(None, 3, f32) == 0
+
+    A = 0x10000
+
+    def c_items(**kw):
+        a = dict(d_in=A, n=1000, d_bitmap=A, d_values=A, values_cap=1000, d_nnz=A)
+        a.update(kw)
+        good = bt.CompressItem(A, 1000, A, A, 1000, A)
+        return (bt.CompressItem * 3)(good, bt.CompressItem(a["d_in"], a["n"], a["d_bitmap"], a["d_values"],
+                                                            a["values_cap"], a["d_nnz"]), good)
+
+    wsb = bt.bt_batch_workspace_bytes([1000] * 3, f32)
+
+    def compress(items=None, count=3, dt=f32, ws=A, wsb=wsb, **kw):
+        return L.bt_compress_batch(c_items(**kw) if items is None else items, count, dt, ws, wsb, None)
+
+    assert compress(dt=5) == 2
+    assert compress(ws=None) == 1
+    assert compress(ws=A + 64) == 3
+    assert compress(d_in=None) == 1 and compress(d_bitmap=None) == 1 and compress(d_nnz=None) == 1
+    assert compress(d_values=None) == 1
+    assert compress(d_in=A + 8) == 3 and compress(d_values=A + 2) == 3 and compress(d_nnz=A + 4) == 3
+    assert compress(n=(1 << 37) + 1) == 6
+    assert compress(wsb=wsb - 1) == 4
+    assert compress(n=0, d_nnz=None) == 1             # an empty tensor still reports its nnz
+    assert L.bt_compress_batch(None, 3, f32, A, wsb, None) == 1
+    assert L.bt_compress_batch(None, 0, f32, None, 0, None) == 0     # nothing to do
+
+    def d_items(bm=A, val=A, n=1000, out=A):
+        good = bt.DecompressItem(A, A, 1000, A)
+        return (bt.DecompressItem * 3)(good, good, bt.DecompressItem(bm, val, n, out))
+
+    def decompress(count=3, dt=f32, ws=A, wsb=wsb, **kw):
+        return L.bt_decompress_batch(d_items(**kw), count, dt, ws, wsb, None)
+
+    assert decompress(dt=-1) == 2
+    assert decompress(ws=None) == 1 and decompress(ws=A + 32) == 3
+    assert decompress(bm=None) == 1 and decompress(out=None) == 1
+    assert decompress(out=A + 4) == 3 and decompress(val=A + 1) == 3 and decompress(bm=A + 2) == 3
+    assert decompress(n=(1 << 37) + 1) == 6
+    assert decompress(wsb=wsb - 1) == 4
+    assert L.bt_decompress_batch(None, 0, f32, None, 0, None) == 0
 
 
 def test_bench_refuses_more_than_one_gpu():

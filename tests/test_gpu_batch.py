@@ -1,0 +1,215 @@
+"""GPU parity of the batched calls (many tensors per launch) against the CPU oracle,
+byte for byte and tensor by tensor: a batched call must give for every tensor exactly
+what Algorithm 1 / Algorithm 2 give for it alone."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2110_15362_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+SENT = 0x5A
+TILE = {4: 8192, 2: 16384}
+
+
+@pytest.fixture(scope="module")
+def bt():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (they never fall back to the CPU)")
+    import paper_2110_15362_amd.bittrain as b
+    b.lib()
+    return b
+
+
+def _sentinel(numel, dtype):
+    t = torch.empty(numel, dtype=dtype, device="cuda")
+    t.view(torch.uint8).fill_(SENT)
+    return t
+
+
+def _sent_of(a):
+    return np.frombuffer(bytes([SENT] * a.itemsize), dtype=a.dtype)[0]
+
+
+def _compress_batch(bt, xs, ws, caps=None):
+    """Runs bt_compress_batch on CPU tensors xs; returns per tensor (bitmap, values, nnz) and
+    asserts that nothing outside bitmap[0,W) / values[0,min(nnz,cap)) was written."""
+    dt = xs[0].dtype
+    caps = [x.numel() for x in xs] if caps is None else caps
+    xd = [x.cuda() for x in xs]
+    bms = [_sentinel((x.numel() + 31) // 32 + 4, torch.int32) for x in xs]
+    vbs = [_sentinel(c + 8, dt) for c in caps]
+    nnz = torch.full((len(xs) + 1,), -7, dtype=torch.int64, device="cuda")
+    items = bt.compress_items(xd, [b[:(x.numel() + 31) // 32] for b, x in zip(bms, xs)],
+                              [v[:c] for v, c in zip(vbs, caps)], nnz)
+    bt.bt_compress_batch(items, len(xs), dt, ws)
+    torch.cuda.synchronize()
+    nnz_h = nnz.cpu().numpy()
+    assert nnz_h[len(xs)] == -7
+    res = []
+    for x, b, v, c, k in zip(xs, bms, vbs, caps, nnz_h):
+        words = (x.numel() + 31) // 32
+        bm = b.cpu().numpy().view(np.uint32)
+        vb = wl.bits(v.cpu())
+        assert (bm[words:] == 0x5A5A5A5A).all(), "wrote past the bitmap"
+        assert (vb[min(int(k), c):] == _sent_of(vb)).all(), "wrote past values[min(nnz, cap))"
+        res.append((bm[:words].copy(), vb[:c].copy(), int(k)))
+    return res
+
+
+def _decompress_batch(bt, comp, ns, dt, ws):
+    """comp: per tensor (bitmap uint32, values bits); returns the restored bits per tensor."""
+    pad = 16 // torch.empty(0, dtype=dt).element_size()
+    bms = [torch.from_numpy(b.view(np.int32).copy()).cuda() for b, _ in comp]
+    vals = [torch.from_numpy(v.view({2: np.int16, 4: np.int32}[v.itemsize]).copy()).view(dt).cuda() for _, v in comp]
+    obufs = [_sentinel(n + pad, dt) for n in ns]
+    items = bt.decompress_items(bms, vals, [o[:n] for o, n in zip(obufs, ns)])
+    bt.bt_decompress_batch(items, len(ns), dt, ws)
+    torch.cuda.synchronize()
+    outs = []
+    for o, n in zip(obufs, ns):
+        ob = wl.bits(o.cpu())
+        assert (ob[n:] == _sent_of(ob)).all(), "wrote past out[n)"
+        outs.append(ob[:n].copy())
+    return outs
+
+
+def _check_batch(bt, oracle, xs, ws=None):
+    dt = xs[0].dtype
+    ns = [x.numel() for x in xs]
+    if ws is None:
+        ws = bt.new_batch_workspace(ns, dt)
+    got = _compress_batch(bt, xs, ws)
+    want = []
+    for i, (x, (bitmap, values, nnz)) in enumerate(zip(xs, got)):
+        o_bitmap, o_values, o_nnz = oracle.compress(wl.bits(x))
+        assert nnz == o_nnz, i
+        assert np.array_equal(bitmap, o_bitmap), i
+        assert np.array_equal(values[:o_nnz], o_values), i
+        want.append((o_bitmap, o_values))
+    outs = _decompress_batch(bt, want, ns, dt, ws)
+    for i, (x, out, (o_bitmap, o_values)) in enumerate(zip(xs, outs, want)):
+        assert np.array_equal(out, oracle.decompress(o_bitmap, o_values, x.numel())), i
+        assert np.array_equal(out, wl.bits(x)), i
+    return ws
+
+
+def _mixed_sizes(width):
+    t = TILE[width]
+    # empty, tiny, around one tile, exactly one scanner row of tiles and one more, a ragged large one
+    return [0, 1, 33, t - 1, t, t + 1, 3 * t + 17, 64 * t, 0, 64 * t + 1, 65 * t - 5, 130 * t + 1234, 7]
+
+
+@pytest.mark.parametrize("dt", ["f32", "f16", "bf16"])
+def test_batch_mixed_sizes(bt, oracle, dt):
+    width = 4 if dt == "f32" else 2
+    xs = [wl.random_sparse(n, dt, 0.1 + 0.07 * (k % 12), 300 + k) for k, n in enumerate(_mixed_sizes(width))]
+    _check_batch(bt, oracle, xs)
+
+
+def test_batch_special_bit_patterns_and_extremes(bt, oracle):
+    t = TILE[4]
+    xs = [wl.special_values("f32"), torch.zeros(2 * t + 5), torch.ones(t + 3), wl.special_values("f32").repeat(700),
+          torch.zeros(1), torch.ones(1)]
+    _check_batch(bt, oracle, xs)
+
+
+def test_batch_of_more_tensors_than_one_launch_takes(bt, oracle):
+    """150 tensors: three launches that reuse the workspace back to back."""
+    xs = [wl.random_sparse(1 + (k * 7919) % 40000, "f32", 0.5, 1000 + k) for k in range(150)]
+    _check_batch(bt, oracle, xs)
+
+
+def test_batch_and_single_calls_share_a_workspace(bt, oracle):
+    """Large batch, small single call, small batch, large single call, large batch: each call
+    cleans up what the one before it left, whatever their sizes."""
+    from tests import gpu_util
+    t = TILE[4]
+    big = [wl.random_sparse(n, "f32", 0.5, 40 + k) for k, n in enumerate([70 * t + 3, 5, 200 * t, t])]
+    small = [wl.random_sparse(n, "f32", 0.7, 50 + k) for k, n in enumerate([100, 2 * t])]
+    n_single = 300 * t + 11
+    ws_bytes = max(bt.bt_batch_workspace_bytes([x.numel() for x in big], torch.float32),
+                   bt.bt_workspace_bytes(n_single, torch.float32))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    bt.bt_workspace_init(ws)
+    xs_small = wl.random_sparse(1000, "f32", 0.3, 60)
+    xs_large = wl.random_sparse(n_single, "f32", 0.6, 61)
+    for _ in range(2):
+        _check_batch(bt, oracle, big, ws)
+        bitmap, values, nnz, ok = gpu_util.gpu_compress(xs_small, ws=ws)
+        o = oracle.compress(wl.bits(xs_small))
+        assert ok and nnz == o[2] and np.array_equal(bitmap, o[0]) and np.array_equal(values[:nnz], o[1])
+        _check_batch(bt, oracle, small, ws)
+        bitmap, values, nnz, ok = gpu_util.gpu_compress(xs_large, ws=ws)
+        o = oracle.compress(wl.bits(xs_large))
+        assert ok and nnz == o[2] and np.array_equal(bitmap, o[0]) and np.array_equal(values[:nnz], o[1])
+        out, ok = gpu_util.gpu_decompress(o[0], o[1], n_single, torch.float32, ws=ws)
+        assert ok and np.array_equal(out, wl.bits(xs_large))
+    hdr = ws[:12].cpu().numpy().view(np.uint32)
+    assert hdr[2] == 0, "a bounded wait ran out"
+
+
+def test_batch_capacity_of_one_tensor_does_not_touch_the_others(bt, oracle):
+    t = TILE[4]
+    xs = [wl.random_sparse(n, "f32", 0.5, 70 + k) for k, n in enumerate([3 * t, 2 * t + 9, t])]
+    want = [oracle.compress(wl.bits(x)) for x in xs]
+    caps = [xs[0].numel(), want[1][2] // 2, 0]
+    ws = bt.new_batch_workspace([x.numel() for x in xs], torch.float32)
+    got = _compress_batch(bt, xs, ws, caps)
+    for (bitmap, values, nnz), (o_bitmap, o_values, o_nnz), cap in zip(got, want, caps):
+        assert nnz == o_nnz and np.array_equal(bitmap, o_bitmap)
+        w = min(o_nnz, cap)
+        assert np.array_equal(values[:w], o_values[:w])
+
+
+def test_batch_empty_list_and_host_errors(bt):
+    ws = bt.new_batch_workspace([], torch.float32)
+    assert ws.numel() == bt.bt_workspace_bytes(0, torch.float32)
+    bt.bt_compress_batch(bt.compress_items([], [], [], torch.zeros(1, dtype=torch.int64, device="cuda")), 0,
+                         torch.float32, ws)
+    bt.bt_decompress_batch(bt.decompress_items([], [], []), 0, torch.float32, ws)
+    x = torch.ones(100000, device="cuda")
+    bitmap = torch.zeros(3125, dtype=torch.int32, device="cuda")
+    values = torch.zeros(100000, device="cuda")
+    nnz = torch.zeros(1, dtype=torch.int64, device="cuda")
+    items = bt.compress_items([x], [bitmap], [values], nnz)
+    with pytest.raises(bt.BitTrainError) as e:
+        bt.bt_compress_batch(items, 1, torch.float32, ws[:512])
+    assert e.value.status == 4
+    items[0].d_in += 4
+    with pytest.raises(bt.BitTrainError) as e:
+        bt.bt_compress_batch(items, 1, torch.float32, bt.new_batch_workspace([100000], torch.float32))
+    assert e.value.status == 3
+    torch.cuda.synchronize()
+    assert int(nnz.item()) == 0 and int(bitmap.abs().sum().item()) == 0    # nothing was launched
+
+
+def test_batch_config4_resnet50_set_full_size(bt, oracle):
+    """The 49 activations of the ResNet-50 set in one compress launch and one restore launch."""
+    dt = torch.float32
+    shapes = wl.config4_shapes()
+    ns = [int(np.prod(s)) for s in shapes]
+    ws = bt.new_batch_workspace(ns, dt)
+    xd, bms, vals = [], [], []
+    want_nnz = []
+    for cfg in wl.config4_tensors():
+        x = cfg["x"].reshape(-1)
+        xd.append(x.cuda())
+        bms.append(torch.empty((x.numel() + 31) // 32, dtype=torch.int32, device="cuda"))
+        want_nnz.append(int((x != 0).sum()))
+        vals.append(torch.empty(want_nnz[-1], dtype=dt, device="cuda"))          # right-sized
+    nnz = torch.zeros(len(ns), dtype=torch.int64, device="cuda")
+    bt.bt_compress_batch(bt.compress_items(xd, bms, vals, nnz), len(ns), dt, ws)
+    torch.cuda.synchronize()
+    assert nnz.cpu().tolist() == want_nnz
+    outs = [torch.empty(n, dtype=dt, device="cuda") for n in ns]
+    bt.bt_decompress_batch(bt.decompress_items(bms, vals, outs), len(ns), dt, ws)
+    torch.cuda.synchronize()
+    for k, (x, b, v, o) in enumerate(zip(xd, bms, vals, outs)):
+        xb = wl.bits(x.cpu())
+        o_bitmap, o_values, o_nnz = oracle.compress(xb)
+        assert o_nnz == want_nnz[k]
+        assert np.array_equal(b.cpu().numpy().view(np.uint32), o_bitmap), k
+        assert np.array_equal(wl.bits(v.cpu()), o_values), k
+        assert np.array_equal(wl.bits(o.cpu()), xb), k
