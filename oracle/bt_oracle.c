@@ -29,6 +29,12 @@
  * elsewhere.  With threshold 0 on a pre-activation tensor this is ReLU.  Pruning
  * followed by Algorithm 1 is what the fused GPU call is checked against.
  *
+ * The COO footprint M_c of Section 3.2 is bt_oracle_coo_size (a value plus one index per
+ * dimension for every non-zero).  The double-mask batch normalisation of Section 3.1
+ * (the sparsity pattern of a layer's input is applied to its output) is
+ * bt_oracle_mask_apply: out[i] = x[i] where the other tensor's bitmap has bit i set, +0
+ * elsewhere -- the same select as the ReLU backward, stated on its own.
+ *
  * Parity pins (tests/test_oracle_*.py): the theoretical columns of Table 1,
  * hand-built tensors, numpy.packbits / boolean indexing, enumeration of all
  * 2^16 zero patterns of a 16-element tensor, every n in [0,130], closed forms
@@ -187,4 +193,31 @@ uint64_t bt_oracle_prune(const void *T, uint64_t n, int dtype, float threshold, 
         }
     }
     return kept;
+}
+
+/* ---- the comparison format and the double mask -------------------------------- */
+
+/* M_c of Section 3.2: every non-zero activation is stored as its value plus one index
+ * per dimension; indices are 4-byte integers or 8-byte longs.  Returns 0 when the
+ * arguments make no sense. */
+uint64_t bt_oracle_coo_size(uint64_t nnz, int ndim, int index_bytes, int width)
+{
+    if (!width_ok(width) || ndim < 1 || (index_bytes != 4 && index_bytes != 8)) return 0;
+    return ((uint64_t)width + (uint64_t)index_bytes * (uint64_t)ndim) * nnz;
+}
+
+/* Double mask (Section 3.1): the bitmap of one tensor (a normalisation layer's input)
+ * masks another tensor x of the same length (that layer's output). */
+int bt_oracle_mask_apply(const uint32_t *bitmap, const void *x, uint64_t n, int width, void *out)
+{
+    if (!width_ok(width)) return -1;
+    const unsigned char *src = (const unsigned char *)x;
+    unsigned char *dst = (unsigned char *)out;
+    for (uint64_t i = 0; i < n; ++i) {
+        if ((bitmap[i / 32] >> (i % 32)) & 1u)
+            store_bits(dst, i, width, load_bits(src, i, width));
+        else
+            store_bits(dst, i, width, 0);
+    }
+    return 0;
 }

@@ -43,6 +43,10 @@ def _load():
         lib.bt_oracle_relu_backward.argtypes = [vp, vp, u64, ci, vp]
         lib.bt_oracle_prune.restype = u64
         lib.bt_oracle_prune.argtypes = [vp, u64, ci, ctypes.c_float, vp]
+        lib.bt_oracle_coo_size.restype = u64
+        lib.bt_oracle_coo_size.argtypes = [u64, ci, ci, ci]
+        lib.bt_oracle_mask_apply.restype = ci
+        lib.bt_oracle_mask_apply.argtypes = [vp, vp, u64, ci, vp]
         _lib = lib
     return _lib
 
@@ -122,3 +126,21 @@ def prune(T, dtype, threshold):
 def compress_pruned(T, dtype, threshold):
     """Pruning followed by Algorithm 1: (bitmap, values, nnz)."""
     return compress(prune(T, dtype, threshold))
+
+
+def coo_size(nnz, ndim, index_bytes, width):
+    """M_c of Section 3.2."""
+    return int(_load().bt_oracle_coo_size(nnz, ndim, index_bytes, width))
+
+
+def mask_apply(bitmap, x):
+    """Double mask (Section 3.1): out[i] = bit(i) ? x[i] : +0 with another tensor's bitmap."""
+    bitmap = np.ascontiguousarray(bitmap, dtype=np.uint32)
+    x = _flat(x)
+    n = x.size
+    assert bitmap.size == (n + 31) // 32
+    out = np.empty(n, dtype=x.dtype)
+    out.view(np.uint8)[:] = 0xA5
+    rc = _load().bt_oracle_mask_apply(_ptr(bitmap), _ptr(x), n, x.dtype.itemsize, _ptr(out))
+    assert rc == 0
+    return out

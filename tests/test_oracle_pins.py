@@ -280,3 +280,59 @@ def test_prune_with_threshold_zero_is_relu(oracle):
     assert kept == sorted(kept, reverse=True) and kept[0] > kept[-1]
     for t, k in zip((0.0, 0.01, 0.05, 0.1), kept):
         assert k == int((x > np.float32(t)).sum())
+
+
+# ---- the COO comparison format (Section 3.2) and the double mask (Section 3.1) ----
+
+def test_coo_size_formula_and_the_papers_break_even(oracle):
+    """M_c = (4 + [4|8] * dimensions) * non-zeros for fp32.  The paper's reading of its
+    footprint figure: COO only pays off at 80 % sparsity or more (about 20 % non-zeros),
+    which is the break-even against the dense format of a 4-D activation with 4-byte
+    indices, (4 + 16) * nnz = 4 * n."""
+    n = 5 * 9 * 128 * 1000                                    # divisible by every break-even ratio below
+    assert oracle.coo_size(1, 4, 4, 4) == 20 and oracle.coo_size(1, 4, 8, 4) == 36
+    assert oracle.coo_size(7, 2, 8, 2) == 7 * (2 + 16)
+    assert oracle.coo_size(n // 5, 4, 4, 4) == oracle.dense_size(n, 4)            # exactly 20 % non-zeros
+    assert oracle.coo_size(n // 5 - 1, 4, 4, 4) < oracle.dense_size(n, 4) < oracle.coo_size(n // 5 + 1, 4, 4, 4)
+    # long indices (the frameworks' default) move the break-even down to 1/9 non-zeros
+    assert oracle.coo_size(n // 9, 4, 8, 4) == oracle.dense_size(n, 4) < oracle.coo_size(n // 9 + 1, 4, 8, 4)
+    # the bitmap format beats dense up to 31/32 non-zeros (Table 1: -3.13 % at 100 %, +21.88 % at 75 %) ...
+    assert oracle.compressed_size(n, n * 31 // 32, 4) == oracle.dense_size(n, 4)
+    # ... and beats COO (4-byte indices, 4-D) as soon as more than 1/128 of the elements are non-zero:
+    # 4 nnz + n/8 < 20 nnz  <=>  nnz > n/128
+    assert oracle.compressed_size(n, n // 128, 4) == oracle.coo_size(n // 128, 4, 4, 4)
+    assert oracle.compressed_size(n, n // 128 + 1, 4) < oracle.coo_size(n // 128 + 1, 4, 4, 4)
+    # nonsense arguments
+    assert oracle.coo_size(5, 0, 4, 4) == 0 and oracle.coo_size(5, 4, 2, 4) == 0 and oracle.coo_size(5, 4, 4, 3) == 0
+
+
+@pytest.mark.parametrize("npdt", [np.uint16, np.uint32, np.uint64])
+def test_mask_apply_is_a_select_by_another_tensors_bitmap(oracle, npdt):
+    rng = np.random.default_rng(77)
+    for n in (0, 1, 31, 32, 33, 100, 1000):
+        x = rng.integers(1, 2**16, size=n).astype(npdt)                   # the masked tensor: no zeros
+        src = rng.integers(0, 2**16, size=n).astype(npdt) * (rng.random(n) < 0.4)   # the tensor that gives the pattern
+        bitmap, _, nnz = oracle.compress(src)
+        out = oracle.mask_apply(bitmap, x)
+        assert np.array_equal(out, np.where(src != 0, x, 0).astype(npdt))
+        # the point of the double mask: the output has exactly the input's sparsity pattern
+        out_bitmap, out_values, out_nnz = oracle.compress(out)
+        assert np.array_equal(out_bitmap, bitmap) and out_nnz == nnz
+        assert np.array_equal(out_values, x[src != 0])
+        # brute force over the bits, pure Python
+        want = [int(x[i]) if (int(bitmap[i // 32]) >> (i % 32)) & 1 else 0 for i in range(n)]
+        assert out.tolist() == want
+
+
+def test_mask_apply_special_cases(oracle):
+    # a select, not a multiply: what sits under a cleared bit never leaks; kept elements keep their bits
+    x = np.array([0x7FC00000, 0xFF800000, 0x80000000, 0x00000001, 0x3F800000], dtype=np.uint32)
+    out = oracle.mask_apply(np.array([0b10110], dtype=np.uint32), x)
+    assert out.tolist() == [0, 0xFF800000, 0x80000000, 0, 0x3F800000]
+    # bits at positions >= n are ignored; all-ones and all-zero masks
+    assert oracle.mask_apply(np.array([0xFFFFFFFF], dtype=np.uint32), x).tolist() == x.tolist()
+    assert oracle.mask_apply(np.array([0xFFFFFFE0], dtype=np.uint32), x).tolist() == [0] * 5
+    # it is the same function of (bitmap, tensor) as the ReLU backward
+    g = np.arange(1, 71, dtype=np.uint16)
+    bm = np.array([0xDEADBEEF, 0x12345678, 0x2A], dtype=np.uint32)
+    assert np.array_equal(oracle.mask_apply(bm, g), oracle.relu_backward(bm, g))
