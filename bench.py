@@ -103,6 +103,8 @@ def other_configs(bt, wl, torch, dev, timed, args):
         draws = c["draws"]
         one("5: fp16 [256,64,112,112] zero probability %.2f" % p, c["x"], 3, 20)
     del draws
+    # double precision (the format covers half, single and double): the configuration-2 tensor as fp64
+    one("fp64 [32,256,56,56], 50 % zeros (configuration 2 widened to double)", wl.config2(0.5)["x"].double(), 4, 30)
 
     # Section 4.3 fused into Algorithm 1 (next-step row): pre-activations of configuration 2, thresholds of the paper
     pre = wl.config2(0.5)["base"].reshape(-1)

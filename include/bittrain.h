@@ -38,7 +38,8 @@ extern "C" {
 typedef enum {
     BT_F32 = 0,  /* 4-byte elements */
     BT_F16 = 1,  /* 2-byte elements */
-    BT_BF16 = 2  /* 2-byte elements; identical to BT_F16 at the byte level */
+    BT_BF16 = 2, /* 2-byte elements; identical to BT_F16 at the byte level */
+    BT_F64 = 3   /* 8-byte elements (the paper's formats are half, single and double precision) */
 } bt_dtype;
 
 typedef enum {
@@ -69,13 +70,22 @@ typedef void *bt_stream;
  * Returns 0 for an unknown dtype or nnz > n. */
 size_t bt_compressed_size(uint64_t n, uint64_t nnz, bt_dtype dtype);
 
+/* M_d of Section 3.2: n * sizeof(dtype), the dense footprint.  0 for an unknown dtype. */
+size_t bt_dense_size(uint64_t n, bt_dtype dtype);
+
+/* M_c of Section 3.2, the footprint of the coordinate-list (COO) format the paper
+ * compares with: (sizeof(dtype) + index_bytes * ndim) * nnz, index_bytes being 4
+ * (integer indices) or 8 (long indices).  0 for an unknown dtype, ndim == 0 or
+ * another index size. */
+size_t bt_coo_size(uint64_t nnz, uint32_t ndim, uint32_t index_bytes, bt_dtype dtype);
+
 /* 4 * ceil(n/32): the bytes d_bitmap must hold. */
 size_t bt_bitmap_bytes(uint64_t n);
 
 /* Bytes of scratch that bt_compress / bt_decompress need for a tensor of n
  * elements: a 256-byte header plus 24 bytes per tile of the single-pass grid
- * scan (a tile is 8192 four-byte or 16384 two-byte elements), in records of 32
- * tiles.  Monotone in n; 0 for an unknown dtype. */
+ * scan (a tile is 32 KiB of dense data: 4096 eight-byte, 8192 four-byte or 16384
+ * two-byte elements), in records of 32 tiles.  Monotone in n; 0 for an unknown dtype. */
 size_t bt_workspace_bytes(uint64_t n, bt_dtype dtype);
 
 /* Size in bytes of one element, 0 for an unknown dtype. */
@@ -121,8 +131,8 @@ bt_status bt_compress(const void *d_in, uint64_t n, bt_dtype dtype,
 /* Activation pruning (Section 4.3) fused into Algorithm 1: one pass that stores an
  * element only where its value exceeds `threshold` and treats it as zero elsewhere
  * (the paper's thresholds are 0, 0.01, 0.05 and 0.1).  The comparison is strict and is
- * made in single precision after widening fp16 / bf16 exactly; a NaN exceeds nothing
- * and is dropped.  The result is exactly bt_compress of the pruned tensor (so a +0.0
+ * made in single precision after widening fp16 / bf16 exactly (for BT_F64: in double
+ * precision, the threshold widened exactly); a NaN exceeds nothing and is dropped.  The result is exactly bt_compress of the pruned tensor (so a +0.0
  * that survives a negative threshold is still not stored).  The bitmap marks the kept
  * elements, d_values holds their original
  * bit patterns in index order, *d_nnz their number.  With threshold 0 on a
@@ -158,6 +168,16 @@ bt_status bt_decompress(const uint32_t *d_bitmap, const void *d_values, uint64_t
 bt_status bt_relu_backward_from_bitmap(const uint32_t *d_bitmap, const void *d_grad_out,
                                        uint64_t n, bt_dtype dtype, void *d_grad_in,
                                        bt_stream stream);
+
+/* Double-mask batch normalisation (Section 3.1, "Exploiting Sparsity"): the sparsity
+ * pattern of a normalisation layer's input is applied to its output, so that the
+ * output compresses as well as the input did.  d_bitmap is the bitmap of that input
+ * (as written by bt_compress), d_in the layer's output:
+ *   out[i] = bit(i) ? in[i] : +0.
+ * The same select as bt_relu_backward_from_bitmap, under the name of this use; all
+ * requirements and errors as there (d_out may be d_in). */
+bt_status bt_mask_apply(const uint32_t *d_bitmap, const void *d_in, uint64_t n, bt_dtype dtype,
+                        void *d_out, bt_stream stream);
 
 /* ---- many tensors in one launch ------------------------------------------------
  *

@@ -25,7 +25,7 @@
  *
  * Activation pruning (Section 4.3) is bt_oracle_prune: an element is kept where its
  * value exceeds the threshold (strictly; the comparison is made in single precision
- * after widening half / bfloat16 exactly; a NaN exceeds nothing) and becomes +0
+ * after widening half / bfloat16 exactly, in double precision for doubles; a NaN exceeds nothing) and becomes +0
  * elsewhere.  With threshold 0 on a pre-activation tensor this is ReLU.  Pruning
  * followed by Algorithm 1 is what the fused GPU call is checked against.
  *
@@ -144,7 +144,7 @@ int bt_oracle_relu_backward(const uint32_t *bitmap, const void *grad_out,
 
 /* ---- activation pruning (Section 4.3) ---------------------------------------- */
 
-/* dtype codes of this file only: 0 = fp32, 1 = fp16, 2 = bfloat16 */
+/* dtype codes of this file only: 0 = fp32, 1 = fp16, 2 = bfloat16 (3 = fp64 is not widened: see bt_oracle_prune) */
 static float widen_to_f32(uint64_t bits, int dtype)
 {
     uint32_t u;
@@ -175,17 +175,27 @@ static float widen_to_f32(uint64_t bits, int dtype)
 }
 
 /* out[i] = T[i] where value(T[i]) > threshold, +0 (all-zero bits) elsewhere.
+ * Double-precision elements (dtype 3) are compared as doubles with the threshold
+ * widened to double, which is exact as well.
  * Returns the number of kept elements, or UINT64_MAX for an unknown dtype. */
 uint64_t bt_oracle_prune(const void *T, uint64_t n, int dtype, float threshold, void *out)
 {
-    if (dtype < 0 || dtype > 2) return UINT64_MAX;
-    const int width = dtype == 0 ? 4 : 2;
+    if (dtype < 0 || dtype > 3) return UINT64_MAX;
+    const int width = dtype == 3 ? 8 : (dtype == 0 ? 4 : 2);
     const unsigned char *t = (const unsigned char *)T;
     unsigned char *o = (unsigned char *)out;
     uint64_t kept = 0;
     for (uint64_t i = 0; i < n; ++i) {
         uint64_t bits = load_bits(t, i, width);
-        if (widen_to_f32(bits, dtype) > threshold) {
+        int keep;
+        if (dtype == 3) {
+            double d;
+            memcpy(&d, &bits, sizeof d);
+            keep = d > (double)threshold;
+        } else {
+            keep = widen_to_f32(bits, dtype) > threshold;
+        }
+        if (keep) {
             store_bits(o, i, width, bits);
             kept += 1;
         } else {

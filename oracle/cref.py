@@ -107,15 +107,15 @@ def relu_backward(bitmap, grad_out):
     return out
 
 
-DTYPE_CODES = {"f32": 0, "f16": 1, "bf16": 2}
+DTYPE_CODES = {"f32": 0, "f16": 1, "bf16": 2, "f64": 3}
 
 
 def prune(T, dtype, threshold):
     """Section 4.3: keep elements whose value exceeds the threshold, +0 elsewhere.
-    T holds raw bits (uint32 for "f32", uint16 for "f16" / "bf16")."""
+    T holds raw bits (uint32 for "f32", uint16 for "f16" / "bf16", uint64 for "f64")."""
     T = _flat(T)
     code = DTYPE_CODES[dtype]
-    assert T.dtype.itemsize == (4 if code == 0 else 2)
+    assert T.dtype.itemsize == {0: 4, 1: 2, 2: 2, 3: 8}[code]
     out = np.empty_like(T)
     out.view(np.uint8)[:] = 0xA5
     kept = int(_load().bt_oracle_prune(_ptr(T), T.size, code, float(np.float32(threshold)), _ptr(out)))

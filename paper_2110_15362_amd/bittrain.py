@@ -13,13 +13,13 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbittrain.so")
 
-BT_F32, BT_F16, BT_BF16 = 0, 1, 2
+BT_F32, BT_F16, BT_BF16, BT_F64 = 0, 1, 2, 3
 BT_OK = 0
 STATUS_NAMES = {0: "BT_OK", 1: "BT_ERR_NULL", 2: "BT_ERR_DTYPE", 3: "BT_ERR_ALIGN", 4: "BT_ERR_WORKSPACE",
                 5: "BT_ERR_HIP", 6: "BT_ERR_SIZE"}
 BT_MAX_ELEMENTS = 1 << 37
 
-_DTYPES = {torch.float32: BT_F32, torch.float16: BT_F16, torch.bfloat16: BT_BF16}
+_DTYPES = {torch.float32: BT_F32, torch.float16: BT_F16, torch.bfloat16: BT_BF16, torch.float64: BT_F64}
 
 _lib = None
 
@@ -65,6 +65,10 @@ def lib():
         L.bt_decompress.argtypes = [vp, vp, u64, ci, vp, vp, sz, vp]
         L.bt_relu_backward_from_bitmap.restype = ci
         L.bt_relu_backward_from_bitmap.argtypes = [vp, vp, u64, ci, vp, vp]
+        L.bt_dense_size.restype, L.bt_dense_size.argtypes = sz, [u64, ci]
+        L.bt_coo_size.restype, L.bt_coo_size.argtypes = sz, [u64, ctypes.c_uint32, ctypes.c_uint32, ci]
+        L.bt_mask_apply.restype = ci
+        L.bt_mask_apply.argtypes = [vp, vp, u64, ci, vp, vp]
         L.bt_batch_workspace_bytes.restype = sz
         L.bt_batch_workspace_bytes.argtypes = [ctypes.POINTER(u64), sz, ci]
         L.bt_compress_batch.restype = ci
@@ -83,11 +87,23 @@ def dtype_code(dtype):
     try:
         return _DTYPES[dtype]
     except KeyError:
-        raise TypeError("libbittrain handles float32, float16 and bfloat16, not %s" % dtype)
+        raise TypeError("libbittrain handles float64, float32, float16 and bfloat16, not %s" % dtype)
 
 
 def bt_compressed_size(n, nnz, dtype):
     return int(lib().bt_compressed_size(n, nnz, dtype if isinstance(dtype, int) else dtype_code(dtype)))
+
+
+def _code(dtype):
+    return dtype if isinstance(dtype, int) else dtype_code(dtype)
+
+
+def bt_dense_size(n, dtype):
+    return int(lib().bt_dense_size(n, _code(dtype)))
+
+
+def bt_coo_size(nnz, ndim, index_bytes, dtype):
+    return int(lib().bt_coo_size(nnz, ndim, index_bytes, _code(dtype)))
 
 
 def bt_bitmap_bytes(n):
@@ -257,3 +273,15 @@ def bt_decompress_batch(items, count, dtype, workspace, stream=None):
     _check("bt_decompress_batch", lib().bt_decompress_batch(
         items, count, dtype if isinstance(dtype, int) else dtype_code(dtype), _ptr(workspace), _bytes(workspace),
         _stream(stream)))
+
+
+def bt_mask_apply(bitmap, x, out, stream=None):
+    """Double mask: out[i] = bit(i) ? x[i] : +0 with the bitmap of another tensor; out may be x."""
+    for t, name in ((bitmap, "bitmap"), (x, "x"), (out, "out")):
+        _dev(t, name)
+    if out.dtype != x.dtype or out.numel() != x.numel():
+        raise TypeError("out must match x")
+    if bitmap.element_size() != 4 or bitmap.numel() * 4 < bt_bitmap_bytes(x.numel()):
+        raise ValueError("bitmap must hold ceil(n/32) 32-bit words")
+    _check("bt_mask_apply", lib().bt_mask_apply(_ptr(bitmap), _ptr(x), x.numel(), dtype_code(x.dtype), _ptr(out),
+                                                _stream(stream)))

@@ -20,6 +20,7 @@
 // about keeping enough bytes in flight while a tile waits for its prefix.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "bittrain.h"
 
@@ -98,11 +99,12 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x) {
     return x;
 }
 
-// OR over each aligned group of G lanes (G = 4 or 8); every lane gets the result.
+// OR over each aligned group of G lanes (G = 4, 8 or 16); every lane gets the result.
 template <int G> __device__ __forceinline__ uint32_t group_or(uint32_t x) {
     x |= BT_DPP(0, x, 0xB1, 0xf, true);       // quad_perm [1,0,3,2]: lane ^ 1
     x |= BT_DPP(0, x, 0x4E, 0xf, true);       // quad_perm [2,3,0,1]: lane ^ 2
-    if (G == 8) x |= BT_DPP(0, x, 0x141, 0xf, true);  // row_half_mirror: lane i <-> 7 - i
+    if (G >= 8) x |= BT_DPP(0, x, 0x141, 0xf, true);   // row_half_mirror: lane i <-> 7 - i
+    if (G == 16) x |= BT_DPP(0, x, 0x140, 0xf, true);  // row_mirror: lane i <-> 15 - i
     return x;
 }
 
@@ -150,7 +152,9 @@ constexpr bool kReluNtLoad = true, kReluNtStore = true;
 template <int S> __device__ __forceinline__ uint32_t nonzero_mask(const uint4 v) {
     const uint32_t d[4] = {v.x, v.y, v.z, v.w};
     uint32_t m = 0;
-    if (S == 4) {
+    if (S == 8) {
+        m = min(d[0] | d[1], 1u) | (min(d[2] | d[3], 1u) << 1);
+    } else if (S == 4) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) m |= min(d[i], 1u) << i;
     } else {
@@ -167,14 +171,19 @@ template <int S> __device__ __forceinline__ uint32_t nonzero_mask(const uint4 v)
 // test (non-zero bit pattern).  Otherwise activation pruning (Section 4.3) followed by
 // that test, in one pass: an element survives pruning where its value exceeds
 // `threshold`, compared in single precision after widening (exact for half and
-// bfloat16; a NaN exceeds nothing), and is then stored if its bit pattern is non-zero
-// (a +0.0 that survives a negative threshold is still a zero for Algorithm 1).
-enum { kKeepNonZero = 0, kKeepAboveF32 = 1, kKeepAboveF16 = 2, kKeepAboveBF16 = 3 };
+// bfloat16; a double is compared with the threshold widened to double, also exact; a
+// NaN exceeds nothing), and is then stored if its bit pattern is non-zero (a +0.0 that
+// survives a negative threshold is still a zero for Algorithm 1).
+enum { kKeepNonZero = 0, kKeepAboveF32 = 1, kKeepAboveF16 = 2, kKeepAboveBF16 = 3, kKeepAboveF64 = 4 };
 template <int S, int KEEP> __device__ __forceinline__ uint32_t keep_mask(const uint4 v, const float threshold) {
     if (KEEP == kKeepNonZero) return nonzero_mask<S>(v);
     const uint32_t d[4] = {v.x, v.y, v.z, v.w};
     uint32_t m = 0;
-    if (KEEP == kKeepAboveF32) {
+    if (KEEP == kKeepAboveF64) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            m |= (__longlong_as_double((long long)(((uint64_t)d[2 * i + 1] << 32) | d[2 * i])) > (double)threshold ? 1u : 0u) << i;
+    } else if (KEEP == kKeepAboveF32) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) m |= (__uint_as_float(d[i]) > threshold ? 1u : 0u) << i;
     } else {
@@ -199,7 +208,16 @@ template <int S, int KEEP> __device__ __forceinline__ uint32_t keep_mask(const u
 // read as 0.  Branch-free: every address is clamped into the buffer, then selected.
 template <int S> __device__ __forceinline__ uint4 load_vec_guarded(const void *base, uint64_t e0, uint64_t n) {
     uint32_t d[4] = {0, 0, 0, 0};
-    if (S == 4) {
+    if (S == 8) {
+        const uint64_t *p = static_cast<const uint64_t *>(base);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint64_t e = e0 + j;
+            const uint64_t v = p[e < n ? e : n - 1];
+            d[2 * j] = e < n ? (uint32_t)v : 0u;
+            d[2 * j + 1] = e < n ? (uint32_t)(v >> 32) : 0u;
+        }
+    } else if (S == 4) {
         const uint32_t *p = static_cast<const uint32_t *>(base);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -226,7 +244,12 @@ template <int S> __device__ __forceinline__ void store_vec_guarded(void *base, u
         return;
     }
     const uint32_t d[4] = {v.x, v.y, v.z, v.w};
-    if (S == 4) {
+    if (S == 8) {
+        uint64_t *p = static_cast<uint64_t *>(base);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            if (e0 + j < n) p[e0 + j] = ((uint64_t)d[2 * j + 1] << 32) | d[2 * j];
+    } else if (S == 4) {
         uint32_t *p = static_cast<uint32_t *>(base);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -510,7 +533,8 @@ __device__ __forceinline__ void strip_store(const unsigned char *strip, char *g0
             for (int j = 0; j < E; ++j) {
                 const uint32_t e = lo + j;
                 if (e >= lo_valid && e < hi_valid) {
-                    if (S == 4) reinterpret_cast<uint32_t *>(gvec)[e] = reinterpret_cast<const uint32_t *>(strip)[e];
+                    if (S == 8) reinterpret_cast<uint64_t *>(gvec)[e] = reinterpret_cast<const uint64_t *>(strip)[e];
+                    else if (S == 4) reinterpret_cast<uint32_t *>(gvec)[e] = reinterpret_cast<const uint32_t *>(strip)[e];
                     else reinterpret_cast<uint16_t *>(gvec)[e] = reinterpret_cast<const uint16_t *>(strip)[e];
                 }
             }
@@ -525,14 +549,14 @@ __device__ __forceinline__ void strip_store(const unsigned char *strip, char *g0
 // vectors: the inner ones (at most 255, all fully inside the range) go four to a
 // lane; of the first and the last vector, lane j < E takes element j of the first
 // and lane E + j element j of the last, each only if it lies inside the range.
-struct Fetched {
+template <int S> struct Fetched {
     uint4 inner[4];
-    uint32_t edge;
+    typename std::conditional<S == 8, uint64_t, uint32_t>::type edge;
 };
 
 template <int S>
 __device__ __forceinline__ void strip_fetch(const char *g0_ptr, const uint32_t pad, const uint32_t cnt, const int lane,
-                                            Fetched &f) {
+                                            Fetched<S> &f) {
     constexpr int E = Geo<S>::E;
     static_assert(kPhaseRows * Geo<S>::ROW / E + 1 <= 2 + 4 * kWaveSize, "a phase must fit four inner vectors per lane");
     const char *gvec = g0_ptr - (size_t)pad * S;
@@ -548,13 +572,17 @@ __device__ __forceinline__ void strip_fetch(const char *g0_ptr, const uint32_t p
     if (lane < 2 * E && n_vec != 0) {
         const uint32_t e = lane < E ? (uint32_t)lane : (n_vec - 1) * E + (uint32_t)(lane - E);
         const bool wanted = e >= pad && e < hi_valid && (lane < E || n_vec > 1);
-        if (wanted) f.edge = S == 4 ? reinterpret_cast<const uint32_t *>(gvec)[e] : reinterpret_cast<const uint16_t *>(gvec)[e];
+        if (wanted) {
+            if (S == 8) f.edge = reinterpret_cast<const uint64_t *>(gvec)[e];
+            else if (S == 4) f.edge = reinterpret_cast<const uint32_t *>(gvec)[e];
+            else f.edge = reinterpret_cast<const uint16_t *>(gvec)[e];
+        }
     }
 }
 
 template <int S>
 __device__ __forceinline__ void strip_commit(unsigned char *strip, const uint32_t pad, const uint32_t cnt, const int lane,
-                                             const Fetched &f) {
+                                             const Fetched<S> &f) {
     constexpr int E = Geo<S>::E;
     const uint32_t hi_valid = pad + cnt;
     const uint32_t n_vec = cnt ? (hi_valid + E - 1) / E : 0;
@@ -567,7 +595,8 @@ __device__ __forceinline__ void strip_commit(unsigned char *strip, const uint32_
         const uint32_t e = lane < E ? (uint32_t)lane : (n_vec - 1) * E + (uint32_t)(lane - E);
         const bool wanted = e >= pad && e < hi_valid && (lane < E || n_vec > 1);
         if (wanted) {
-            if (S == 4) reinterpret_cast<uint32_t *>(strip)[e] = f.edge;
+            if (S == 8) reinterpret_cast<uint64_t *>(strip)[e] = f.edge;
+            else if (S == 4) reinterpret_cast<uint32_t *>(strip)[e] = (uint32_t)f.edge;
             else reinterpret_cast<uint16_t *>(strip)[e] = (uint16_t)f.edge;
         }
     }
@@ -683,7 +712,14 @@ __device__ __forceinline__ void compress_tile(const void *__restrict__ in, const
             uint32_t r = row_start + BT_FIELD(rank2, k);
             const uint32_t mk = BT_MASK(S, mp, k);
             const uint32_t d[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
-            if (S == 4) {
+            if (S == 8) {
+                uint64_t *l = reinterpret_cast<uint64_t *>(strip);
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    if (mk & (1u << j)) l[r] = ((uint64_t)d[2 * j + 1] << 32) | d[2 * j];
+                    r += (mk >> j) & 1u;
+                }
+            } else if (S == 4) {
                 uint32_t *l = reinterpret_cast<uint32_t *>(strip);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -820,7 +856,7 @@ __device__ __forceinline__ void decompress_tile(const uint32_t *__restrict__ bit
     //     wait for that store to reach memory.
     constexpr int kPhases = kRows / kPhaseRows;
     unsigned char *strip = s_stage + wave * G::LDS_WAVE;
-    Fetched fetched[kPhases];
+    Fetched<S> fetched[kPhases];
     uint32_t pads[kPhases], cnts[kPhases];
 #pragma unroll
     for (int ph = 0; ph < kPhases; ++ph) {
@@ -844,7 +880,18 @@ __device__ __forceinline__ void decompress_tile(const uint32_t *__restrict__ bit
             uint32_t r = row_start + BT_FIELD(rank2, k);
             const uint32_t mk = BT_MASK(S, mp, k);
             uint32_t d[4] = {0, 0, 0, 0};
-            if (S == 4) {
+            if (S == 8) {
+                const uint64_t *l = reinterpret_cast<const uint64_t *>(strip);
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    if (mk & (1u << j)) {
+                        const uint64_t v = l[r];
+                        d[2 * j] = (uint32_t)v;
+                        d[2 * j + 1] = (uint32_t)(v >> 32);
+                    }
+                    r += (mk >> j) & 1u;
+                }
+            } else if (S == 4) {
                 const uint32_t *l = reinterpret_cast<const uint32_t *>(strip);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -947,7 +994,10 @@ __global__ __launch_bounds__(kBlock) void relu_backward_kernel(const uint32_t *_
     for (int k = 0; k < kR; ++k) {
         const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
         uint32_t d[4] = {g[k].x, g[k].y, g[k].z, g[k].w};
-        if (S == 4) {
+        if (S == 8) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) d[j] = (m[k] & (1u << (j >> 1))) ? d[j] : 0u;
+        } else if (S == 4) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) d[j] = (m[k] & (1u << j)) ? d[j] : 0u;
         } else {
@@ -978,11 +1028,12 @@ int elem_size(bt_dtype dt) {
         case BT_F32: return 4;
         case BT_F16: return 2;
         case BT_BF16: return 2;
+        case BT_F64: return 8;
     }
     return 0;
 }
 
-uint64_t tile_elems(int s) { return s == 4 ? (uint64_t)Geo<4>::TILE : (uint64_t)Geo<2>::TILE; }
+uint64_t tile_elems(int s) { return (uint64_t)kBlock * kRows * (kVecBytes / s); }
 
 uint64_t tiles_for(uint64_t n, int s) {
     const uint64_t t = tile_elems(s);
@@ -1073,6 +1124,14 @@ size_t bt_compressed_size(uint64_t n, uint64_t nnz, bt_dtype dtype) {
     return (size_t)(4 * ((n + 31) / 32) + nnz * (uint64_t)s);
 }
 
+size_t bt_dense_size(uint64_t n, bt_dtype dtype) { return (size_t)(n * (uint64_t)elem_size(dtype)); }
+
+size_t bt_coo_size(uint64_t nnz, uint32_t ndim, uint32_t index_bytes, bt_dtype dtype) {
+    const int s = elem_size(dtype);
+    if (s == 0 || ndim == 0 || (index_bytes != 4 && index_bytes != 8)) return 0;
+    return (size_t)(((uint64_t)s + (uint64_t)index_bytes * ndim) * nnz);
+}
+
 size_t bt_workspace_bytes(uint64_t n, bt_dtype dtype) {
     const int s = elem_size(dtype);
     if (s == 0) return 0;
@@ -1125,8 +1184,11 @@ static bt_status compress_common(const void *d_in, uint64_t n, bt_dtype dtype, b
 #define BT_LAUNCH_COMPRESS(S_, KEEP_) \
     compress_kernel<S_, KEEP_><<<grid, block, 0, hs>>>(d_in, n, d_bitmap, d_values, values_cap, d_nnz, ws, n_tiles, threshold)
     if (!prune) {
-        if (s == 4) BT_LAUNCH_COMPRESS(4, kKeepNonZero);
+        if (s == 8) BT_LAUNCH_COMPRESS(8, kKeepNonZero);
+        else if (s == 4) BT_LAUNCH_COMPRESS(4, kKeepNonZero);
         else BT_LAUNCH_COMPRESS(2, kKeepNonZero);
+    } else if (dtype == BT_F64) {
+        BT_LAUNCH_COMPRESS(8, kKeepAboveF64);
     } else if (dtype == BT_F32) {
         BT_LAUNCH_COMPRESS(4, kKeepAboveF32);
     } else if (dtype == BT_F16) {
@@ -1164,7 +1226,9 @@ bt_status bt_decompress(const uint32_t *d_bitmap, const void *d_values, uint64_t
     hipStream_t hs = (hipStream_t)stream;
     const uint32_t n_tiles = (uint32_t)tiles_for(n, s);
     char *ws = static_cast<char *>(d_workspace);
-    if (s == 4)
+    if (s == 8)
+        decompress_kernel<8><<<dim3(n_tiles + 1), dim3(kBlock), 0, hs>>>(d_bitmap, d_values, n, d_out, ws, n_tiles);
+    else if (s == 4)
         decompress_kernel<4><<<dim3(n_tiles + 1), dim3(kBlock), 0, hs>>>(d_bitmap, d_values, n, d_out, ws, n_tiles);
     else
         decompress_kernel<2><<<dim3(n_tiles + 1), dim3(kBlock), 0, hs>>>(d_bitmap, d_values, n, d_out, ws, n_tiles);
@@ -1181,11 +1245,18 @@ bt_status bt_relu_backward_from_bitmap(const uint32_t *d_bitmap, const void *d_g
     if (misaligned(d_grad_out, 16) || misaligned(d_grad_in, 16) || misaligned(d_bitmap, 4)) return BT_ERR_ALIGN;
     hipStream_t hs = (hipStream_t)stream;
     const uint32_t blocks = (uint32_t)relu_blocks_for(n, s);
-    if (s == 4)
+    if (s == 8)
+        relu_backward_kernel<8><<<dim3(blocks), dim3(kBlock), 0, hs>>>(d_bitmap, d_grad_out, n, d_grad_in);
+    else if (s == 4)
         relu_backward_kernel<4><<<dim3(blocks), dim3(kBlock), 0, hs>>>(d_bitmap, d_grad_out, n, d_grad_in);
     else
         relu_backward_kernel<2><<<dim3(blocks), dim3(kBlock), 0, hs>>>(d_bitmap, d_grad_out, n, d_grad_in);
     return launched();
+}
+
+bt_status bt_mask_apply(const uint32_t *d_bitmap, const void *d_in, uint64_t n, bt_dtype dtype, void *d_out,
+                        bt_stream stream) {
+    return bt_relu_backward_from_bitmap(d_bitmap, d_in, n, dtype, d_out, stream);
 }
 
 size_t bt_batch_workspace_bytes(const uint64_t *n, size_t count, bt_dtype dtype) {
@@ -1229,7 +1300,8 @@ bt_status bt_compress_batch(const bt_compress_item *items, size_t count, bt_dtyp
             b.nnz[i] = it.d_nnz;
         }
         const dim3 grid(b.lay.start[c] + 1), block(kBlock);
-        if (s == 4) compress_batch_kernel<4><<<grid, block, 0, hs>>>(b, ws);
+        if (s == 8) compress_batch_kernel<8><<<grid, block, 0, hs>>>(b, ws);
+        else if (s == 4) compress_batch_kernel<4><<<grid, block, 0, hs>>>(b, ws);
         else compress_batch_kernel<2><<<grid, block, 0, hs>>>(b, ws);
         const bt_status ls = launched();
         if (ls != BT_OK) return ls;
@@ -1267,7 +1339,8 @@ bt_status bt_decompress_batch(const bt_decompress_item *items, size_t count, bt_
             b.out[i] = it.d_out;
         }
         const dim3 grid(b.lay.start[c] + 1), block(kBlock);
-        if (s == 4) decompress_batch_kernel<4><<<grid, block, 0, hs>>>(b, ws);
+        if (s == 8) decompress_batch_kernel<8><<<grid, block, 0, hs>>>(b, ws);
+        else if (s == 4) decompress_batch_kernel<4><<<grid, block, 0, hs>>>(b, ws);
         else decompress_batch_kernel<2><<<grid, block, 0, hs>>>(b, ws);
         const bt_status ls = launched();
         if (ls != BT_OK) return ls;

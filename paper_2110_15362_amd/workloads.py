@@ -21,7 +21,7 @@ _T_ABS = {0.5: 0.6744897501960817, 0.7: 1.0364333894937898, 0.9: 1.6448536269514
 # One-sided: P(x < t) = 0.7.
 _T_70 = 0.5244005127080407
 
-DTYPES = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+DTYPES = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "f64": torch.float64}
 _BITS = {torch.float32: torch.int32, torch.float16: torch.int16, torch.bfloat16: torch.int16,
          torch.float64: torch.int64}
 _NP_BITS = {4: np.uint32, 2: np.uint16, 8: np.uint64}
@@ -126,16 +126,25 @@ def config5(zero_prob, batch=None, draws=None):
 def random_sparse(n, dtype, zero_frac, seed):
     """Flat tensor of n elements, i.i.d. zeros with probability zero_frac."""
     g = _gen(seed)
-    x = torch.randn(n, generator=g)
+    dt = DTYPES[dtype] if isinstance(dtype, str) else dtype
+    # doubles are drawn as doubles, so that all 64 bits of an element vary
+    x = torch.randn(n, generator=g, dtype=torch.float64 if dt == torch.float64 else torch.float32)
     u = torch.rand(n, generator=g)
     x[u < zero_frac] = 0.0
-    return x.to(DTYPES[dtype] if isinstance(dtype, str) else dtype)
+    return x.to(dt)
 
 
 def special_values(dtype):
     """A short tensor of the awkward bit patterns: +0, -0, smallest denormal, NaNs
     with payloads, infinities, largest finite, interleaved with zeros."""
     dt = DTYPES[dtype] if isinstance(dtype, str) else dtype
+    if dt == torch.float64:
+        pats = [0x0000000000000000, 0x8000000000000000, 0x0000000000000001, 0x8000000000000001,
+                0x7FF8000000000000, 0xFFF8000000000001, 0x7FF0000000000001, 0x7FF0000000000000,
+                0xFFF0000000000000, 0x7FEFFFFFFFFFFFFF, 0x0000000000000000, 0x3FF0000000000000,
+                0x0000000000000000, 0x0000000000000000, 0xBFF0000000000000, 0x0000000100000000]
+        a = np.array(pats, dtype=np.uint64).view(np.int64)
+        return torch.from_numpy(a.copy()).view(torch.float64)
     if dt == torch.float32:
         pats = [0x00000000, 0x80000000, 0x00000001, 0x80000001, 0x7FC00000, 0xFFC00001,
                 0x7F800001, 0x7F800000, 0xFF800000, 0x7F7FFFFF, 0x00000000, 0x3F800000,

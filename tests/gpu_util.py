@@ -48,7 +48,7 @@ def gpu_decompress(bitmap_np, values_np, n, dtype, ws=None, values_offset=0, dev
     """bitmap_np uint32[W], values_np raw bits -> restored tensor bits; also checks the guard after out."""
     words = (n + 31) // 32
     bitmap = torch.from_numpy(bitmap_np.view(np.int32).copy()).to(dev)
-    vb = torch.from_numpy(values_np.view({2: np.int16, 4: np.int32}[values_np.itemsize]).copy()).view(dtype)
+    vb = torch.from_numpy(values_np.view({2: np.int16, 4: np.int32, 8: np.int64}[values_np.itemsize]).copy()).view(dtype)
     vbuf = _sentinel(vb.numel() + values_offset + 8, dtype, dev)
     vbuf[values_offset:values_offset + vb.numel()] = vb.to(dev)
     values = vbuf[values_offset:values_offset + vb.numel()]
@@ -64,7 +64,9 @@ def gpu_decompress(bitmap_np, values_np, n, dtype, ws=None, values_offset=0, dev
     return ob[:n].copy(), bool((ob[n:] == sent).all())
 
 
-def gpu_relu_backward(bitmap_np, g, inplace=False, dev="cuda"):
+def gpu_relu_backward(bitmap_np, g, inplace=False, dev="cuda", call=None):
+    """`call` is the binding function to run: bt_relu_backward_from_bitmap unless given."""
+    call = call or bt.bt_relu_backward_from_bitmap
     g = g.contiguous().reshape(-1)
     n = g.numel()
     bitmap = torch.from_numpy(bitmap_np.view(np.int32).copy()).to(dev)
@@ -72,11 +74,11 @@ def gpu_relu_backward(bitmap_np, g, inplace=False, dev="cuda"):
     gbuf = _sentinel(n + pad, g.dtype, dev)
     gbuf[:n] = g.to(dev)
     if inplace:
-        bt.bt_relu_backward_from_bitmap(bitmap, gbuf[:n], gbuf[:n])
+        call(bitmap, gbuf[:n], gbuf[:n])
         obuf = gbuf
     else:
         obuf = _sentinel(n + pad, g.dtype, dev)
-        bt.bt_relu_backward_from_bitmap(bitmap, gbuf[:n], obuf[:n])
+        call(bitmap, gbuf[:n], obuf[:n])
     torch.cuda.synchronize()
     ob = wl.bits(obuf.cpu())
     sent = np.frombuffer(bytes([SENTINEL] * ob.itemsize), dtype=ob.dtype)[0]

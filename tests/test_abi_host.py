@@ -29,7 +29,8 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported(bt):
     names = _declared_functions()
     assert {"bt_compress", "bt_compressed_size", "bt_decompress", "bt_relu_backward_from_bitmap",
-            "bt_compress_pruned", "bt_compress_batch", "bt_decompress_batch", "bt_batch_workspace_bytes"} <= set(names)
+            "bt_compress_pruned", "bt_compress_batch", "bt_decompress_batch", "bt_batch_workspace_bytes",
+            "bt_mask_apply", "bt_dense_size", "bt_coo_size"} <= set(names)
     raw = ctypes.CDLL(bt.LIB_PATH)
     for name in names:
         assert hasattr(raw, name), name
@@ -61,7 +62,7 @@ def test_compressed_size_matches_table1(bt):
 def test_size_helpers(bt, oracle):
     for n in (0, 1, 31, 32, 33, 4096, 25690112):
         assert bt.bt_bitmap_bytes(n) == 4 * ((n + 31) // 32)
-        for code, width in ((bt.BT_F32, 4), (bt.BT_F16, 2), (bt.BT_BF16, 2)):
+        for code, width in ((bt.BT_F32, 4), (bt.BT_F16, 2), (bt.BT_BF16, 2), (bt.BT_F64, 8)):
             for nnz in (0, n // 3, n):
                 assert bt.bt_compressed_size(n, nnz, code) == oracle.compressed_size(n, nnz, width)
             assert bt.lib().bt_dtype_size(code) == width
@@ -109,7 +110,7 @@ def test_argument_errors_are_found_on_the_host(bt):
     def relu(bm=A, g=A, n=1000, dt=bt.BT_BF16, gi=A):
         return L.bt_relu_backward_from_bitmap(bm, g, n, dt, gi, None)
 
-    assert relu(dt=3) == 2
+    assert relu(dt=4) == 2
     assert relu(bm=None) == 1 and relu(g=None) == 1 and relu(gi=None) == 1
     assert relu(g=A + 2) == 3 and relu(gi=A + 8) == 3 and relu(bm=A + 1) == 3
     assert relu(n=0, bm=None, g=None, gi=None) == 0
@@ -184,6 +185,49 @@ def test_batch_workspace_bytes_and_host_errors(bt):
     assert L.bt_decompress_batch(None, 0, f32, None, 0, None) == 0
 
 
+def test_dense_and_coo_sizes_match_the_oracle(bt, oracle):
+    for code, width in ((bt.BT_F32, 4), (bt.BT_F16, 2), (bt.BT_BF16, 2), (bt.BT_F64, 8)):
+        for n in (0, 1, 33, 3211264, 25690112):
+            assert bt.bt_dense_size(n, code) == oracle.dense_size(n, width)
+            for ndim in (1, 2, 3, 4):
+                for ib in (4, 8):
+                    assert bt.bt_coo_size(n // 3, ndim, ib, code) == oracle.coo_size(n // 3, ndim, ib, width)
+    assert bt.bt_dense_size(10, 9) == 0
+    assert bt.bt_coo_size(10, 0, 4, bt.BT_F32) == 0 and bt.bt_coo_size(10, 4, 2, bt.BT_F32) == 0
+    assert bt.bt_coo_size(10, 4, 4, 9) == 0
+    L = bt.lib()
+    A = 0x10000
+    assert L.bt_mask_apply(None, A, 10, bt.BT_F32, A, None) == 1
+    assert L.bt_mask_apply(A, A + 4, 10, bt.BT_F32, A, None) == 3
+    assert L.bt_mask_apply(A, A, 10, 7, A, None) == 2
+    assert L.bt_mask_apply(None, None, 0, bt.BT_F32, None, None) == 0
+
+
+def test_footprint_calculator_reproduces_table1_and_the_coo_break_even(bt):
+    import torch
+    from paper_2110_15362_amd import footprint as fp
+    golden = os.path.join(ROOT, "tests", "golden", "table1_theoretical.txt")
+    rows = 0
+    for line in open(golden):
+        if line.startswith("#") or not line.strip():
+            continue
+        b, c, w, h, n, pct, dense_mb, bitmap_mb, improv = line.split()
+        r = fp.footprint((int(b), int(c), int(w), int(h)), int(pct) / 100.0)
+        assert r["elements"] == int(n)
+        assert abs(r["dense_bytes"] / 2**20 - float(dense_mb)) <= 0.005 + 1e-9
+        assert abs(r["bitmap_bytes"] / 2**20 - float(bitmap_mb)) <= 0.005 + 1e-9
+        assert abs(r["bitmap_improvement_pct"] - float(improv)) <= 0.005 + 1e-9
+        rows += 1
+    assert rows == 30
+    # Section 3.2: COO pays off only at about 20 % non-zeros or fewer (4-D activation, integer indices)
+    be = fp.break_even_nonzero_fraction(4, 4)
+    assert be["coo_vs_dense"] == 0.2 and be["bitmap_vs_dense"] == 31 / 32
+    sw = fp.sweep((16, 64, 56, 56), fractions=(0.1, 0.2, 0.3, 0.9))
+    assert sw[0]["coo_int_bytes"] < sw[0]["dense_bytes"] and sw[2]["coo_int_bytes"] > sw[2]["dense_bytes"]
+    assert all(r["bitmap_bytes"] < r["dense_bytes"] and r["bitmap_bytes"] < r["coo_int_bytes"] for r in sw)
+    assert fp.footprint((8, 2048, 4096), 0.35, torch.bfloat16)["bitmap_bytes"] == 2 * int(8 * 2048 * 4096 * 0.35) + 8 * 2048 * 4096 // 8
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
@@ -194,7 +238,7 @@ def test_bench_refuses_more_than_one_gpu():
 
 def test_workspace_bytes_cover_every_tile(bt):
     # 256-byte header + one 768-byte record per 32 tiles of 32 KiB of dense data
-    for code, elems_per_tile in ((bt.BT_F32, 8192), (bt.BT_F16, 16384), (bt.BT_BF16, 16384)):
+    for code, elems_per_tile in ((bt.BT_F32, 8192), (bt.BT_F16, 16384), (bt.BT_BF16, 16384), (bt.BT_F64, 4096)):
         for tiles in (1, 32, 33, 3136, 100000):
             n = tiles * elems_per_tile
             assert bt.bt_workspace_bytes(n, code) == 256 + 768 * ((tiles + 31) // 32)

@@ -10,7 +10,7 @@ from paper_2110_15362_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 SENT = 0x5A
-TILE = {4: 8192, 2: 16384}
+TILE = {4: 8192, 2: 16384, 8: 4096}
 
 
 @pytest.fixture(scope="module")
@@ -62,7 +62,7 @@ def _decompress_batch(bt, comp, ns, dt, ws):
     """comp: per tensor (bitmap uint32, values bits); returns the restored bits per tensor."""
     pad = 16 // torch.empty(0, dtype=dt).element_size()
     bms = [torch.from_numpy(b.view(np.int32).copy()).cuda() for b, _ in comp]
-    vals = [torch.from_numpy(v.view({2: np.int16, 4: np.int32}[v.itemsize]).copy()).view(dt).cuda() for _, v in comp]
+    vals = [torch.from_numpy(v.view({2: np.int16, 4: np.int32, 8: np.int64}[v.itemsize]).copy()).view(dt).cuda() for _, v in comp]
     obufs = [_sentinel(n + pad, dt) for n in ns]
     items = bt.decompress_items(bms, vals, [o[:n] for o, n in zip(obufs, ns)])
     bt.bt_decompress_batch(items, len(ns), dt, ws)
@@ -101,9 +101,9 @@ def _mixed_sizes(width):
     return [0, 1, 33, t - 1, t, t + 1, 3 * t + 17, 64 * t, 0, 64 * t + 1, 65 * t - 5, 130 * t + 1234, 7]
 
 
-@pytest.mark.parametrize("dt", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("dt", ["f32", "f16", "bf16", "f64"])
 def test_batch_mixed_sizes(bt, oracle, dt):
-    width = 4 if dt == "f32" else 2
+    width = {"f32": 4, "f16": 2, "bf16": 2, "f64": 8}[dt]
     xs = [wl.random_sparse(n, dt, 0.1 + 0.07 * (k % 12), 300 + k) for k, n in enumerate(_mixed_sizes(width))]
     _check_batch(bt, oracle, xs)
 

@@ -10,8 +10,8 @@ from paper_2110_15362_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-DTYPES = ["f32", "f16", "bf16"]
-# tile = 4096 fp32 / 8192 16-bit elements; wave strip = 1024 / 2048; row = 256 / 512
+DTYPES = ["f32", "f16", "bf16", "f64"]
+# tile = 8192 fp32 / 16384 16-bit / 4096 fp64 elements; wave strip = a quarter of it; row = 256 / 512 / 128
 SIZES = [1, 3, 4, 5, 7, 8, 9, 31, 32, 33, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1023, 1024, 1025, 2047, 2049,
          4095, 4096, 4097, 8191, 8192, 8193, 12305, 16384, 3 * 8192 + 17, 100003, 5 * 8192, 1000000 + 37]
 
@@ -135,11 +135,11 @@ def test_workspace_reuse_across_calls_and_sizes(gpu, oracle):
     assert hdr[2] == 0           # no tile ever gave up waiting for another tile's count
 
 
-@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("dt", ["f32", "bf16", "f64"])
 def test_tile_record_and_scan_window_boundaries(gpu, oracle, dt):
     """Sizes around the bookkeeping granularities: a tile (8192 fp32 / 16384 16-bit elements), a
     workspace record (32 tiles), a scanner row (64 tiles) and a scanner pass (512 tiles)."""
-    tile = 8192 if dt == "f32" else 16384
+    tile = {"f32": 8192, "bf16": 16384, "f64": 4096}[dt]
     sizes = []
     for tiles in (1, 31, 32, 33, 63, 64, 65, 511, 512, 513, 1025):
         sizes += [tiles * tile - 1, tiles * tile, tiles * tile + 1]
@@ -314,7 +314,7 @@ def test_compress_pruned_thresholds_and_tails(gpu, oracle, dt):
             o_bitmap, o_values, o_nnz = _check_compress_pruned(gpu, oracle, x, dt, thr)
         # decompressing the threshold-0 form gives ReLU(x) bit for bit (ReLU(-0.0) = +0 here)
         o_bitmap, o_values, o_nnz = oracle.compress_pruned(wl.bits(x), dt, 0.0)
-        relu_bits = wl.bits(torch.where(x.float() > 0, x, torch.zeros_like(x)))
+        relu_bits = wl.bits(torch.where(x.double() > 0, x, torch.zeros_like(x)))
         _check_decompress(gpu, oracle, o_bitmap, o_values, n, x.dtype, relu_bits)
 
 
@@ -323,7 +323,7 @@ def test_compress_pruned_special_values(gpu, oracle, dt):
     """Denormals, -0.0, infinities and NaNs against thresholds that are themselves tiny:
     the comparison is the IEEE single-precision one on both sides."""
     x = wl.special_values(dt).repeat(1100)[:17000]
-    tiny = {"f32": 1e-45, "f16": 6e-8, "bf16": 1e-40}[dt]
+    tiny = {"f32": 1e-45, "f16": 6e-8, "bf16": 1e-40, "f64": 1e-45}[dt]
     for thr in (0.0, tiny, -tiny, 1.0, float("-inf"), float("nan")):
         _check_compress_pruned(gpu, oracle, x, dt, thr)
 
@@ -333,3 +333,21 @@ def test_compress_pruned_config2_full_size(gpu, oracle):
     for thr in (0.0, 0.1):
         o_bitmap, o_values, o_nnz = _check_compress_pruned(gpu, oracle, x, "f32", thr)
         assert abs(o_nnz / x.numel() - (0.5 if thr == 0.0 else 0.4602)) < 2e-3
+
+
+@pytest.mark.parametrize("dt", DTYPES)
+def test_mask_apply_with_a_foreign_bitmap(gpu, oracle, dt):
+    """Double mask: the bitmap of one tensor (a normalisation layer's input) applied to another
+    (its output); out of place and in place; the result compresses to the same bitmap."""
+    import paper_2110_15362_amd.bittrain as bt
+    for k, n in enumerate((1, 33, 8191, 8193, 3 * 16384 + 5, 1000003)):
+        src = wl.random_sparse(n, dt, 0.6, 900 + k)
+        y = torch.randn(n, generator=torch.Generator().manual_seed(950 + k)).to(src.dtype)   # dense, like a BN output
+        bitmap, _, nnz = oracle.compress(wl.bits(src))
+        want = oracle.mask_apply(bitmap, wl.bits(y))
+        for inplace in (False, True):
+            out, ok = gpu.gpu_relu_backward(bitmap, y, inplace=inplace, call=bt.bt_mask_apply)
+            assert ok and np.array_equal(out, want), (n, inplace)
+        got_bitmap, _, got_nnz, ok = gpu.gpu_compress(torch.from_numpy(want.view({2: np.int16, 4: np.int32, 8: np.int64}[want.itemsize])).view(src.dtype))
+        y_nonzero_under_mask = int(((wl.bits(y) != 0) & (wl.bits(src) != 0)).sum())
+        assert ok and got_nnz == y_nonzero_under_mask and got_nnz <= nnz

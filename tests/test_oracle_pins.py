@@ -336,3 +336,24 @@ def test_mask_apply_special_cases(oracle):
     g = np.arange(1, 71, dtype=np.uint16)
     bm = np.array([0xDEADBEEF, 0x12345678, 0x2A], dtype=np.uint32)
     assert np.array_equal(oracle.mask_apply(bm, g), oracle.relu_backward(bm, g))
+
+
+def test_prune_fp64_against_numpy_and_special_values(oracle):
+    """Double-precision elements: kept where the double exceeds the threshold widened to double."""
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal(5000)
+    x[::7] = 0.0
+    specials = np.array([0.0, -0.0, 5e-324, -5e-324, np.nan, np.inf, -np.inf, 0.01, np.float64(np.float32(0.01)),
+                         np.nextafter(np.float64(np.float32(0.01)), 1.0), 1.7976931348623157e308], dtype=np.float64)
+    x = np.concatenate([specials, x])
+    for thr in (0.0, 0.01, 0.05, 0.1, -1.0, float("inf"), float("-inf")):
+        t = np.float64(np.float32(thr))
+        with np.errstate(invalid="ignore"):
+            want = np.where(x > t, x, 0.0).view(np.uint64)
+        want = np.where(x > t, x.view(np.uint64), 0).astype(np.uint64)     # kept elements keep their bits
+        got = oracle.prune(x.view(np.uint64), "f64", thr)
+        assert np.array_equal(got, want), thr
+    # the threshold is the single-precision number: 0.01f is a little below 0.01, so the double 0.01 survives it
+    got = oracle.prune(specials.view(np.uint64), "f64", 0.01).view(np.float64)
+    assert got[7] == 0.01 and got[8] == 0.0 and got[9] > 0.0
+    assert oracle.prune(specials.view(np.uint64), "f64", float("nan")).any() == False
