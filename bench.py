@@ -95,6 +95,36 @@ def other_configs(bt, wl, torch, dev, timed, args):
                      "relu_backward_roofline_frac": round((2 * n * s + 4 * words) / tr / 1e3 / HBM_PEAK_GBPS, 4)})
 
     one("1: fp32 [1,64,56,56] relu(randn) (launch-latency bound)", wl.config1()["x"], 64, 200)
+
+    # configuration 1 again, the three calls captured once in a HIP graph and replayed: what is left
+    # of the launch cost when the host is out of the loop
+    x = wl.config1()["x"].reshape(-1).to(dev)
+    n = x.numel()
+    bitmap = torch.empty((n + 31) // 32, dtype=torch.int32, device=dev)
+    values, out, gin = torch.empty_like(x), torch.empty_like(x), torch.empty_like(x)
+    nnz_d = torch.zeros(1, dtype=torch.int64, device=dev)
+    ws = bt.new_workspace(n, x.dtype, device=dev)
+
+    def step1():
+        bt.bt_compress(x, bitmap, values, nnz_d, ws)
+        bt.bt_decompress(bitmap, values, out, ws)
+        bt.bt_relu_backward_from_bitmap(bitmap, x, gin)
+
+    t_eager = timed(lambda i: step1(), 200, 10)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step1()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step1()
+    t_graph = timed(lambda i: graph.replay(), 200, 10)
+    assert torch.equal(out.view(torch.int32), x.view(torch.int32)), "round trip mismatch under graph replay"
+    rows.append({"config": "1: the step (compress + decompress + ReLU backward) eager and as one captured HIP graph",
+                 "n": n, "step_us_eager": round(t_eager, 2), "step_us_graph_replay": round(t_graph, 2)})
+    del x, bitmap, values, out, gin
     one("3a: bf16 [8,2048,4096] dead feature columns", wl.config3("a")["x"], 8, 50)
     one("3b: bf16 [8,2048,4096] dead rows (whole empty tiles)", wl.config3("b")["x"], 8, 50)
     draws = None
