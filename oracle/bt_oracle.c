@@ -35,6 +35,10 @@
  * bt_oracle_mask_apply: out[i] = x[i] where the other tensor's bitmap has bit i set, +0
  * elsewhere -- the same select as the ReLU backward, stated on its own.
  *
+ * bt_oracle_tile_index is Algorithm 2's counter j sampled at regular positions: entry t
+ * is the value j has when the loop reaches element t * tile_elems, i.e. the number of
+ * values consumed before that element.  With it Algorithm 2 can start anywhere.
+ *
  * Parity pins (tests/test_oracle_*.py): the theoretical columns of Table 1,
  * hand-built tensors, numpy.packbits / boolean indexing, enumeration of all
  * 2^16 zero patterns of a 16-element tensor, every n in [0,130], closed forms
@@ -230,4 +234,18 @@ int bt_oracle_mask_apply(const uint32_t *bitmap, const void *x, uint64_t n, int 
             store_bits(dst, i, width, 0);
     }
     return 0;
+}
+
+/* Algorithm 2's counter j at the start of every block of tile_elems elements:
+ * index[t] = number of set bits among bits [0, min(t * tile_elems, n)).  Writes
+ * ceil(n / tile_elems) entries and returns that number (0 when tile_elems is 0). */
+uint64_t bt_oracle_tile_index(const uint32_t *bitmap, uint64_t n, uint64_t tile_elems, uint64_t *index)
+{
+    if (tile_elems == 0) return 0;
+    uint64_t j = 0, tiles = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        if (i % tile_elems == 0) index[tiles++] = j;      /* j before element i */
+        if ((bitmap[i / 32] >> (i % 32)) & 1u) j += 1;    /* Algorithm 2: a set bit consumes a value */
+    }
+    return tiles;
 }

@@ -47,6 +47,8 @@ def _load():
         lib.bt_oracle_coo_size.argtypes = [u64, ci, ci, ci]
         lib.bt_oracle_mask_apply.restype = ci
         lib.bt_oracle_mask_apply.argtypes = [vp, vp, u64, ci, vp]
+        lib.bt_oracle_tile_index.restype = u64
+        lib.bt_oracle_tile_index.argtypes = [vp, u64, u64, vp]
         _lib = lib
     return _lib
 
@@ -144,3 +146,14 @@ def mask_apply(bitmap, x):
     rc = _load().bt_oracle_mask_apply(_ptr(bitmap), _ptr(x), n, x.dtype.itemsize, _ptr(out))
     assert rc == 0
     return out
+
+
+def tile_index(bitmap, n, tile_elems):
+    """Algorithm 2's counter j at elements 0, tile_elems, 2 * tile_elems, ...: uint64[ceil(n / tile_elems)]."""
+    bitmap = np.ascontiguousarray(bitmap, dtype=np.uint32)
+    assert bitmap.size == (n + 31) // 32 and tile_elems > 0
+    tiles = (n + tile_elems - 1) // tile_elems
+    index = np.full(tiles + 1, 0xA5A5A5A5A5A5A5A5, dtype=np.uint64)
+    wrote = int(_load().bt_oracle_tile_index(_ptr(bitmap), n, tile_elems, _ptr(index)))
+    assert wrote == tiles and index[tiles] == 0xA5A5A5A5A5A5A5A5
+    return index[:tiles].copy()

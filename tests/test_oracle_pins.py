@@ -357,3 +357,40 @@ def test_prune_fp64_against_numpy_and_special_values(oracle):
     got = oracle.prune(specials.view(np.uint64), "f64", 0.01).view(np.float64)
     assert got[7] == 0.01 and got[8] == 0.0 and got[9] > 0.0
     assert oracle.prune(specials.view(np.uint64), "f64", float("nan")).any() == False
+
+
+# ---- Algorithm 2's counter at tile boundaries ----
+
+@pytest.mark.parametrize("tile", [1, 5, 32, 33, 64, 4096])
+def test_tile_index_is_the_prefix_count_at_tile_starts(oracle, tile):
+    rng = np.random.default_rng(31)
+    for n in (0, 1, 31, 32, 33, 100, 4095, 4096, 4097, 10000):
+        x = (rng.integers(1, 2**31, size=n) * (rng.random(n) < 0.35)).astype(np.uint32)
+        bitmap, values, nnz = oracle.compress(x)
+        index = oracle.tile_index(bitmap, n, tile)
+        tiles = (n + tile - 1) // tile
+        assert index.size == tiles
+        # numpy: cumulative count of non-zeros before each tile start
+        before = np.concatenate([[0], np.cumsum(x != 0)])
+        assert np.array_equal(index, before[np.arange(tiles) * tile].astype(np.uint64))
+        # what it is for: the values of tile t are values[index[t] : index[t+1]], so Algorithm 2 can start at any tile
+        ends = np.append(index[1:], nnz) if tiles else np.array([], dtype=np.uint64)
+        for t in range(0, tiles, max(1, tiles // 7)):
+            lo, hi = t * tile, min((t + 1) * tile, n)
+            chunk = x[lo:hi]
+            assert np.array_equal(values[int(index[t]):int(ends[t])], chunk[chunk != 0])
+            if lo % 32 == 0 and tile % 32 == 0:
+                # restarting Algorithm 2 at element lo with j = index[t] restores exactly that tile
+                part = oracle.decompress(bitmap[lo // 32:(hi + 31) // 32], values[int(index[t]):int(ends[t])], hi - lo)
+                assert np.array_equal(part, chunk)
+
+
+def test_tile_index_hand_built_and_degenerate(oracle):
+    bm = np.array([0b1011, 0xFFFFFFFF, 0x0, 0x80000001], dtype=np.uint32)
+    assert oracle.tile_index(bm, 128, 32).tolist() == [0, 3, 35, 35]
+    assert oracle.tile_index(bm, 128, 64).tolist() == [0, 35]
+    assert oracle.tile_index(bm, 100, 48).tolist() == [0, 19, 35]      # bits 0..47: 3 + 16
+    assert oracle.tile_index(bm[:1], 4, 1).tolist() == [0, 1, 2, 2]
+    assert oracle.tile_index(bm[:0], 0, 32).tolist() == []
+    assert oracle.tile_index(np.zeros(4, dtype=np.uint32), 128, 32).tolist() == [0, 0, 0, 0]
+    assert oracle.tile_index(np.full(4, 0xFFFFFFFF, dtype=np.uint32), 128, 32).tolist() == [0, 32, 64, 96]
