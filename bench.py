@@ -287,12 +287,30 @@ def main():
         def step(i):
             compress(i); decompress(i); relu(i)
 
+        # the same pair with the tile index (8 bytes per tile written by compress, read by decompress);
+        # reported beside the plain calls, not part of the step
+        tiles = bt.bt_index_bytes(n, x.dtype) // 8
+        indexes = [torch.empty(tiles, dtype=torch.int64, device=dev) for _ in range(K)]
+        for k in range(K):
+            bt.bt_compress_indexed(xs[k], bitmaps[k], values[k], nnz_d, indexes[k], ws)
+        bt.bt_decompress_indexed(bitmaps[0], values[0], indexes[0], outs[0])
+        torch.cuda.synchronize()
+        assert torch.equal(outs[0].view(torch.int32), xs[0].view(torch.int32)), "round trip mismatch (indexed)"
+
+        def compress_indexed(i):
+            bt.bt_compress_indexed(xs[i % K], bitmaps[i % K], values[i % K], nnz_d, indexes[i % K], ws)
+
+        def decompress_indexed(i):
+            bt.bt_decompress_indexed(bitmaps[i % K], values[i % K], indexes[i % K], outs[i % K])
+
         row = {"sparsity": z, "n": n, "nnz": nnz, "measured_zero_fraction": round(1 - nnz / n, 5),
                "compressed_bytes": bt.bt_compressed_size(n, nnz, x.dtype), "dense_bytes": n * s,
                "compression_ratio": round(n * s / bt.bt_compressed_size(n, nnz, x.dtype), 4),
                "footprint_reduction_pct": round(100 * (1 - bt.bt_compressed_size(n, nnz, x.dtype) / (n * s)), 2)}
         for name, fn, alg in (("compress", compress, alg_codec), ("decompress", decompress, alg_codec),
-                              ("relu_backward", relu, alg_relu)):
+                              ("relu_backward", relu, alg_relu),
+                              ("compress_indexed", compress_indexed, alg_codec + 8 * tiles),
+                              ("decompress_indexed", decompress_indexed, alg_codec + 8 * tiles)):
             cold = timed(fn, args.steps, args.warmup)
             warm = cold if args.cold_only else timed(lambda i, fn=fn: fn(0), args.steps, args.warmup)
             row[name] = {"us_cold": round(cold, 2), "us_warm": round(warm, 2),
@@ -306,7 +324,7 @@ def main():
             if args.copy_calibration:
                 timed(lambda i: outs[i % K].copy_(xs[i % K]), 10, 2)
         ops.append(row)
-        del xs, gs, bitmaps, values, outs, gins
+        del xs, gs, bitmaps, values, outs, gins, indexes
 
     other = None
     if args.all_configs:

@@ -158,6 +158,42 @@ bt_status bt_decompress(const uint32_t *d_bitmap, const void *d_values, uint64_t
                         bt_dtype dtype, void *d_out,
                         void *d_workspace, size_t workspace_bytes, bt_stream stream);
 
+/* ---- Algorithm 2 without the scan: the tile index ------------------------------
+ *
+ * Algorithm 2 carries one counter, j, the position in d_values of the next value.
+ * bt_decompress has to find j for every tile of the tensor by a scan over the whole
+ * bitmap before a tile can fetch its values.  bt_compress knows these numbers when it
+ * writes the values: bt_compress_indexed also leaves them in d_index, entry t being j
+ * at element t * bt_tile_elems(dtype) (the number of values stored before that
+ * element), and bt_decompress_indexed starts every tile from its entry: no workspace,
+ * no dependency between tiles.  The index is 8 bytes per 32 KiB of dense data, derived
+ * from the bitmap alone; the compressed form proper (bitmap, values, nnz) is unchanged. */
+
+/* Elements per tile: 32 KiB / sizeof(dtype).  0 for an unknown dtype. */
+size_t bt_tile_elems(bt_dtype dtype);
+
+/* Bytes d_index must hold: 8 * ceil(n / bt_tile_elems(dtype)). */
+size_t bt_index_bytes(uint64_t n, bt_dtype dtype);
+
+/* bt_compress, plus d_index (8-byte aligned, bt_index_bytes(n, dtype) bytes; every entry
+ * is written).  Everything else as bt_compress. */
+bt_status bt_compress_indexed(const void *d_in, uint64_t n, bt_dtype dtype,
+                              uint32_t *d_bitmap, void *d_values, uint64_t values_cap,
+                              uint64_t *d_nnz, uint64_t *d_index,
+                              void *d_workspace, size_t workspace_bytes, bt_stream stream);
+
+/* Algorithm 2 with j taken from the tile index.
+ *   d_values, values_cap   the stored values and how many elements d_values holds (at
+ *                          least the number of set bits, for a correct result); nothing at
+ *                          or beyond values_cap is read, whatever d_index says.
+ *   d_index                as written by bt_compress_indexed for this bitmap.  Entries that
+ *                          do not belong to the bitmap give a wrong d_out, never an access
+ *                          outside the buffers.
+ * d_bitmap, d_out, alignment and errors as bt_decompress (no workspace errors). */
+bt_status bt_decompress_indexed(const uint32_t *d_bitmap, const void *d_values, uint64_t values_cap,
+                                const uint64_t *d_index, uint64_t n, bt_dtype dtype, void *d_out,
+                                bt_stream stream);
+
 /* Backward of y = ReLU(x) from the bitmap of y alone.  Algorithm 1 sets bit i
  * exactly where y[i] != 0, i.e. where x[i] > 0, which is the ReLU derivative, so
  * the values array is not needed:

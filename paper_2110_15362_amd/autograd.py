@@ -8,7 +8,9 @@ Two pieces, both thin: every byte of codec work is done by libbittrain's kernels
   saved activation runs ``bt_compress`` into a reusable worst-case scratch buffer, reads
   nnz (one host synchronisation per tensor: that is the price of right-sizing) and keeps
   only ``values[:nnz]`` and the bitmap; if that is not smaller than the dense tensor the
-  tensor is kept as it is.  Unpacking runs ``bt_decompress``.  The round trip is
+  tensor is kept as it is.  Packing also keeps the tile index (8 bytes per 32 KiB of
+  dense data) that compression produces on the way, so unpacking runs
+  ``bt_decompress_indexed``, which needs no scan over the bitmap.  The round trip is
   bit-exact, so gradients are identical to those of the unhooked graph.
 * ``bitmap_relu`` -- a ReLU whose backward is served by
   ``bt_relu_backward_from_bitmap`` and which saves nothing but the bitmap of its output
@@ -18,7 +20,7 @@ import torch
 
 from . import bittrain as bt
 
-_SUPPORTED = (torch.float32, torch.float16, torch.bfloat16)
+_SUPPORTED = (torch.float32, torch.float16, torch.bfloat16, torch.float64)
 
 
 class _DeviceState:
@@ -57,10 +59,11 @@ def _state(device):
 
 
 class _Packed:
-    __slots__ = ("bitmap", "values", "shape", "dtype", "device")
+    __slots__ = ("bitmap", "values", "index", "shape", "dtype", "device")
 
-    def __init__(self, bitmap, values, shape, dtype, device):
-        self.bitmap, self.values, self.shape, self.dtype, self.device = bitmap, values, shape, dtype, device
+    def __init__(self, bitmap, values, index, shape, dtype, device):
+        self.bitmap, self.values, self.index = bitmap, values, index
+        self.shape, self.dtype, self.device = shape, dtype, device
 
 
 class BitmapStash(torch.autograd.graph.saved_tensors_hooks):
@@ -84,22 +87,23 @@ class BitmapStash(torch.autograd.graph.saved_tensors_hooks):
         self.stats["tensors"] += 1
         self.stats["dense_bytes"] += n * t.element_size()
         bitmap = torch.empty((n + 31) // 32, dtype=torch.int32, device=t.device)
+        index = torch.empty(bt.bt_index_bytes(n, t.dtype) // 8, dtype=torch.int64, device=t.device)
         scratch = st.value_scratch(n, t.dtype)
-        bt.bt_compress(t.detach(), bitmap, scratch, st.nnz, st.workspace(n, t.dtype))
+        bt.bt_compress_indexed(t.detach(), bitmap, scratch, st.nnz, index, st.workspace(n, t.dtype))
         nnz = int(st.nnz.item())                                   # host sync: needed to right-size
-        if bt.bt_compressed_size(n, nnz, t.dtype) >= n * t.element_size():
+        stored = bt.bt_compressed_size(n, nnz, t.dtype) + 8 * index.numel()    # M_b plus the tile index
+        if stored >= n * t.element_size():
             self.stats["stored_bytes"] += n * t.element_size()
             return t                                               # too dense: the bitmap form would be larger
         self.stats["compressed"] += 1
-        self.stats["stored_bytes"] += bt.bt_compressed_size(n, nnz, t.dtype)
-        return _Packed(bitmap, scratch[:nnz].clone(), t.shape, t.dtype, t.device)
+        self.stats["stored_bytes"] += stored
+        return _Packed(bitmap, scratch[:nnz].clone(), index, t.shape, t.dtype, t.device)
 
     def _unpack(self, obj):
         if not isinstance(obj, _Packed):
             return obj
-        st = _state(obj.device)
         out = torch.empty(obj.shape, dtype=obj.dtype, device=obj.device)
-        bt.bt_decompress(obj.bitmap, obj.values, out, st.workspace(out.numel(), obj.dtype))
+        bt.bt_decompress_indexed(obj.bitmap, obj.values, obj.index, out)
         return out
 
 
@@ -108,7 +112,7 @@ class _BitmapReLU(torch.autograd.Function):
     def forward(ctx, x):
         y = torch.relu(x)
         if not (y.is_cuda and y.dtype in _SUPPORTED and y.is_contiguous()):
-            raise TypeError("bitmap_relu needs a contiguous float32/float16/bfloat16 device tensor")
+            raise TypeError("bitmap_relu needs a contiguous float64/float32/float16/bfloat16 device tensor")
         st = _state(y.device)
         n = y.numel()
         bitmap = torch.empty((n + 31) // 32, dtype=torch.int32, device=y.device)

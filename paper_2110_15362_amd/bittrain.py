@@ -69,6 +69,12 @@ def lib():
         L.bt_coo_size.restype, L.bt_coo_size.argtypes = sz, [u64, ctypes.c_uint32, ctypes.c_uint32, ci]
         L.bt_mask_apply.restype = ci
         L.bt_mask_apply.argtypes = [vp, vp, u64, ci, vp, vp]
+        L.bt_tile_elems.restype, L.bt_tile_elems.argtypes = sz, [ci]
+        L.bt_index_bytes.restype, L.bt_index_bytes.argtypes = sz, [u64, ci]
+        L.bt_compress_indexed.restype = ci
+        L.bt_compress_indexed.argtypes = [vp, u64, ci, vp, vp, u64, vp, vp, vp, sz, vp]
+        L.bt_decompress_indexed.restype = ci
+        L.bt_decompress_indexed.argtypes = [vp, vp, u64, vp, u64, ci, vp, vp]
         L.bt_batch_workspace_bytes.restype = sz
         L.bt_batch_workspace_bytes.argtypes = [ctypes.POINTER(u64), sz, ci]
         L.bt_compress_batch.restype = ci
@@ -285,3 +291,44 @@ def bt_mask_apply(bitmap, x, out, stream=None):
         raise ValueError("bitmap must hold ceil(n/32) 32-bit words")
     _check("bt_mask_apply", lib().bt_mask_apply(_ptr(bitmap), _ptr(x), x.numel(), dtype_code(x.dtype), _ptr(out),
                                                 _stream(stream)))
+
+
+def bt_tile_elems(dtype):
+    return int(lib().bt_tile_elems(_code(dtype)))
+
+
+def bt_index_bytes(n, dtype):
+    return int(lib().bt_index_bytes(n, _code(dtype)))
+
+
+def bt_compress_indexed(x, bitmap, values, nnz, index, workspace, stream=None):
+    """bt_compress that also leaves the tile index (int64[ceil(n / bt_tile_elems)]) for bt_decompress_indexed."""
+    for t, name in ((x, "x"), (bitmap, "bitmap"), (values, "values"), (nnz, "nnz"), (index, "index"),
+                    (workspace, "workspace")):
+        _dev(t, name)
+    if values.dtype != x.dtype:
+        raise TypeError("values must have the dtype of x")
+    if bitmap.element_size() != 4 or bitmap.numel() * 4 < bt_bitmap_bytes(x.numel()):
+        raise ValueError("bitmap must hold ceil(n/32) 32-bit words")
+    if nnz.element_size() != 8 or nnz.numel() < 1:
+        raise ValueError("nnz must be one 64-bit integer")
+    if index.element_size() != 8 or index.numel() * 8 < bt_index_bytes(x.numel(), x.dtype):
+        raise ValueError("index must hold one 64-bit integer per tile")
+    _check("bt_compress_indexed", lib().bt_compress_indexed(
+        _ptr(x), x.numel(), dtype_code(x.dtype), _ptr(bitmap), _ptr(values), values.numel(), _ptr(nnz), _ptr(index),
+        _ptr(workspace), _bytes(workspace), _stream(stream)))
+
+
+def bt_decompress_indexed(bitmap, values, index, out, stream=None):
+    """Algorithm 2 started at every tile from the tile index: no workspace, no scan."""
+    for t, name in ((bitmap, "bitmap"), (values, "values"), (index, "index"), (out, "out")):
+        _dev(t, name)
+    if values.dtype != out.dtype:
+        raise TypeError("values must have the dtype of out")
+    if bitmap.element_size() != 4 or bitmap.numel() * 4 < bt_bitmap_bytes(out.numel()):
+        raise ValueError("bitmap must hold ceil(n/32) 32-bit words")
+    if index.element_size() != 8 or index.numel() * 8 < bt_index_bytes(out.numel(), out.dtype):
+        raise ValueError("index must hold one 64-bit integer per tile")
+    _check("bt_decompress_indexed", lib().bt_decompress_indexed(
+        _ptr(bitmap), _ptr(values), values.numel(), _ptr(index), out.numel(), dtype_code(out.dtype), _ptr(out),
+        _stream(stream)))

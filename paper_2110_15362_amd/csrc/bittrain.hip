@@ -458,8 +458,11 @@ __device__ __forceinline__ void idle_slot(char *ws, const uint32_t slot, const u
 // Run by every thread of a tile's block: publishes the tile's count in its slot, waits
 // for the scanner's answer, and returns the number of stored values of this tensor
 // before this wave's part of the tile (wave-uniform).  Contains two block barriers.
+// If `index_entry` is not null the tile's own prefix is also written there (the tile index
+// that bt_compress_indexed leaves for bt_decompress_indexed).
 __device__ __forceinline__ uint64_t tile_prefix(char *ws, PrefixShared &sh, const uint32_t slot,
-                                                const uint32_t n_slots, const uint32_t wave_total) {
+                                                const uint32_t n_slots, const uint32_t wave_total,
+                                                uint64_t *index_entry = nullptr) {
     const int tid = threadIdx.x;
     const uint32_t lane = tid & (kWaveSize - 1), wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);
     uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
@@ -483,6 +486,7 @@ __device__ __forceinline__ uint64_t tile_prefix(char *ws, PrefixShared &sh, cons
             if (spin_expired<kTileSleep>(hdr, spins)) { v = 1; break; }
         }
         sh.tile_prefix = v - 1;
+        if (index_entry != nullptr) *index_entry = v - 1;
     }
     __syncthreads();
     uint64_t prefix = sh.tile_prefix;
@@ -611,7 +615,8 @@ __device__ __forceinline__ void compress_tile(const void *__restrict__ in, const
                                               uint32_t *__restrict__ bitmap, void *__restrict__ values,
                                               const uint64_t values_cap, char *ws, const uint32_t tile,
                                               const uint32_t slot, const uint32_t n_slots, const float threshold,
-                                              unsigned char *s_stage, PrefixShared &s_prefix) {
+                                              unsigned char *s_stage, PrefixShared &s_prefix,
+                                              uint64_t *__restrict__ index = nullptr) {
     using G = Geo<S>;
     constexpr int E = G::E;
     const int tid = threadIdx.x;
@@ -688,7 +693,8 @@ __device__ __forceinline__ void compress_tile(const void *__restrict__ in, const
     }
 
     // (4) block total -> count for the scanner -> this wave's position in B.values
-    uint64_t g0 = tile_prefix(ws, s_prefix, slot, n_slots, wave_total);   // index in B.values of this wave's next value
+    uint64_t g0 = tile_prefix(ws, s_prefix, slot, n_slots, wave_total,     // index in B.values of this wave's next value
+                              index != nullptr ? index + tile : nullptr);
     {
         const int g = lane / G::G, i = lane % G::G;
 #pragma unroll
@@ -753,7 +759,8 @@ template <int S, int KEEP>
 __global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restrict__ in, const uint64_t n,
                                                           uint32_t *__restrict__ bitmap, void *__restrict__ values,
                                                           const uint64_t values_cap, uint64_t *__restrict__ nnz_out,
-                                                          char *ws, const uint32_t n_tiles, const float threshold) {
+                                                          char *ws, const uint32_t n_tiles, const float threshold,
+                                                          uint64_t *__restrict__ index) {
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
     __shared__ PrefixShared s_prefix;
     if (blockIdx.x == 0) {
@@ -765,7 +772,8 @@ __global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restr
         return;
     }
     const uint32_t tile = blockIdx.x - 1;
-    compress_tile<S, KEEP>(in, n, bitmap, values, values_cap, ws, tile, tile, n_tiles, threshold, s_stage, s_prefix);
+    compress_tile<S, KEEP>(in, n, bitmap, values, values_cap, ws, tile, tile, n_tiles, threshold, s_stage, s_prefix,
+                           index);
 }
 
 // Several tensors in one launch (bt_compress_batch): the kernel arguments carry the
@@ -818,16 +826,23 @@ __global__ __launch_bounds__(kBlock, 8) void compress_batch_kernel(const Compres
 
 // ---- Algorithm 2: bitmap -> dense ---------------------------------------------------------
 
-template <int S>
+// INDEXED: Algorithm 2's j at the start of the tile is read from a tile index (written by
+// bt_compress_indexed) instead of being found by the grid scan: no workspace, no waiting;
+// values at or beyond values_cap are never read.
+template <int S, bool INDEXED = false>
 __device__ __forceinline__ void decompress_tile(const uint32_t *__restrict__ bitmap, const void *__restrict__ values,
                                                 const uint64_t n, void *__restrict__ out, char *ws,
                                                 const uint32_t tile, const uint32_t slot, const uint32_t n_slots,
-                                                unsigned char *s_stage, PrefixShared &s_prefix) {
+                                                unsigned char *s_stage, PrefixShared &s_prefix,
+                                                const uint64_t *__restrict__ index = nullptr,
+                                                const uint64_t values_cap = ~(uint64_t)0) {
     using G = Geo<S>;
     constexpr int E = G::E;
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in a scalar register
+    uint64_t tile_j = 0;
+    if (INDEXED) tile_j = index[tile];                           // asked for first, needed last
 
     const uint64_t n_words = (n + 31) >> 5;
     const uint64_t wave_e0 = (uint64_t)tile * G::TILE + (uint64_t)wave * G::WAVE;
@@ -846,7 +861,17 @@ __device__ __forceinline__ void decompress_tile(const uint32_t *__restrict__ bit
     for (int k = 0; k < kRows; ++k) wave_total += BT_FIELD(total2, k);
 
     // (2) block total -> count for the scanner -> this wave's value of j
-    uint64_t g0 = tile_prefix(ws, s_prefix, slot, n_slots, wave_total);   // Algorithm 2's j for this wave
+    uint64_t g0;                                                          // Algorithm 2's j for this wave
+    if (INDEXED) {
+        if (lane == 0) s_prefix.wave_total[wave] = wave_total;
+        __syncthreads();
+        g0 = tile_j;
+        for (int w = 0; w < wave; ++w) g0 += s_prefix.wave_total[w];
+        g0 = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(g0 >> 32)) << 32) |
+             (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)g0);
+    } else {
+        g0 = tile_prefix(ws, s_prefix, slot, n_slots, wave_total);
+    }
 
     // (3) Ask for the values of every phase (kPhaseRows rows each) first, so that all of
     //     them are in flight together; then, phase by phase, put them into the LDS strip
@@ -865,8 +890,13 @@ __device__ __forceinline__ void decompress_tile(const uint32_t *__restrict__ bit
         for (int k = ph * kPhaseRows; k < (ph + 1) * kPhaseRows; ++k) cnts[ph] += BT_FIELD(total2, k);
         const char *gsrc = static_cast<const char *>(values) + g0 * S;
         pads[ph] = (uint32_t)(reinterpret_cast<uintptr_t>(gsrc) & (kVecBytes - 1)) / S;
+        const uint32_t phase_total = cnts[ph];
+        if (INDEXED) {   // an index that does not belong to this bitmap must not lead outside d_values
+            if (g0 >= values_cap) cnts[ph] = 0;
+            else if (values_cap - g0 < cnts[ph]) cnts[ph] = (uint32_t)(values_cap - g0);
+        }
         strip_fetch<S>(gsrc, pads[ph], cnts[ph], lane, fetched[ph]);
-        g0 += cnts[ph];
+        g0 += phase_total;
     }
     const bool full = (uint64_t)(tile + 1) * G::TILE <= n;
 #pragma unroll
@@ -957,6 +987,18 @@ __global__ __launch_bounds__(kBlock) void decompress_batch_kernel(const Decompre
         return;
     }
     decompress_tile<S>(b.bitmap[i], b.values[i], b.n[i], b.out[i], ws, tile, slot, n_slots, s_stage, s_prefix);
+}
+
+// bt_decompress_indexed: one workgroup per tile and nothing else.
+template <int S>
+__global__ __launch_bounds__(kBlock) void decompress_indexed_kernel(const uint32_t *__restrict__ bitmap,
+                                                                    const void *__restrict__ values,
+                                                                    const uint64_t values_cap,
+                                                                    const uint64_t *__restrict__ index, const uint64_t n,
+                                                                    void *__restrict__ out) {
+    __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
+    __shared__ PrefixShared s_prefix;
+    decompress_tile<S, true>(bitmap, values, n, out, nullptr, blockIdx.x, 0, 0, s_stage, s_prefix, index, values_cap);
 }
 
 // ---- ReLU backward from the bitmap -----------------------------------------------------------
@@ -1163,7 +1205,7 @@ bt_status bt_workspace_init(void *d_workspace, size_t workspace_bytes, bt_stream
 
 static bt_status compress_common(const void *d_in, uint64_t n, bt_dtype dtype, bool prune, float threshold,
                                  uint32_t *d_bitmap, void *d_values, uint64_t values_cap, uint64_t *d_nnz,
-                                 void *d_workspace, size_t workspace_bytes, bt_stream stream) {
+                                 uint64_t *d_index, void *d_workspace, size_t workspace_bytes, bt_stream stream) {
     const bt_status st = check_common(n, dtype, d_workspace, workspace_bytes);
     if (st != BT_OK) return st;
     if (d_nnz == nullptr) return BT_ERR_NULL;
@@ -1182,7 +1224,7 @@ static bt_status compress_common(const void *d_in, uint64_t n, bt_dtype dtype, b
     char *ws = static_cast<char *>(d_workspace);
     const dim3 grid(n_tiles + 1), block(kBlock);
 #define BT_LAUNCH_COMPRESS(S_, KEEP_) \
-    compress_kernel<S_, KEEP_><<<grid, block, 0, hs>>>(d_in, n, d_bitmap, d_values, values_cap, d_nnz, ws, n_tiles, threshold)
+    compress_kernel<S_, KEEP_><<<grid, block, 0, hs>>>(d_in, n, d_bitmap, d_values, values_cap, d_nnz, ws, n_tiles, threshold, d_index)
     if (!prune) {
         if (s == 8) BT_LAUNCH_COMPRESS(8, kKeepNonZero);
         else if (s == 4) BT_LAUNCH_COMPRESS(4, kKeepNonZero);
@@ -1203,15 +1245,54 @@ static bt_status compress_common(const void *d_in, uint64_t n, bt_dtype dtype, b
 bt_status bt_compress(const void *d_in, uint64_t n, bt_dtype dtype, uint32_t *d_bitmap, void *d_values,
                       uint64_t values_cap, uint64_t *d_nnz, void *d_workspace, size_t workspace_bytes,
                       bt_stream stream) {
-    return compress_common(d_in, n, dtype, false, 0.0f, d_bitmap, d_values, values_cap, d_nnz, d_workspace,
+    return compress_common(d_in, n, dtype, false, 0.0f, d_bitmap, d_values, values_cap, d_nnz, nullptr, d_workspace,
                            workspace_bytes, stream);
 }
 
 bt_status bt_compress_pruned(const void *d_in, uint64_t n, bt_dtype dtype, float threshold, uint32_t *d_bitmap,
                              void *d_values, uint64_t values_cap, uint64_t *d_nnz, void *d_workspace,
                              size_t workspace_bytes, bt_stream stream) {
-    return compress_common(d_in, n, dtype, true, threshold, d_bitmap, d_values, values_cap, d_nnz, d_workspace,
+    return compress_common(d_in, n, dtype, true, threshold, d_bitmap, d_values, values_cap, d_nnz, nullptr, d_workspace,
                            workspace_bytes, stream);
+}
+
+size_t bt_tile_elems(bt_dtype dtype) {
+    const int s = elem_size(dtype);
+    return s == 0 ? 0 : (size_t)tile_elems(s);
+}
+
+size_t bt_index_bytes(uint64_t n, bt_dtype dtype) {
+    const int s = elem_size(dtype);
+    return s == 0 ? 0 : (size_t)(8 * tiles_for(n, s));
+}
+
+bt_status bt_compress_indexed(const void *d_in, uint64_t n, bt_dtype dtype, uint32_t *d_bitmap, void *d_values,
+                              uint64_t values_cap, uint64_t *d_nnz, uint64_t *d_index, void *d_workspace,
+                              size_t workspace_bytes, bt_stream stream) {
+    if (elem_size(dtype) != 0 && n != 0 && n <= BT_MAX_ELEMENTS) {
+        if (d_index == nullptr) return BT_ERR_NULL;
+        if (misaligned(d_index, 8)) return BT_ERR_ALIGN;
+    }
+    return compress_common(d_in, n, dtype, false, 0.0f, d_bitmap, d_values, values_cap, d_nnz, d_index, d_workspace,
+                           workspace_bytes, stream);
+}
+
+bt_status bt_decompress_indexed(const uint32_t *d_bitmap, const void *d_values, uint64_t values_cap,
+                                const uint64_t *d_index, uint64_t n, bt_dtype dtype, void *d_out, bt_stream stream) {
+    const int s = elem_size(dtype);
+    if (s == 0) return BT_ERR_DTYPE;
+    if (n > BT_MAX_ELEMENTS) return BT_ERR_SIZE;
+    if (n == 0) return BT_OK;
+    if (d_bitmap == nullptr || d_out == nullptr || d_index == nullptr) return BT_ERR_NULL;
+    if (d_values == nullptr && values_cap != 0) return BT_ERR_NULL;
+    if (misaligned(d_out, 16) || misaligned(d_bitmap, 4) || misaligned(d_values, (size_t)s) || misaligned(d_index, 8))
+        return BT_ERR_ALIGN;
+    hipStream_t hs = (hipStream_t)stream;
+    const dim3 grid((uint32_t)tiles_for(n, s)), block(kBlock);
+    if (s == 8) decompress_indexed_kernel<8><<<grid, block, 0, hs>>>(d_bitmap, d_values, values_cap, d_index, n, d_out);
+    else if (s == 4) decompress_indexed_kernel<4><<<grid, block, 0, hs>>>(d_bitmap, d_values, values_cap, d_index, n, d_out);
+    else decompress_indexed_kernel<2><<<grid, block, 0, hs>>>(d_bitmap, d_values, values_cap, d_index, n, d_out);
+    return launched();
 }
 
 bt_status bt_decompress(const uint32_t *d_bitmap, const void *d_values, uint64_t n, bt_dtype dtype, void *d_out,

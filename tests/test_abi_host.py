@@ -30,7 +30,8 @@ def test_every_declared_symbol_is_exported(bt):
     names = _declared_functions()
     assert {"bt_compress", "bt_compressed_size", "bt_decompress", "bt_relu_backward_from_bitmap",
             "bt_compress_pruned", "bt_compress_batch", "bt_decompress_batch", "bt_batch_workspace_bytes",
-            "bt_mask_apply", "bt_dense_size", "bt_coo_size"} <= set(names)
+            "bt_mask_apply", "bt_dense_size", "bt_coo_size", "bt_compress_indexed", "bt_decompress_indexed",
+            "bt_tile_elems", "bt_index_bytes"} <= set(names)
     raw = ctypes.CDLL(bt.LIB_PATH)
     for name in names:
         assert hasattr(raw, name), name
@@ -226,6 +227,34 @@ def test_footprint_calculator_reproduces_table1_and_the_coo_break_even(bt):
     assert sw[0]["coo_int_bytes"] < sw[0]["dense_bytes"] and sw[2]["coo_int_bytes"] > sw[2]["dense_bytes"]
     assert all(r["bitmap_bytes"] < r["dense_bytes"] and r["bitmap_bytes"] < r["coo_int_bytes"] for r in sw)
     assert fp.footprint((8, 2048, 4096), 0.35, torch.bfloat16)["bitmap_bytes"] == 2 * int(8 * 2048 * 4096 * 0.35) + 8 * 2048 * 4096 // 8
+
+
+def test_tile_index_sizes_and_host_errors(bt):
+    for code, width in ((bt.BT_F32, 4), (bt.BT_F16, 2), (bt.BT_BF16, 2), (bt.BT_F64, 8)):
+        tile = bt.bt_tile_elems(code)
+        assert tile * width == 32 * 1024
+        for n in (0, 1, tile - 1, tile, tile + 1, 25690112):
+            assert bt.bt_index_bytes(n, code) == 8 * -(-n // tile)
+    assert bt.bt_tile_elems(9) == 0 and bt.bt_index_bytes(100, 9) == 0
+    L = bt.lib()
+    A = 0x10000
+    wsb = bt.bt_workspace_bytes(1000, bt.BT_F32)
+
+    def compress(d_in=A, n=1000, dt=bt.BT_F32, bm=A, val=A, cap=1000, nnz=A, idx=A, ws=A, wsb=wsb):
+        return L.bt_compress_indexed(d_in, n, dt, bm, val, cap, nnz, idx, ws, wsb, None)
+
+    assert compress(idx=None) == 1 and compress(idx=A + 4) == 3
+    assert compress(dt=8) == 2 and compress(d_in=None) == 1 and compress(nnz=None) == 1
+    assert compress(d_in=A + 8) == 3 and compress(wsb=wsb - 1) == 4 and compress(n=(1 << 37) + 1) == 6
+
+    def decompress(bm=A, val=A, cap=1000, idx=A, n=1000, dt=bt.BT_F32, out=A):
+        return L.bt_decompress_indexed(bm, val, cap, idx, n, dt, out, None)
+
+    assert decompress(dt=4) == 2 and decompress(n=(1 << 37) + 1) == 6
+    assert decompress(bm=None) == 1 and decompress(out=None) == 1 and decompress(idx=None) == 1
+    assert decompress(val=None) == 1                       # a capacity without a buffer
+    assert decompress(out=A + 4) == 3 and decompress(idx=A + 2) == 3 and decompress(val=A + 2) == 3
+    assert decompress(n=0, bm=None, val=None, cap=0, idx=None, out=None) == 0
 
 
 def test_bench_refuses_more_than_one_gpu():
