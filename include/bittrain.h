@@ -95,6 +95,21 @@ const char *bt_status_str(bt_status status);
 
 /* ---- device calls -------------------------------------------------------- */
 
+/* What a caller may look at, or set, in a workspace: 32-bit words at the start of it.
+ *   BT_WS_ERROR_WORD        0 in normal operation.  Every wait inside the kernels (a tile
+ *                           waiting for the grid scan, the scan waiting for a tile) is
+ *                           bounded; a kernel whose wait ran out sets this word to 1 and
+ *                           ends normally, staying inside all buffers.  The outputs of that
+ *                           call are undefined, and later calls on the workspace write
+ *                           nothing at all, until bt_workspace_init has been run on it again.
+ *   BT_WS_WAIT_LIMIT_WORD   polls after which a wait is given up; 0 (the initial state)
+ *                           means the built-in limit of 2^20 polls, far beyond what any
+ *                           tensor needs.  Written by the caller only (a device-side store
+ *                           or copy ordered before the call); meant for tests of the
+ *                           failure path. */
+#define BT_WS_ERROR_WORD 2
+#define BT_WS_WAIT_LIMIT_WORD 3
+
 /* Put a workspace into its initial state (all zero bytes) by enqueueing a fill
  * kernel on `stream`.  Required once after allocating a workspace, before its
  * first use, and again if a kernel using it was aborted.  After that the

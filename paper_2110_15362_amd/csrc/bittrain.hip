@@ -48,7 +48,8 @@ constexpr int kReluRows = BT_RELU_ROWS;   // 16-byte vectors per lane in the ReL
 // Header (uint32 words), then one 768-byte record per 32 tiles.
 constexpr int kHdrSeq = 0;       // calls completed on this workspace; its low bit picks the copy in use
 constexpr int kHdrPrevTiles = 1; // tiles of the previous call (what it left behind in the other copy)
-constexpr int kHdrError = 2;     // set if a tile gave up waiting for another tile's count
+constexpr int kHdrError = BT_WS_ERROR_WORD;           // set if a wait was given up
+constexpr int kHdrSpinLimit = BT_WS_WAIT_LIMIT_WORD;  // polls before a wait is given up; 0: kSpinLimit
 constexpr size_t kHeaderBytes = 256;
 // Record of 32 tiles, two copies c = 0, 1 of everything, in separate 128-byte lines:
 //   [128*c, 128*c + 128)          uint32 count + 1 of each tile, written by the tile
@@ -313,9 +314,10 @@ __device__ __forceinline__ char *ws_prefix(char *ws, uint32_t tile, uint32_t cop
 }
 
 template <int SLEEP> __device__ __forceinline__ bool spin_expired(uint32_t *hdr, uint32_t &spins) {
-    // bounded wait: give up after kSpinLimit polls, or soon after anyone has given up
+    // bounded wait: give up after the limit of polls, or soon after anyone has given up
     ++spins;
-    if (spins > kSpinLimit ||
+    const uint32_t asked = hdr[kHdrSpinLimit];          // never written by a kernel
+    if (spins > (asked != 0 ? asked : kSpinLimit) ||
         ((spins & 255u) == 0 && __hip_atomic_load(&hdr[kHdrError], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
         __hip_atomic_store(&hdr[kHdrError], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return true;
@@ -415,6 +417,13 @@ __device__ __forceinline__ void scan_counts(char *ws, const Segments seg) {
         __hip_atomic_store(&hdr[kHdrPrevTiles], n_slots, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(&hdr[kHdrSeq], seq + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+}
+
+// A workspace on which a wait was given up is in no defined state: later calls on it do
+// nothing (and stay away from its stale entries) until bt_workspace_init has been run.
+// Uniform over the workgroup, tested before anything else.
+__device__ __forceinline__ bool workspace_failed(const char *ws) {
+    return reinterpret_cast<const uint32_t *>(ws)[kHdrError] != 0;
 }
 
 struct PrefixShared {
@@ -763,6 +772,7 @@ __global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restr
                                                           uint64_t *__restrict__ index) {
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
     __shared__ PrefixShared s_prefix;
+    if (workspace_failed(ws)) return;
     if (blockIdx.x == 0) {
         if (threadIdx.x < kWaveSize) {
             const uint32_t start[2] = {0, n_tiles};
@@ -808,6 +818,7 @@ template <int S>
 __global__ __launch_bounds__(kBlock, 8) void compress_batch_kernel(const CompressBatch b, char *ws) {
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
     __shared__ PrefixShared s_prefix;
+    if (workspace_failed(ws)) return;
     const uint32_t n_slots = b.lay.start[b.lay.count];
     if (blockIdx.x == 0) {
         if (threadIdx.x < kWaveSize) scan_counts(ws, Segments{b.lay.count, b.lay.start, b.nnz});
@@ -951,6 +962,7 @@ __global__ __launch_bounds__(kBlock) void decompress_kernel(const uint32_t *__re
                                                             void *__restrict__ out, char *ws, const uint32_t n_tiles) {
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
     __shared__ PrefixShared s_prefix;
+    if (workspace_failed(ws)) return;
     if (blockIdx.x == 0) {
         if (threadIdx.x < kWaveSize) {
             const uint32_t start[2] = {0, n_tiles};
@@ -974,6 +986,7 @@ template <int S>
 __global__ __launch_bounds__(kBlock) void decompress_batch_kernel(const DecompressBatch b, char *ws) {
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
     __shared__ PrefixShared s_prefix;
+    if (workspace_failed(ws)) return;
     const uint32_t n_slots = b.lay.start[b.lay.count];
     if (blockIdx.x == 0) {
         if (threadIdx.x < kWaveSize) scan_counts(ws, Segments{b.lay.count, b.lay.start, nullptr});

@@ -351,3 +351,28 @@ def test_mask_apply_with_a_foreign_bitmap(gpu, oracle, dt):
         got_bitmap, _, got_nnz, ok = gpu.gpu_compress(torch.from_numpy(want.view({2: np.int16, 4: np.int32, 8: np.int64}[want.itemsize])).view(src.dtype))
         y_nonzero_under_mask = int(((wl.bits(y) != 0) & (wl.bits(src) != 0)).sum())
         assert ok and got_nnz == y_nonzero_under_mask and got_nnz <= nnz
+
+
+def test_a_wait_that_runs_out_ends_the_kernel_and_raises_the_flag(gpu, oracle):
+    """Failure path, forced from the host: with the wait limit of the workspace set to one poll,
+    tiles give up waiting for the grid scan.  The kernels must still end, stay inside their
+    buffers and leave the error word set; after bt_workspace_init the workspace works again."""
+    import paper_2110_15362_amd.bittrain as bt
+    n = 600 * 8192 + 77
+    x = wl.random_sparse(n, "f32", 0.5, seed=31337)
+    ws = bt.new_workspace(n, torch.float32)
+    words = ws.view(torch.int32)
+    words[3] = 1                                   # BT_WS_WAIT_LIMIT_WORD: one poll
+    bitmap, values, nnz, tail_ok = gpu.gpu_compress(x, ws=ws)          # synchronises; returns at all
+    assert tail_ok, "wrote outside bitmap[0,W) or values[0,min(nnz,cap))"
+    assert int(words[2].item()) == 1               # BT_WS_ERROR_WORD
+    o_bitmap, o_values, o_nnz = oracle.compress(wl.bits(x))
+    # a later call on the failed workspace writes nothing: the output keeps the test's fill pattern
+    out, guard_ok = gpu.gpu_decompress(o_bitmap, o_values, n, torch.float32, ws=ws)
+    assert guard_ok and int(words[2].item()) == 1
+    assert (out == 0x5A5A5A5A).all()
+    bt.bt_workspace_init(ws)
+    assert int(words[2].item()) == 0 and int(words[3].item()) == 0
+    _check_compress(gpu, oracle, x, ws=ws)
+    _check_decompress(gpu, oracle, o_bitmap, o_values, n, x.dtype, wl.bits(x), ws=ws)
+    assert int(words[2].item()) == 0
