@@ -319,8 +319,21 @@ def main():
                          "roofline_frac_cold": round(alg / cold / 1e3 / HBM_PEAK_GBPS, 4),
                          "roofline_frac_warm": round(alg / warm / 1e3 / HBM_PEAK_GBPS, 4)}
         if z == 0.5:
+            # what a stream with the same traffic and no dependency between workgroups gets on this GPU:
+            # one tile per workgroup, 8 rows (32 KiB) read + 4 written for compress, 4 read + 8 written for
+            # decompress (at 50 % zeros the compressed side is half the dense side, plus the bitmap's 3 %)
+            tiles32k = n * s // 32768
+            tc = timed(lambda i: bt.bt_stream_probe(xs[i % K], values[i % K], tiles32k, 8, 4), args.steps, args.warmup)
+            td = timed(lambda i: bt.bt_stream_probe(values[i % K], outs[i % K], tiles32k, 4, 8), args.steps, args.warmup)
+            tcp = timed(lambda i: bt.bt_stream_probe(xs[i % K], outs[i % K], tiles32k, 8, 8), args.steps, args.warmup)
+            moved = tiles32k * 12 * 4096
+            stream_ceiling = {"what": "dependency-free streams of the same shape (bt_stream_probe), cold",
+                              "compress_like_us": round(tc, 2), "compress_like_frac": round(moved / tc / 1e3 / HBM_PEAK_GBPS, 4),
+                              "decompress_like_us": round(td, 2), "decompress_like_frac": round(moved / td / 1e3 / HBM_PEAK_GBPS, 4),
+                              "copy_us": round(tcp, 2), "copy_frac": round(tiles32k * 16 * 4096 / tcp / 1e3 / HBM_PEAK_GBPS, 4)}
             t_step = float("nan") if args.no_step else timed(step, args.steps, args.warmup)
-            headline = {"n": n, "s": s, "nnz": nnz, "t_step_us": t_step, "row": row, "alg_codec": alg_codec}
+            headline = {"n": n, "s": s, "nnz": nnz, "t_step_us": t_step, "row": row, "alg_codec": alg_codec,
+                        "stream_ceiling": stream_ceiling}
             if args.copy_calibration:
                 timed(lambda i: outs[i % K].copy_(xs[i % K]), 10, 2)
         ops.append(row)
@@ -339,7 +352,7 @@ def main():
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(dom),
                 "algorithmic_bytes_per_launch": row[dom]["algorithmic_bytes"],
                 "avg_launch_us": row[dom]["us_cold"], "cache": "cold (8 rotating buffer sets)",
-                "frac_warm": row[dom]["roofline_frac_warm"]}
+                "frac_warm": row[dom]["roofline_frac_warm"], "stream_ceiling": headline["stream_ceiling"]}
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -276,6 +276,19 @@ bt_status bt_compress_batch(const bt_compress_item *items, size_t count, bt_dtyp
 bt_status bt_decompress_batch(const bt_decompress_item *items, size_t count, bt_dtype dtype,
                               void *d_workspace, size_t workspace_bytes, bt_stream stream);
 
+/* ---- measurement aid -------------------------------------------------------------
+ *
+ * Not part of the method: a plain stream with the traffic shape of the codec kernels and
+ * no dependency between workgroups, for callers (the benchmark) that want to know what
+ * the memory system gives that shape at best.  Workgroup t of `tiles` reads read_rows
+ * rows of 4 KiB from d_in and writes write_rows rows of 4 KiB to d_out, each contiguous:
+ * d_in must hold tiles * read_rows * 4096 bytes and d_out tiles * write_rows * 4096 bytes
+ * (at least 16 * tiles bytes when write_rows is 0), both 16-byte aligned.  d_out receives
+ * arbitrary bytes.  (read_rows, write_rows) is one of (8,4) the compress shape at 50 %
+ * zeros, (4,8) the decompress shape, (8,8), (8,0), (0,8); anything else: BT_ERR_SIZE. */
+bt_status bt_stream_probe(const void *d_in, void *d_out, uint64_t tiles, int read_rows, int write_rows,
+                          bt_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

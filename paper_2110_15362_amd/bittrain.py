@@ -75,6 +75,8 @@ def lib():
         L.bt_compress_indexed.argtypes = [vp, u64, ci, vp, vp, u64, vp, vp, vp, sz, vp]
         L.bt_decompress_indexed.restype = ci
         L.bt_decompress_indexed.argtypes = [vp, vp, u64, vp, u64, ci, vp, vp]
+        L.bt_stream_probe.restype = ci
+        L.bt_stream_probe.argtypes = [vp, vp, u64, ci, ci, vp]
         L.bt_batch_workspace_bytes.restype = sz
         L.bt_batch_workspace_bytes.argtypes = [ctypes.POINTER(u64), sz, ci]
         L.bt_compress_batch.restype = ci
@@ -332,3 +334,14 @@ def bt_decompress_indexed(bitmap, values, index, out, stream=None):
     _check("bt_decompress_indexed", lib().bt_decompress_indexed(
         _ptr(bitmap), _ptr(values), values.numel(), _ptr(index), out.numel(), dtype_code(out.dtype), _ptr(out),
         _stream(stream)))
+
+
+def bt_stream_probe(src, dst, tiles, read_rows, write_rows, stream=None):
+    """Measurement aid: a dependency-free stream of `tiles` workgroups reading read_rows and writing
+    write_rows 4 KiB rows each (see the C header)."""
+    _dev(src, "src")
+    _dev(dst, "dst")
+    if _bytes(src) < tiles * read_rows * 4096 or _bytes(dst) < max(tiles * write_rows * 4096, 16 * tiles):
+        raise ValueError("buffers too small for this many tiles")
+    _check("bt_stream_probe", lib().bt_stream_probe(_ptr(src), _ptr(dst), tiles, read_rows, write_rows,
+                                                    _stream(stream)))

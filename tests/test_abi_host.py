@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(bt):
     assert {"bt_compress", "bt_compressed_size", "bt_decompress", "bt_relu_backward_from_bitmap",
             "bt_compress_pruned", "bt_compress_batch", "bt_decompress_batch", "bt_batch_workspace_bytes",
             "bt_mask_apply", "bt_dense_size", "bt_coo_size", "bt_compress_indexed", "bt_decompress_indexed",
-            "bt_tile_elems", "bt_index_bytes"} <= set(names)
+            "bt_tile_elems", "bt_index_bytes", "bt_stream_probe"} <= set(names)
     raw = ctypes.CDLL(bt.LIB_PATH)
     for name in names:
         assert hasattr(raw, name), name
@@ -255,6 +255,16 @@ def test_tile_index_sizes_and_host_errors(bt):
     assert decompress(val=None) == 1                       # a capacity without a buffer
     assert decompress(out=A + 4) == 3 and decompress(idx=A + 2) == 3 and decompress(val=A + 2) == 3
     assert decompress(n=0, bm=None, val=None, cap=0, idx=None, out=None) == 0
+
+
+def test_stream_probe_host_errors(bt):
+    L = bt.lib()
+    A = 0x10000
+    assert L.bt_stream_probe(None, A, 10, 8, 4, None) == 1 and L.bt_stream_probe(A, None, 10, 8, 4, None) == 1
+    assert L.bt_stream_probe(A + 8, A, 10, 8, 4, None) == 3
+    assert L.bt_stream_probe(A, A, 10, 3, 5, None) == 6          # not one of the listed shapes
+    assert L.bt_stream_probe(A, A, 1 << 31, 8, 4, None) == 6
+    assert L.bt_stream_probe(A, A, 0, 8, 4, None) == 0
 
 
 def test_bench_refuses_more_than_one_gpu():

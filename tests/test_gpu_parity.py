@@ -376,3 +376,18 @@ def test_a_wait_that_runs_out_ends_the_kernel_and_raises_the_flag(gpu, oracle):
     _check_compress(gpu, oracle, x, ws=ws)
     _check_decompress(gpu, oracle, o_bitmap, o_values, n, x.dtype, wl.bits(x), ws=ws)
     assert int(words[2].item()) == 0
+
+
+def test_stream_probe_stays_inside_its_buffers(gpu):
+    """The measurement aid reads tiles * read_rows * 4 KiB and writes tiles * write_rows * 4 KiB, no more."""
+    import paper_2110_15362_amd.bittrain as bt
+    tiles = 777
+    for r, w in ((8, 4), (4, 8), (8, 8), (8, 0), (0, 8)):
+        src = torch.arange(tiles * max(r, 1) * 1024, dtype=torch.int32, device="cuda")
+        guard = 4096
+        dst = torch.full((max(tiles * w * 1024, 4 * tiles) + guard,), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+        bt.bt_stream_probe(src, dst[:dst.numel() - guard], tiles, r, w)
+        torch.cuda.synchronize()
+        assert bool((dst[dst.numel() - guard:] == 0x5A5A5A5A).all()), (r, w)
+        if w:
+            assert not bool((dst[:tiles * w * 1024] == 0x5A5A5A5A).all()), (r, w)
