@@ -281,7 +281,7 @@ __device__ __forceinline__ uint32_t bitmap_bits(const uint32_t *bitmap, uint64_t
 // tiles before it (Algorithm 1 appends in index order; Algorithm 2's counter j).
 // Tiles do not talk to each other.  Each tile publishes its count in the workspace;
 // ONE extra workgroup (workgroup 0, a single wave: the "scanner") reads the counts
-// in index order, up to 384 at a time, keeps the running sum, and writes every tile's
+// in index order, up to 448 at a time, keeps the running sum, and writes every tile's
 // prefix back; a tile then polls its own prefix, one 8-byte load.  Per tile that
 // is one store and one polled load on lines shared with few other tiles.  (Having
 // every tile read its predecessors' counts itself -- a look-back window or a tree --
@@ -341,11 +341,12 @@ template <int SLEEP> __device__ __forceinline__ bool spin_expired(uint32_t *hdr,
 // When a tensor's counts are all in it writes the tensor's total (nnz); at the end it
 // advances the header for the next call.
 // Rows per pass, measured on MI355X (25.7 M fp32 elements, cold, compress / decompress
-// microseconds): 2 rows 39.0 / 36.8, 4 rows 34.9 / 33.5, 6 rows 34.2 / 33.5, 8 rows 34.1 / 34.0,
-// 16 rows 35.2 / 34.2, 32 rows 37.4 / 36.6: a pass costs a load round trip whatever its
-// width, but a wider pass waits for the slowest of more loads.
+// microseconds at 50 % zeros): 2 rows 39.0 / 36.8, 4 rows 34.9 / 33.5, 6 rows 33.6 / 33.6,
+// 7 rows 33.4 / 33.9, 8 rows 33.6 / 34.0, 16 rows 35.2 / 34.2, 32 rows 37.4 / 36.6 (at 90 % zeros
+// 6 rows cost compress 0.9): a pass costs a load round trip whatever its width, but a
+// wider pass waits for the slowest of more loads.
 #ifndef BT_SCAN_ROWS
-#define BT_SCAN_ROWS 6
+#define BT_SCAN_ROWS 7
 #endif
 constexpr int kScanRows = BT_SCAN_ROWS;
 // What the scanner has to know about the tensors of one call.  A call on one tensor

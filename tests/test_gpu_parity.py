@@ -138,10 +138,10 @@ def test_workspace_reuse_across_calls_and_sizes(gpu, oracle):
 @pytest.mark.parametrize("dt", ["f32", "bf16", "f64"])
 def test_tile_record_and_scan_window_boundaries(gpu, oracle, dt):
     """Sizes around the bookkeeping granularities: a tile (8192 fp32 / 16384 16-bit elements), a
-    workspace record (32 tiles), a scanner row (64 tiles) and a scanner pass (384 tiles; 512 in earlier builds)."""
+    workspace record (32 tiles), a scanner row (64 tiles) and a scanner pass (448 tiles; 384 and 512 in earlier builds)."""
     tile = {"f32": 8192, "bf16": 16384, "f64": 4096}[dt]
     sizes = []
-    for tiles in (1, 31, 32, 33, 63, 64, 65, 383, 384, 385, 511, 512, 513, 769, 1025):
+    for tiles in (1, 31, 32, 33, 63, 64, 65, 383, 384, 385, 447, 448, 449, 511, 512, 513, 897, 1025):
         sizes += [tiles * tile - 1, tiles * tile, tiles * tile + 1]
     for i, n in enumerate(sizes):
         x = wl.random_sparse(n, dt, 0.5 if i % 3 else 0.97, seed=6000 + i)
