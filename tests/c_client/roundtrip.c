@@ -3,7 +3,7 @@
  * device buffers from the HIP runtime, every call checked against the C oracle that is
  * linked in (test infrastructure).  Prints "c_client ok" and returns 0 on success.
  *
- * Built by __graft_entry__.build() with hipcc; run by tests/test_gpu_c_client.py.
+ * Built by __graft_entry__.build() with hipcc; run by tests/test_gpu_z_c_client.py.
  */
 #include <hip/hip_runtime_api.h>
 #include <stdint.h>
