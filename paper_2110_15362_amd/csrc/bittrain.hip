@@ -1089,8 +1089,9 @@ __global__ __launch_bounds__(kBlock) void relu_backward_kernel(const uint32_t *_
 // both contiguous per workgroup and per wave, with the same cache hints as the codec.
 // Nothing waits for anything: this is what the memory system gives the codec's access
 // pattern at best, the figure the codec kernels are compared with.
+constexpr int kProbeThreads = 256;     // a row is 256 lanes x 16 bytes = 4 KiB, whatever the codec's workgroup size
 template <int R, int W>
-__global__ __launch_bounds__(kBlock) void stream_probe_kernel(const uint4 *__restrict__ in, uint4 *__restrict__ out,
+__global__ __launch_bounds__(kProbeThreads) void stream_probe_kernel(const uint4 *__restrict__ in, uint4 *__restrict__ out,
                                                               const uint32_t tiles) {
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1099,7 +1100,7 @@ __global__ __launch_bounds__(kBlock) void stream_probe_kernel(const uint4 *__res
     uint4 acc = make_uint4(1, 2, 3, (uint32_t)t);
     if (R > 0) {
         uint4 v[R > 0 ? R : 1];
-        const uint64_t base = (t * kWaves + wave) * (uint64_t)(kWaveSize * R) + lane;
+        const uint64_t base = (t * (kProbeThreads / kWaveSize) + wave) * (uint64_t)(kWaveSize * R) + lane;
 #pragma unroll
         for (int k = 0; k < R; ++k) v[k] = stream_load<true>(in + base + kWaveSize * k);
 #pragma unroll
@@ -1108,7 +1109,7 @@ __global__ __launch_bounds__(kBlock) void stream_probe_kernel(const uint4 *__res
         }
     }
     if (W > 0) {
-        const uint64_t base = (t * kWaves + wave) * (uint64_t)(kWaveSize * W) + lane;
+        const uint64_t base = (t * (kProbeThreads / kWaveSize) + wave) * (uint64_t)(kWaveSize * W) + lane;
 #pragma unroll
         for (int k = 0; k < W; ++k) {
             uint4 o = acc;
@@ -1411,7 +1412,7 @@ bt_status bt_stream_probe(const void *d_in, void *d_out, uint64_t tiles, int rea
     if (tiles == 0) return BT_OK;
     if (tiles > 0x7fffffffu) return BT_ERR_SIZE;
     hipStream_t hs = (hipStream_t)stream;
-    const dim3 grid((uint32_t)tiles), block(kBlock);
+    const dim3 grid((uint32_t)tiles), block(kProbeThreads);
     const uint4 *in = static_cast<const uint4 *>(d_in);
     uint4 *out = static_cast<uint4 *>(d_out);
     const uint32_t t = (uint32_t)tiles;
