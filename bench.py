@@ -154,7 +154,23 @@ def other_configs(bt, wl, torch, dev, timed, args):
                      "n": n, "zero_fraction": round(1 - nnz / n, 4),
                      "compression_ratio": round(n * 4 / bt.bt_compressed_size(n, nnz, pre.dtype), 4),
                      "compress_us": round(t, 2), "compress_roofline_frac": round(alg / t / 1e3 / HBM_PEAK_GBPS, 4)})
-    del xs, bitmaps, values
+    # the activation and its stash in one pass (dense ReLU output + compressed form), against ReLU followed by compress
+    outs = [torch.empty(n, dtype=pre.dtype, device=dev) for _ in range(sets)]
+    t_fused = timed(lambda i: bt.bt_activation_compress(xs[i % sets], 0.0, outs[i % sets], bitmaps[i % sets], values[i % sets], nnz_d, ws), 100, 5)
+
+    def unfused(i):
+        torch.clamp_min(xs[i % sets], 0.0, out=outs[i % sets])          # ReLU into a preallocated output
+        bt.bt_compress(outs[i % sets], bitmaps[i % sets], values[i % sets], nnz_d, ws)
+
+    t_unfused = timed(unfused, 100, 5)
+    bt.bt_activation_compress(xs[0], 0.0, outs[0], bitmaps[0], values[0], nnz_d, ws)
+    torch.cuda.synchronize()
+    nnz = int(nnz_d.item())
+    alg_fused = 2 * n * 4 + 4 * ((n + 31) // 32) + nnz * 4
+    rows.append({"config": "ReLU output + its compressed form in one pass (bt_activation_compress, threshold 0) on the same pre-activations",
+                 "n": n, "fused_us": round(t_fused, 2), "relu_then_compress_us": round(t_unfused, 2),
+                 "fused_roofline_frac": round(alg_fused / t_fused / 1e3 / HBM_PEAK_GBPS, 4)})
+    del xs, bitmaps, values, outs
 
     # configuration 4: the 49 ResNet-50 activations, compressed in forward order and restored in
     # reverse order on one stream with one workspace; value buffers right-sized from nnz

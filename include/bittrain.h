@@ -159,6 +159,20 @@ bt_status bt_compress_pruned(const void *d_in, uint64_t n, bt_dtype dtype, float
                              uint64_t *d_nnz,
                              void *d_workspace, size_t workspace_bytes, bt_stream stream);
 
+/* The activation itself and its stash in one pass: as bt_compress_pruned, and in addition
+ * the dense pruned tensor goes to d_dense_out (n elements, 16-byte aligned):
+ *   d_dense_out[i] = x[i] where x[i] > threshold, +0 elsewhere,
+ * i.e. y = ReLU(x) for threshold 0 -- what the next layer consumes -- while bitmap, values
+ * and nnz are the compressed form of that same y, kept for the backward pass.  One read of
+ * x serves both; run separately, ReLU and bt_compress read the activation three times and
+ * write it once more.  d_dense_out may be d_in itself (in place) but must not partly
+ * overlap it or any other argument.  Everything else as bt_compress_pruned. */
+bt_status bt_activation_compress(const void *d_in, uint64_t n, bt_dtype dtype, float threshold,
+                                 void *d_dense_out,
+                                 uint32_t *d_bitmap, void *d_values, uint64_t values_cap,
+                                 uint64_t *d_nnz,
+                                 void *d_workspace, size_t workspace_bytes, bt_stream stream);
+
 /* Algorithm 2 (bitmap -> dense).
  *   d_bitmap    ceil(n/32) words as written by bt_compress (bits at positions
  *               >= n are ignored).

@@ -109,16 +109,21 @@ class BitmapStash(torch.autograd.graph.saved_tensors_hooks):
 
 class _BitmapReLU(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x):
-        y = torch.relu(x)
-        if not (y.is_cuda and y.dtype in _SUPPORTED and y.is_contiguous()):
+    def forward(ctx, x, fused):
+        if not (x.is_cuda and x.dtype in _SUPPORTED and x.is_contiguous()):
             raise TypeError("bitmap_relu needs a contiguous float64/float32/float16/bfloat16 device tensor")
-        st = _state(y.device)
-        n = y.numel()
-        bitmap = torch.empty((n + 31) // 32, dtype=torch.int32, device=y.device)
-        empty = torch.empty(0, dtype=y.dtype, device=y.device)
+        st = _state(x.device)
+        n = x.numel()
+        bitmap = torch.empty((n + 31) // 32, dtype=torch.int32, device=x.device)
+        empty = torch.empty(0, dtype=x.dtype, device=x.device)
         # capacity 0: only the bitmap (and nnz) are produced, no value is written
-        bt.bt_compress(y, bitmap, empty, st.nnz, st.workspace(n, y.dtype))
+        if fused:
+            # one pass: y = x where x > 0 else +0, and y's bitmap (a NaN input gives 0 here, NaN in torch.relu)
+            y = torch.empty_like(x)
+            bt.bt_activation_compress(x, 0.0, y, bitmap, empty, st.nnz, st.workspace(n, x.dtype))
+        else:
+            y = torch.relu(x)
+            bt.bt_compress(y, bitmap, empty, st.nnz, st.workspace(n, y.dtype))
         ctx.bitmap = bitmap
         return y
 
@@ -127,9 +132,11 @@ class _BitmapReLU(torch.autograd.Function):
         grad_out = grad_out.contiguous()
         grad_in = torch.empty_like(grad_out)
         bt.bt_relu_backward_from_bitmap(ctx.bitmap, grad_out, grad_in)
-        return grad_in
+        return grad_in, None
 
 
-def bitmap_relu(x):
-    """ReLU that keeps only the 1-bit-per-element mask of its output for backward."""
-    return _BitmapReLU.apply(x)
+def bitmap_relu(x, fused=False):
+    """ReLU that keeps only the 1-bit-per-element mask of its output for backward.  fused=True computes the
+    output and the mask in one pass over x (bt_activation_compress) instead of torch.relu followed by a pass
+    over its output; the two differ only for NaN inputs (0 instead of NaN)."""
+    return _BitmapReLU.apply(x, fused)

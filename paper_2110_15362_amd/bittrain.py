@@ -61,6 +61,8 @@ def lib():
         L.bt_compress.argtypes = [vp, u64, ci, vp, vp, u64, vp, vp, sz, vp]
         L.bt_compress_pruned.restype = ci
         L.bt_compress_pruned.argtypes = [vp, u64, ci, ctypes.c_float, vp, vp, u64, vp, vp, sz, vp]
+        L.bt_activation_compress.restype = ci
+        L.bt_activation_compress.argtypes = [vp, u64, ci, ctypes.c_float, vp, vp, vp, u64, vp, vp, sz, vp]
         L.bt_decompress.restype = ci
         L.bt_decompress.argtypes = [vp, vp, u64, ci, vp, vp, sz, vp]
         L.bt_relu_backward_from_bitmap.restype = ci
@@ -345,3 +347,20 @@ def bt_stream_probe(src, dst, tiles, read_rows, write_rows, stream=None):
         raise ValueError("buffers too small for this many tiles")
     _check("bt_stream_probe", lib().bt_stream_probe(_ptr(src), _ptr(dst), tiles, read_rows, write_rows,
                                                     _stream(stream)))
+
+
+def bt_activation_compress(x, threshold, dense_out, bitmap, values, nnz, workspace, stream=None):
+    """One pass over x: dense_out = x where x > threshold else +0 (ReLU for threshold 0; dense_out may be x
+    itself), and bitmap / values / nnz = the compressed form of that dense_out."""
+    for t, name in ((x, "x"), (dense_out, "dense_out"), (bitmap, "bitmap"), (values, "values"), (nnz, "nnz"),
+                    (workspace, "workspace")):
+        _dev(t, name)
+    if values.dtype != x.dtype or dense_out.dtype != x.dtype or dense_out.numel() != x.numel():
+        raise TypeError("values and dense_out must match x")
+    if bitmap.element_size() != 4 or bitmap.numel() * 4 < bt_bitmap_bytes(x.numel()):
+        raise ValueError("bitmap must hold ceil(n/32) 32-bit words")
+    if nnz.element_size() != 8 or nnz.numel() < 1:
+        raise ValueError("nnz must be one 64-bit integer")
+    _check("bt_activation_compress", lib().bt_activation_compress(
+        _ptr(x), x.numel(), dtype_code(x.dtype), ctypes.c_float(threshold), _ptr(dense_out), _ptr(bitmap), _ptr(values),
+        values.numel(), _ptr(nnz), _ptr(workspace), _bytes(workspace), _stream(stream)))

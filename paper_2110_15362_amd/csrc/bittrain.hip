@@ -633,13 +633,13 @@ __device__ __forceinline__ void strip_commit(unsigned char *strip, const uint32_
 
 // One tile of one tensor: `tile` counts the tensor's own tiles (it addresses the data),
 // `slot` is the tile's entry in the workspace (equal to `tile` unless the call is batched).
-template <int S, int KEEP>
-__device__ __forceinline__ void compress_tile(const void *__restrict__ in, const uint64_t n,
+template <int S, int KEEP, bool DENSE = false>
+__device__ __forceinline__ void compress_tile(const void *in, const uint64_t n,
                                               uint32_t *__restrict__ bitmap, void *__restrict__ values,
                                               const uint64_t values_cap, char *ws, const uint32_t tile,
                                               const uint32_t slot, const uint32_t n_slots, const float threshold,
                                               unsigned char *s_stage, PrefixShared &s_prefix,
-                                              uint64_t *__restrict__ index = nullptr) {
+                                              uint64_t *__restrict__ index = nullptr, void *dense = nullptr) {
     using G = Geo<S>;
     constexpr int E = G::E;
     const int tid = threadIdx.x;
@@ -774,16 +774,43 @@ __device__ __forceinline__ void compress_tile(const void *__restrict__ in, const
         strip_store<S>(strip, gdst, pad, cnt, lane);
         g0 += phase_total;
     }
+
+    // (6) the dense tensor after pruning, if asked for (bt_activation_compress): what survives keeps its
+    //     bits, the rest is +0.  Last, so that no store precedes the polling loads of (4); `dense` may be
+    //     `in` itself (every lane rewrites exactly the vectors it has read).
+    if (DENSE) {
+#pragma unroll
+        for (int k = 0; k < kRows; ++k) {
+            const uint32_t mk = BT_MASK(S, mp, k);
+            uint32_t d[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
+            // masks by arithmetic (0 - bit is all ones or zero), not by compares: see nonzero_mask
+            if (S == 8) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) d[j] &= 0u - ((mk >> (j >> 1)) & 1u);
+            } else if (S == 4) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) d[j] &= 0u - ((mk >> j) & 1u);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    d[j] &= (((mk >> (2 * j)) & 1u) * 0x0000ffffu) | (((mk >> (2 * j + 1)) & 1u) * 0xffff0000u);
+            }
+            const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
+            const uint4 o = make_uint4(d[0], d[1], d[2], d[3]);
+            if (full) stream_store<kCompressNtStore>(reinterpret_cast<uint4 *>(static_cast<char *>(dense) + e0 * S), o);
+            else store_vec_guarded<S>(dense, e0, n, o);
+        }
+    }
 }
 
 // bt_compress / bt_compress_pruned: one tensor.  Workgroup 0 is the scanner, workgroup
 // t + 1 is tile t.
-template <int S, int KEEP>
-__global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restrict__ in, const uint64_t n,
+template <int S, int KEEP, bool DENSE>
+__global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *in, const uint64_t n,
                                                           uint32_t *__restrict__ bitmap, void *__restrict__ values,
                                                           const uint64_t values_cap, uint64_t *__restrict__ nnz_out,
                                                           char *ws, const uint32_t n_tiles, const float threshold,
-                                                          uint64_t *__restrict__ index) {
+                                                          uint64_t *__restrict__ index, void *dense) {
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
     __shared__ PrefixShared s_prefix;
     if (workspace_failed(ws)) return;
@@ -796,8 +823,8 @@ __global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *__restr
         return;
     }
     const uint32_t tile = blockIdx.x - 1;
-    compress_tile<S, KEEP>(in, n, bitmap, values, values_cap, ws, tile, tile, n_tiles, threshold, s_stage, s_prefix,
-                           index);
+    compress_tile<S, KEEP, DENSE>(in, n, bitmap, values, values_cap, ws, tile, tile, n_tiles, threshold, s_stage,
+                                  s_prefix, index, dense);
 }
 
 // Several tensors in one launch (bt_compress_batch): the kernel arguments carry the
@@ -1270,7 +1297,8 @@ bt_status bt_workspace_init(void *d_workspace, size_t workspace_bytes, bt_stream
 
 static bt_status compress_common(const void *d_in, uint64_t n, bt_dtype dtype, bool prune, float threshold,
                                  uint32_t *d_bitmap, void *d_values, uint64_t values_cap, uint64_t *d_nnz,
-                                 uint64_t *d_index, void *d_workspace, size_t workspace_bytes, bt_stream stream) {
+                                 uint64_t *d_index, void *d_dense, void *d_workspace, size_t workspace_bytes,
+                                 bt_stream stream) {
     const bt_status st = check_common(n, dtype, d_workspace, workspace_bytes);
     if (st != BT_OK) return st;
     if (d_nnz == nullptr) return BT_ERR_NULL;
@@ -1288,20 +1316,22 @@ static bt_status compress_common(const void *d_in, uint64_t n, bt_dtype dtype, b
     const uint32_t n_tiles = (uint32_t)tiles_for(n, s);
     char *ws = static_cast<char *>(d_workspace);
     const dim3 grid(n_tiles + 1), block(kBlock);
-#define BT_LAUNCH_COMPRESS(S_, KEEP_) \
-    compress_kernel<S_, KEEP_><<<grid, block, 0, hs>>>(d_in, n, d_bitmap, d_values, values_cap, d_nnz, ws, n_tiles, threshold, d_index)
+#define BT_LAUNCH_COMPRESS(S_, KEEP_, DENSE_) \
+    compress_kernel<S_, KEEP_, DENSE_><<<grid, block, 0, hs>>>(d_in, n, d_bitmap, d_values, values_cap, d_nnz, ws, n_tiles, threshold, d_index, d_dense)
     if (!prune) {
-        if (s == 8) BT_LAUNCH_COMPRESS(8, kKeepNonZero);
-        else if (s == 4) BT_LAUNCH_COMPRESS(4, kKeepNonZero);
-        else BT_LAUNCH_COMPRESS(2, kKeepNonZero);
-    } else if (dtype == BT_F64) {
-        BT_LAUNCH_COMPRESS(8, kKeepAboveF64);
-    } else if (dtype == BT_F32) {
-        BT_LAUNCH_COMPRESS(4, kKeepAboveF32);
-    } else if (dtype == BT_F16) {
-        BT_LAUNCH_COMPRESS(2, kKeepAboveF16);
+        if (s == 8) BT_LAUNCH_COMPRESS(8, kKeepNonZero, false);
+        else if (s == 4) BT_LAUNCH_COMPRESS(4, kKeepNonZero, false);
+        else BT_LAUNCH_COMPRESS(2, kKeepNonZero, false);
+    } else if (d_dense == nullptr) {
+        if (dtype == BT_F64) BT_LAUNCH_COMPRESS(8, kKeepAboveF64, false);
+        else if (dtype == BT_F32) BT_LAUNCH_COMPRESS(4, kKeepAboveF32, false);
+        else if (dtype == BT_F16) BT_LAUNCH_COMPRESS(2, kKeepAboveF16, false);
+        else BT_LAUNCH_COMPRESS(2, kKeepAboveBF16, false);
     } else {
-        BT_LAUNCH_COMPRESS(2, kKeepAboveBF16);
+        if (dtype == BT_F64) BT_LAUNCH_COMPRESS(8, kKeepAboveF64, true);
+        else if (dtype == BT_F32) BT_LAUNCH_COMPRESS(4, kKeepAboveF32, true);
+        else if (dtype == BT_F16) BT_LAUNCH_COMPRESS(2, kKeepAboveF16, true);
+        else BT_LAUNCH_COMPRESS(2, kKeepAboveBF16, true);
     }
 #undef BT_LAUNCH_COMPRESS
     return launched();
@@ -1310,15 +1340,26 @@ static bt_status compress_common(const void *d_in, uint64_t n, bt_dtype dtype, b
 bt_status bt_compress(const void *d_in, uint64_t n, bt_dtype dtype, uint32_t *d_bitmap, void *d_values,
                       uint64_t values_cap, uint64_t *d_nnz, void *d_workspace, size_t workspace_bytes,
                       bt_stream stream) {
-    return compress_common(d_in, n, dtype, false, 0.0f, d_bitmap, d_values, values_cap, d_nnz, nullptr, d_workspace,
-                           workspace_bytes, stream);
+    return compress_common(d_in, n, dtype, false, 0.0f, d_bitmap, d_values, values_cap, d_nnz, nullptr, nullptr,
+                           d_workspace, workspace_bytes, stream);
 }
 
 bt_status bt_compress_pruned(const void *d_in, uint64_t n, bt_dtype dtype, float threshold, uint32_t *d_bitmap,
                              void *d_values, uint64_t values_cap, uint64_t *d_nnz, void *d_workspace,
                              size_t workspace_bytes, bt_stream stream) {
-    return compress_common(d_in, n, dtype, true, threshold, d_bitmap, d_values, values_cap, d_nnz, nullptr, d_workspace,
-                           workspace_bytes, stream);
+    return compress_common(d_in, n, dtype, true, threshold, d_bitmap, d_values, values_cap, d_nnz, nullptr, nullptr,
+                           d_workspace, workspace_bytes, stream);
+}
+
+bt_status bt_activation_compress(const void *d_in, uint64_t n, bt_dtype dtype, float threshold, void *d_dense_out,
+                                 uint32_t *d_bitmap, void *d_values, uint64_t values_cap, uint64_t *d_nnz,
+                                 void *d_workspace, size_t workspace_bytes, bt_stream stream) {
+    if (elem_size(dtype) != 0 && n != 0 && n <= BT_MAX_ELEMENTS) {
+        if (d_dense_out == nullptr) return BT_ERR_NULL;
+        if (misaligned(d_dense_out, 16)) return BT_ERR_ALIGN;
+    }
+    return compress_common(d_in, n, dtype, true, threshold, d_bitmap, d_values, values_cap, d_nnz, nullptr, d_dense_out,
+                           d_workspace, workspace_bytes, stream);
 }
 
 size_t bt_tile_elems(bt_dtype dtype) {
@@ -1338,8 +1379,8 @@ bt_status bt_compress_indexed(const void *d_in, uint64_t n, bt_dtype dtype, uint
         if (d_index == nullptr) return BT_ERR_NULL;
         if (misaligned(d_index, 8)) return BT_ERR_ALIGN;
     }
-    return compress_common(d_in, n, dtype, false, 0.0f, d_bitmap, d_values, values_cap, d_nnz, d_index, d_workspace,
-                           workspace_bytes, stream);
+    return compress_common(d_in, n, dtype, false, 0.0f, d_bitmap, d_values, values_cap, d_nnz, d_index, nullptr,
+                           d_workspace, workspace_bytes, stream);
 }
 
 bt_status bt_decompress_indexed(const uint32_t *d_bitmap, const void *d_values, uint64_t values_cap,

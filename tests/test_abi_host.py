@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(bt):
     assert {"bt_compress", "bt_compressed_size", "bt_decompress", "bt_relu_backward_from_bitmap",
             "bt_compress_pruned", "bt_compress_batch", "bt_decompress_batch", "bt_batch_workspace_bytes",
             "bt_mask_apply", "bt_dense_size", "bt_coo_size", "bt_compress_indexed", "bt_decompress_indexed",
-            "bt_tile_elems", "bt_index_bytes", "bt_stream_probe"} <= set(names)
+            "bt_tile_elems", "bt_index_bytes", "bt_stream_probe", "bt_activation_compress"} <= set(names)
     raw = ctypes.CDLL(bt.LIB_PATH)
     for name in names:
         assert hasattr(raw, name), name
@@ -255,6 +255,19 @@ def test_tile_index_sizes_and_host_errors(bt):
     assert decompress(val=None) == 1                       # a capacity without a buffer
     assert decompress(out=A + 4) == 3 and decompress(idx=A + 2) == 3 and decompress(val=A + 2) == 3
     assert decompress(n=0, bm=None, val=None, cap=0, idx=None, out=None) == 0
+
+
+def test_activation_compress_host_errors(bt):
+    L = bt.lib()
+    A = 0x10000
+    wsb = bt.bt_workspace_bytes(1000, bt.BT_F32)
+
+    def call(d_in=A, n=1000, dt=bt.BT_F32, thr=0.0, dense=A + 0x10000, bm=A, val=A, cap=1000, nnz=A, ws=A, wsb=wsb):
+        return L.bt_activation_compress(d_in, n, dt, ctypes.c_float(thr), dense, bm, val, cap, nnz, ws, wsb, None)
+
+    assert call(dense=None) == 1 and call(dense=A + 8) == 3
+    assert call(dt=9) == 2 and call(d_in=None) == 1 and call(nnz=None) == 1 and call(bm=None) == 1
+    assert call(wsb=wsb - 1) == 4 and call(n=(1 << 37) + 1) == 6 and call(d_in=A + 4) == 3
 
 
 def test_stream_probe_host_errors(bt):

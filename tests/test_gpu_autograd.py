@@ -47,13 +47,17 @@ def test_saved_tensor_hooks_give_identical_gradients(ag, dtype):
     assert stash.stats["stored_bytes"] < 0.8 * stash.stats["dense_bytes"]
 
 
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
-def test_bitmap_relu_backward_matches_torch(ag, dtype):
+def test_bitmap_relu_backward_matches_torch(ag, dtype, fused):
     x, ws = _mlp(2, dtype)
-    _forward(x, ws, torch.relu).backward()
+    ref_loss = _forward(x, ws, torch.relu)
+    ref_loss.backward()
     ref = [t.grad.clone() for t in (x,) + ws]
     for t in (x,) + ws:
         t.grad = None
-    _forward(x, ws, ag.bitmap_relu).backward()
+    loss = _forward(x, ws, lambda t: ag.bitmap_relu(t, fused=fused))
+    loss.backward()
+    assert torch.equal(loss, ref_loss)
     for r, t in zip(ref, (x,) + ws):
         assert torch.equal(r, t.grad)

@@ -391,3 +391,52 @@ def test_stream_probe_stays_inside_its_buffers(gpu):
         assert bool((dst[dst.numel() - guard:] == 0x5A5A5A5A).all()), (r, w)
         if w:
             assert not bool((dst[:tiles * w * 1024] == 0x5A5A5A5A).all()), (r, w)
+
+
+@pytest.mark.parametrize("dt", DTYPES)
+def test_activation_compress_dense_and_stash_in_one_pass(gpu, oracle, dt):
+    """bt_activation_compress: the dense pruned tensor equals the oracle's pruning, the compressed form
+    equals Algorithm 1 on it; out of place and in place; ReLU for threshold 0."""
+    import paper_2110_15362_amd.bittrain as bt
+    dev = "cuda"
+    for i, n in enumerate([1, 33, 4097, 8193, 3 * 16384 + 5, 100003, 600001]):
+        x = wl.random_sparse(n, dt, 0.1, seed=8500 + i)
+        if n > 100:
+            x[:16] = wl.special_values(dt)
+        xb = wl.bits(x)
+        for thr in (0.0, 0.05, -0.5):
+            want_dense = oracle.prune(xb, dt, thr)
+            o_bitmap, o_values, o_nnz = oracle.compress(want_dense)
+            for inplace in (False, True):
+                pad = 16 // x.element_size()
+                xd = x.to(dev)
+                dbuf = xd if inplace else torch.empty(n + pad, dtype=x.dtype, device=dev)
+                if not inplace:
+                    dbuf.view(torch.uint8).fill_(0x5A)
+                dense = xd if inplace else dbuf[:n]
+                words = (n + 31) // 32
+                bitmap = torch.full((words + 4,), 0x5A5A5A5A, dtype=torch.int32, device=dev)
+                values = torch.empty(n + 8, dtype=x.dtype, device=dev)
+                values.view(torch.uint8).fill_(0x5A)
+                nnz = torch.full((1,), -7, dtype=torch.int64, device=dev)
+                ws = bt.new_workspace(n, x.dtype)
+                bt.bt_activation_compress(xd, thr, dense, bitmap[:words], values[:n], nnz, ws)
+                torch.cuda.synchronize()
+                assert int(nnz.item()) == o_nnz, (n, thr, inplace)
+                assert np.array_equal(wl.bits(dense.cpu()), want_dense), (n, thr, inplace)
+                assert np.array_equal(bitmap[:words].cpu().numpy().view(np.uint32), o_bitmap)
+                assert np.array_equal(wl.bits(values[:o_nnz].cpu()), o_values)
+                sent = np.frombuffer(bytes([0x5A] * x.element_size()), dtype=wl.bits(values.cpu()).dtype)[0]
+                assert (wl.bits(values[o_nnz:].cpu()) == sent).all() and bool((bitmap[words:] == 0x5A5A5A5A).all())
+                if not inplace:
+                    assert (wl.bits(dbuf[n:].cpu()) == sent).all(), "wrote past dense[n)"
+    # threshold 0 on pre-activations is ReLU
+    x = wl.random_sparse(50000, "f32", 0.0, seed=8600)
+    xd = x.to(dev)
+    y = torch.empty_like(xd)
+    bitmap = torch.empty((50000 + 31) // 32, dtype=torch.int32, device=dev)
+    values = torch.empty(50000, device=dev)
+    nnz = torch.zeros(1, dtype=torch.int64, device=dev)
+    bt.bt_activation_compress(xd, 0.0, y, bitmap, values, nnz, bt.new_workspace(50000, torch.float32))
+    torch.cuda.synchronize()
+    assert torch.equal(y, torch.relu(xd))
