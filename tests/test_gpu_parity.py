@@ -440,3 +440,30 @@ def test_activation_compress_dense_and_stash_in_one_pass(gpu, oracle, dt):
     bt.bt_activation_compress(xd, 0.0, y, bitmap, values, nnz, bt.new_workspace(50000, torch.float32))
     torch.cuda.synchronize()
     assert torch.equal(y, torch.relu(xd))
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16", "f64"])
+def test_bitmap_bits_beyond_n_are_ignored(gpu, oracle, dt):
+    """A bitmap whose last word carries set bits at positions >= n (not what bt_compress writes, but allowed
+    on input): Algorithm 2 and the select run over the n valid bits only."""
+    import paper_2110_15362_amd.bittrain as bt
+    for n in (5, 33, 8191, 3 * 16384 + 7, 100001):
+        x = wl.random_sparse(n, dt, 0.5, seed=9100 + n % 97)
+        o_bitmap, o_values, o_nnz = oracle.compress(wl.bits(x))
+        dirty = o_bitmap.copy()
+        dirty[-1] |= np.uint32((0xFFFFFFFF << (n % 32)) & 0xFFFFFFFF)          # n % 32 != 0 for these sizes
+        assert not np.array_equal(dirty, o_bitmap)
+        out, ok = gpu.gpu_decompress(dirty, o_values, n, x.dtype)
+        assert ok and np.array_equal(out, wl.bits(x))
+        g = torch.randn(n, generator=torch.Generator().manual_seed(n)).to(x.dtype)
+        got, ok = gpu.gpu_relu_backward(dirty, g)
+        assert ok and np.array_equal(got, oracle.relu_backward(o_bitmap, wl.bits(g)))
+        # the indexed restoration too
+        tile = bt.bt_tile_elems(x.dtype)
+        index = torch.from_numpy(oracle.tile_index(o_bitmap, n, tile).view(np.int64).copy()).cuda()
+        bm = torch.from_numpy(dirty.view(np.int32).copy()).cuda()
+        vals = x[x.view({2: torch.int16, 4: torch.int32, 8: torch.int64}[x.element_size()]) != 0].cuda()
+        outd = torch.empty(n, dtype=x.dtype, device="cuda")
+        bt.bt_decompress_indexed(bm, vals, index, outd)
+        torch.cuda.synchronize()
+        assert np.array_equal(wl.bits(outd.cpu()), wl.bits(x))
