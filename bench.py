@@ -257,6 +257,24 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / iters
 
+    def timed_batches(fn, iters, warm, batches=5):
+        """As timed(), with an event after every iters/batches calls: (average over all calls, median and
+        minimum of the batch averages), microseconds per call.  Nothing is synchronised between batches."""
+        batches = max(1, min(batches, iters))
+        per = iters // batches
+        for i in range(warm):
+            fn(i)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(batches + 1)]
+        ev[0].record(stream)
+        for b in range(batches):
+            for i in range(per):
+                fn(b * per + i)
+            ev[b + 1].record(stream)
+        torch.cuda.synchronize()
+        each = sorted(ev[b].elapsed_time(ev[b + 1]) * 1e3 / per for b in range(batches))
+        return ev[0].elapsed_time(ev[batches]) * 1e3 / (per * batches), each[len(each) // 2], each[0]
+
     K = max(1, args.sets)
     levels = [0.5] if args.only_z50 else [0.5, 0.7, 0.9]
     ops, headline = [], None
@@ -328,9 +346,10 @@ def main():
                               ("relu_backward", relu, alg_relu),
                               ("compress_indexed", compress_indexed, alg_codec + 8 * tiles),
                               ("decompress_indexed", decompress_indexed, alg_codec + 8 * tiles)):
-            cold = timed(fn, args.steps, args.warmup)
+            cold, cold_median, cold_min = timed_batches(fn, args.steps, args.warmup)
             warm = cold if args.cold_only else timed(lambda i, fn=fn: fn(0), args.steps, args.warmup)
-            row[name] = {"us_cold": round(cold, 2), "us_warm": round(warm, 2),
+            row[name] = {"us_cold": round(cold, 2), "us_cold_median_of_5_batches": round(cold_median, 2),
+                         "us_cold_min_of_5_batches": round(cold_min, 2), "us_warm": round(warm, 2),
                          "input_GBps_cold": round(n * s / cold / 1e3, 1), "input_GBps_warm": round(n * s / warm / 1e3, 1),
                          "algorithmic_bytes": alg,
                          "roofline_frac_cold": round(alg / cold / 1e3 / HBM_PEAK_GBPS, 4),
