@@ -500,3 +500,41 @@ def test_two_streams_with_their_own_workspaces(gpu, oracle):
             assert np.array_equal(wl.bits(b["values"][:o_nnz].cpu()), o_values)
             assert np.array_equal(wl.bits(b["out"].cpu()), wl.bits(x))
             assert int(b["ws"].view(torch.int32)[2].item()) == 0
+
+
+def _pattern_masks(n, tile):
+    """Zero / non-zero layouts whose run lengths sit on, just before and just after the sizes the kernels
+    work in: a 16-byte vector, a bitmap word, a wave row, a wave strip, a tile."""
+    i = np.arange(n)
+    row, strip = tile // 32, tile // 4
+    masks = {"alternate": i % 2 == 0, "every_32nd": i % 32 == 31, "every_33rd": i % 33 == 0,
+             "first_of_each_word_missing": i % 32 != 0, "dense_then_empty": i < n // 2, "empty_then_dense": i >= n // 2,
+             "only_the_last_tile": i >= (n // tile) * tile, "only_the_last_element": i == n - 1}
+    for name, period in (("row", row), ("strip", strip), ("tile", tile)):
+        masks["every_other_%s" % name] = (i // period) % 2 == 0
+        masks["runs_of_%s_minus_1" % name] = (i // (period - 1)) % 2 == 1
+        masks["runs_of_%s_plus_1" % name] = (i // (period + 1)) % 2 == 1
+        masks["one_per_%s" % name] = i % period == period - 1
+    rng = np.random.default_rng(17)
+    for block in (3, 64, 1000):
+        masks["random_blocks_of_%d" % block] = np.repeat(rng.random(n // block + 1) < 0.4, block)[:n]
+    return masks
+
+
+@pytest.mark.parametrize("dt", ["f32", "f16", "f64"])
+def test_structured_zero_patterns(gpu, oracle, dt):
+    """The ranks, the scatter through LDS and the tile offsets depend on where the zeros are, not
+    only on how many there are: run lengths on and around every internal size."""
+    tile = {"f32": 8192, "f16": 16384, "f64": 4096}[dt]
+    n = 3 * tile + tile // 4 + 37
+    base = wl.random_sparse(n, dt, 0.0, 23)                    # no zeros: every kept element is distinct enough
+    g = wl.random_sparse(n, dt, 0.0, 24)
+    assert int((wl.bits(base) == 0).sum()) == 0
+    for name, keep in _pattern_masks(n, tile).items():
+        x = base.clone()
+        x[torch.from_numpy(~keep)] = 0
+        o_bitmap, o_values, o_nnz = _check_compress(gpu, oracle, x)
+        assert o_nnz == int(keep.sum()), name
+        _check_decompress(gpu, oracle, o_bitmap, o_values, n, x.dtype, wl.bits(x))
+        out, guard_ok = gpu.gpu_relu_backward(o_bitmap, g)
+        assert np.array_equal(out, oracle.relu_backward(o_bitmap, wl.bits(g))) and guard_ok, name
