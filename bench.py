@@ -57,9 +57,77 @@ def parse():
                     help="skip the combined-step loop (in it decompress reads what compress just wrote, i.e. warm data)")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time configurations 1, 3, 4 and 5 (adds about a minute; reported under `other_configs`)")
+    ap.add_argument("--timeline", action="store_true",
+                    help="instead of timing: one cold bt_compress and bt_decompress of configuration 2 (50 %% zeros) with the "
+                         "instrumented build of the library, per-tile time stamps printed as a markdown table")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of the input tensor, as a known-size reference for counters")
     return ap.parse_args()
+
+
+def timeline(bt, wl, torch, dev, sets):
+    """Per-tile time stamps (bt_timeline_set, library built with -DBT_TIMELINE) of one cold bt_compress and one cold
+    bt_decompress of configuration 2 at 50 % zeros, as markdown on stdout."""
+    import numpy as np
+    from paper_2110_15362_amd import build as hip_build
+    if not os.path.exists(hip_build.TIMELINE_LIB):
+        print("bench.py --timeline: libbittrain_timeline.so is not built (run __graft_entry__.build())", file=sys.stderr)
+        sys.exit(2)
+    bt._lib, bt.LIB_PATH = None, hip_build.TIMELINE_LIB
+    bt.lib()
+    x = wl.config2(0.5)["x"].reshape(-1)
+    n, K = x.numel(), max(2, sets)
+    tiles = bt.bt_index_bytes(n, x.dtype) // 8
+    max_passes = 256
+    xs = [x.to(dev) for _ in range(K)]
+    bitmaps = [torch.empty((n + 31) // 32, dtype=torch.int32, device=dev) for _ in range(K)]
+    values = [torch.empty(n, dtype=x.dtype, device=dev) for _ in range(K)]
+    outs = [torch.empty(n, dtype=x.dtype, device=dev) for _ in range(K)]
+    nnz = torch.zeros(1, dtype=torch.int64, device=dev)
+    ws = bt.new_workspace(n, x.dtype, device=dev)
+    calls = {"bt_compress": lambda i: bt.bt_compress(xs[i % K], bitmaps[i % K], values[i % K], nnz, ws),
+             "bt_decompress": lambda i: bt.bt_decompress(bitmaps[i % K], values[i % K], outs[i % K], ws)}
+    print("# Per-tile timeline of one cold launch: configuration 2 (fp32 [32,256,56,56]), 50 %% zeros, %d tiles\n" % tiles)
+    print("Command: `python3 bench.py --timeline` (libbittrain_timeline.so is built by `__graft_entry__.build()`).  One launch each,\n"
+          "after a device synchronisation, so both run a few microseconds longer than the averages of the timed loops.\n")
+    print("Microseconds from the start of the first workgroup, read from the 100 MHz device clock inside the kernel\n"
+          "(library built with -DBT_TIMELINE; the stamps cost the kernel a few per cent).  `counted`: the tile has loaded\n"
+          "its input and counted it (the count is published next); `prefix`: it has seen its prefix; `issued` / `acked`:\n"
+          "its stores are issued / acknowledged.\n")
+    for name, fn in calls.items():
+        for i in range(K):
+            calls["bt_compress"](i)
+        for i in range(3 * K):
+            fn(i)
+        torch.cuda.synchronize()
+        buf = torch.zeros(8 * tiles + 2 * max_passes, dtype=torch.int64, device=dev)
+        bt.bt_timeline_set(buf, tiles, max_passes)
+        fn(1)
+        torch.cuda.synchronize()
+        bt.bt_timeline_set(None, 0, 0)
+        a = buf.cpu().numpy()
+        t = a[:8 * tiles].reshape(tiles, 8)
+        t0 = int(t[:, 0].min())
+        us = lambda v: (np.asarray(v, dtype=np.int64) - t0) / 100.0
+        assert (t[:, 0] <= t[:, 1]).all() and (t[:, 1] <= t[:, 2]).all() and (t[:, 2] <= t[:, 3]).all() and (t[:, 3] <= t[:, 4]).all()
+        print("## %s\n" % name)
+        print("| tile | started | counted | prefix | issued | acked | polls |\n|---|---|---|---|---|---|---|")
+        for k in sorted(set(list(range(0, tiles, max(1, tiles // 16))) + [2046, 2047, tiles - 1])):
+            if k < tiles:
+                r = t[k]
+                print("| %d | %.2f | %.2f | %.2f | %.2f | %.2f | %d |" % (k, us(r[0]), us(r[1]), us(r[2]), us(r[3]), us(r[4]), r[5]))
+        print("\nLast of all tiles: started %.2f, counted %.2f, prefix %.2f, issued %.2f, acked %.2f.\n"
+              % tuple(float(us(t[:, c].max())) for c in range(5)))
+        print("| µs | tiles started | counted | with prefix | finished |\n|---|---|---|---|---|")
+        end = float(us(t[:, 4].max()))
+        for g in np.arange(2.0, end + 2.0, 2.0):
+            print("| %.0f | %d | %d | %d | %d |" % (g, (us(t[:, 0]) <= g).sum(), (us(t[:, 1]) <= g).sum(),
+                                                 (us(t[:, 2]) <= g).sum(), (us(t[:, 4]) <= g).sum()))
+        p = a[8 * tiles:].reshape(max_passes, 2)
+        p = p[p[:, 0] != 0]
+        print("\nScanner passes that consumed counts (time, slots):", ", ".join(
+            "%.2f: %d–%d" % (float(us(tm)), int(ff) >> 32, int(ff) & 0xffffffff) for tm, ff in p), "\n")
+    assert torch.equal(outs[1].view(torch.int32), xs[1].view(torch.int32)), "round trip mismatch"
 
 
 def other_configs(bt, wl, torch, dev, timed, args):
@@ -243,6 +311,9 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     stream = torch.cuda.current_stream()
+    if args.timeline:
+        timeline(bt, wl, torch, dev, args.sets)
+        return
 
     def timed(fn, iters, warm):
         """Average microseconds per call of fn(i), HIP events on the launch stream."""

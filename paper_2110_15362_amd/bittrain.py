@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libbittrain.so")
 BT_F32, BT_F16, BT_BF16, BT_F64 = 0, 1, 2, 3
 BT_OK = 0
 STATUS_NAMES = {0: "BT_OK", 1: "BT_ERR_NULL", 2: "BT_ERR_DTYPE", 3: "BT_ERR_ALIGN", 4: "BT_ERR_WORKSPACE",
-                5: "BT_ERR_HIP", 6: "BT_ERR_SIZE"}
+                5: "BT_ERR_HIP", 6: "BT_ERR_SIZE", 7: "BT_ERR_UNSUPPORTED"}
 BT_MAX_ELEMENTS = 1 << 37
 
 _DTYPES = {torch.float32: BT_F32, torch.float16: BT_F16, torch.bfloat16: BT_BF16, torch.float64: BT_F64}
@@ -79,6 +79,8 @@ def lib():
         L.bt_decompress_indexed.argtypes = [vp, vp, u64, vp, u64, ci, vp, vp]
         L.bt_stream_probe.restype = ci
         L.bt_stream_probe.argtypes = [vp, vp, u64, ci, ci, vp]
+        L.bt_timeline_set.restype = ci
+        L.bt_timeline_set.argtypes = [vp, u64, ctypes.c_uint32, ctypes.c_uint32]
         L.bt_batch_workspace_bytes.restype = sz
         L.bt_batch_workspace_bytes.argtypes = [ctypes.POINTER(u64), sz, ci]
         L.bt_compress_batch.restype = ci
@@ -364,3 +366,15 @@ def bt_activation_compress(x, threshold, dense_out, bitmap, values, nnz, workspa
     _check("bt_activation_compress", lib().bt_activation_compress(
         _ptr(x), x.numel(), dtype_code(x.dtype), ctypes.c_float(threshold), _ptr(dense_out), _ptr(bitmap), _ptr(values),
         values.numel(), _ptr(nnz), _ptr(workspace), _bytes(workspace), _stream(stream)))
+
+
+def bt_timeline_set(buf, tiles, max_passes):
+    """Switch the per-tile time stamps on (buf: zeroed int64 device tensor) or off (buf None).  Only the
+    library built with -DBT_TIMELINE records anything; the regular one raises BT_ERR_UNSUPPORTED."""
+    if buf is None:
+        _check("bt_timeline_set", lib().bt_timeline_set(None, 0, 0, 0))
+        return
+    _dev(buf, "buf")
+    if buf.element_size() != 8:
+        raise ValueError("buf must be a tensor of 64-bit integers")
+    _check("bt_timeline_set", lib().bt_timeline_set(_ptr(buf), buf.numel(), tiles, max_passes))

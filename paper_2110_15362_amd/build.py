@@ -6,6 +6,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc", "bittrain.hip")
 LIB = os.path.join(HERE, "libbittrain.so")
+# the same source with per-tile time stamps compiled in (bt_timeline_set); used by `bench.py --timeline` only
+TIMELINE_LIB = os.path.join(HERE, "libbittrain_timeline.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
@@ -14,9 +16,9 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose=False, extra_flags=()):
+def build(verbose=False, extra_flags=(), lib=LIB):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-I", os.path.join(ROOT, "include"), SRC, "-o", LIB]
+    cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-I", os.path.join(ROOT, "include"), SRC, "-o", lib]
     if verbose:
         print(" ".join(cmd))
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -26,8 +28,13 @@ def build(verbose=False, extra_flags=()):
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
-    return LIB
+    return lib
+
+
+def build_timeline(verbose=False):
+    return build(verbose=verbose, extra_flags=("-DBT_TIMELINE",), lib=TIMELINE_LIB)
 
 
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_timeline(verbose=True))

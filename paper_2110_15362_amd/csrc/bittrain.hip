@@ -295,6 +295,29 @@ __device__ __forceinline__ uint32_t bitmap_bits(const uint32_t *bitmap, uint64_t
 // Entries are value + 1 (0 = not published), written and read with relaxed
 // device-scope atomics: the entry is the only thing that is communicated.
 
+// ---- timeline (only in a build with -DBT_TIMELINE) ---------------------------------------------
+// Every tile of a single-tensor bt_compress / bt_decompress launch leaves five times of the
+// 100 MHz device clock and its number of polls in the caller's buffer (8 words per tile: started,
+// counted, prefix seen, stores issued, stores acknowledged, polls), and the scanner two words per
+// pass that consumed something (time, first slot << 32 | end slot), after the tiles' words.
+#ifdef BT_TIMELINE
+__device__ uint64_t *g_timeline = nullptr;
+__device__ uint32_t g_timeline_tiles = 0, g_timeline_passes = 0;
+#define BT_TL(slot, k)                                                                            \
+    do {                                                                                          \
+        if (threadIdx.x == 0 && g_timeline != nullptr && (slot) < g_timeline_tiles)               \
+            g_timeline[8 * (size_t)(slot) + (k)] = wall_clock64();                                \
+    } while (0)
+#define BT_TL_VALUE(slot, k, v)                                                                   \
+    do {                                                                                          \
+        if (threadIdx.x == 0 && g_timeline != nullptr && (slot) < g_timeline_tiles)               \
+            g_timeline[8 * (size_t)(slot) + (k)] = (v);                                           \
+    } while (0)
+#else
+#define BT_TL(slot, k) do {} while (0)
+#define BT_TL_VALUE(slot, k, v) do {} while (0)
+#endif
+
 __device__ __forceinline__ uint64_t ws_load64(const void *p) {
     return __hip_atomic_load(static_cast<const uint64_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -373,6 +396,10 @@ __device__ __forceinline__ void scan_counts(char *ws, const Segments seg) {
     uint64_t running = 0;      // stored values of tensor `item` in its tiles before `frontier`
     uint32_t spins = 0;
     const uint32_t limit = wait_limit(hdr);
+#ifdef BT_TIMELINE
+    uint64_t *const timeline = g_timeline;      // read once: a load in the loop would join the scanner's waits
+    uint32_t timeline_pass = 0;
+#endif
     while (frontier < n_slots) {
         const uint32_t w0 = frontier & ~63u;
         uint32_t c[kScanRows];
@@ -423,6 +450,13 @@ __device__ __forceinline__ void scan_counts(char *ws, const Segments seg) {
             if (spin_expired<kScannerSleep>(hdr, spins, limit)) return;
             continue;
         }
+#ifdef BT_TIMELINE
+        if (timeline != nullptr && lane == 0 && timeline_pass < g_timeline_passes) {
+            timeline[8 * (size_t)g_timeline_tiles + 2 * timeline_pass] = wall_clock64();
+            timeline[8 * (size_t)g_timeline_tiles + 2 * timeline_pass + 1] = ((uint64_t)frontier << 32) | new_frontier;
+            ++timeline_pass;
+        }
+#endif
         frontier = new_frontier;
     }
     if (lane == 0) {
@@ -495,6 +529,7 @@ __device__ __forceinline__ uint64_t tile_prefix(char *ws, PrefixShared &sh, cons
 
     if (lane == 0) sh.wave_total[wave] = wave_total;
     __syncthreads();
+    BT_TL(slot, 1);
     if (tid == 0) {
         const uint32_t tile_total = sh.wave_total[0] + sh.wave_total[1] + sh.wave_total[2] + sh.wave_total[3];
         ws_store32(ws_count(ws, slot, cur), tile_total + 1);
@@ -509,6 +544,8 @@ __device__ __forceinline__ uint64_t tile_prefix(char *ws, PrefixShared &sh, cons
             if (spin_expired<kTileSleep>(hdr, spins, limit)) { v = 1; break; }
         }
         sh.tile_prefix = v - 1;
+        BT_TL(slot, 2);
+        BT_TL_VALUE(slot, 5, spins);
         if (index_entry != nullptr) *index_entry = v - 1;
     }
     __syncthreads();
@@ -823,8 +860,14 @@ __global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *in, con
         return;
     }
     const uint32_t tile = blockIdx.x - 1;
+    BT_TL(tile, 0);
     compress_tile<S, KEEP, DENSE>(in, n, bitmap, values, values_cap, ws, tile, tile, n_tiles, threshold, s_stage,
                                   s_prefix, index, dense);
+#ifdef BT_TIMELINE
+    BT_TL(tile, 3);
+    if (threadIdx.x == 0) __builtin_amdgcn_s_waitcnt(0);     // this wave's stores have been acknowledged
+    BT_TL(tile, 4);
+#endif
 }
 
 // Several tensors in one launch (bt_compress_batch): the kernel arguments carry the
@@ -1012,7 +1055,13 @@ __global__ __launch_bounds__(kBlock) void decompress_kernel(const uint32_t *__re
         return;
     }
     const uint32_t tile = blockIdx.x - 1;
+    BT_TL(tile, 0);
     decompress_tile<S>(bitmap, values, n, out, ws, tile, tile, n_tiles, s_stage, s_prefix);
+#ifdef BT_TIMELINE
+    BT_TL(tile, 3);
+    if (threadIdx.x == 0) __builtin_amdgcn_s_waitcnt(0);     // this wave's stores have been acknowledged
+    BT_TL(tile, 4);
+#endif
 }
 
 struct DecompressBatch {
@@ -1281,6 +1330,7 @@ const char *bt_status_str(bt_status status) {
         case BT_ERR_WORKSPACE: return "workspace too small";
         case BT_ERR_HIP: return "HIP launch failed";
         case BT_ERR_SIZE: return "element count too large";
+        case BT_ERR_UNSUPPORTED: return "not available in this build of the library";
     }
     return "unknown status";
 }
@@ -1464,6 +1514,23 @@ bt_status bt_stream_probe(const void *d_in, void *d_out, uint64_t tiles, int rea
     else if (read_rows == 0 && write_rows == 8) stream_probe_kernel<0, 8><<<grid, block, 0, hs>>>(in, out, t);
     else return BT_ERR_SIZE;
     return launched();
+}
+
+bt_status bt_timeline_set(uint64_t *d_buf, uint64_t buf_words, uint32_t tiles, uint32_t max_passes) {
+#ifdef BT_TIMELINE
+    if (d_buf == nullptr) tiles = max_passes = 0;
+    else if (misaligned(d_buf, 8)) return BT_ERR_ALIGN;
+    if (8 * (uint64_t)tiles + 2 * (uint64_t)max_passes > buf_words) return BT_ERR_SIZE;
+    // blocking copies: this call is the one place where the library waits for the device
+    if (hipMemcpyToSymbol(HIP_SYMBOL(g_timeline_tiles), &tiles, sizeof(tiles)) != hipSuccess ||
+        hipMemcpyToSymbol(HIP_SYMBOL(g_timeline_passes), &max_passes, sizeof(max_passes)) != hipSuccess ||
+        hipMemcpyToSymbol(HIP_SYMBOL(g_timeline), &d_buf, sizeof(d_buf)) != hipSuccess)
+        return BT_ERR_HIP;
+    return BT_OK;
+#else
+    (void)d_buf; (void)buf_words; (void)tiles; (void)max_passes;
+    return BT_ERR_UNSUPPORTED;
+#endif
 }
 
 size_t bt_batch_workspace_bytes(const uint64_t *n, size_t count, bt_dtype dtype) {

@@ -295,3 +295,21 @@ def test_workspace_bytes_cover_every_tile(bt):
             n = tiles * elems_per_tile
             assert bt.bt_workspace_bytes(n, code) == 256 + 768 * ((tiles + 31) // 32)
             assert bt.bt_workspace_bytes(n + 1, code) == 256 + 768 * ((tiles + 1 + 31) // 32)
+
+
+def test_timeline_is_a_build_option(bt):
+    """The regular library exports bt_timeline_set and says that it records nothing; the instrumented
+    build (same source, -DBT_TIMELINE) exports the same symbols and checks the buffer size on the host."""
+    import ctypes
+    from paper_2110_15362_amd import build as hip_build
+    assert bt.lib().bt_timeline_set(None, 0, 0, 0) == 7
+    assert bt.status_str(7) == "not available in this build of the library"
+    if not os.path.exists(hip_build.TIMELINE_LIB):
+        pytest.fail("libbittrain_timeline.so is not built: run __graft_entry__.build()")
+    T = ctypes.CDLL(hip_build.TIMELINE_LIB)
+    T.bt_timeline_set.restype = ctypes.c_int
+    T.bt_timeline_set.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32]
+    for name in _declared_functions():
+        assert hasattr(T, name), name
+    assert T.bt_timeline_set(0x10000, 8 * 100 + 2 * 10 - 1, 100, 10) == 6      # buffer one word too small
+    assert T.bt_timeline_set(0x10004, 8 * 100 + 2 * 10, 100, 10) == 3          # misaligned
