@@ -954,10 +954,20 @@ __device__ __forceinline__ void decompress_tile(const uint32_t *__restrict__ bit
     uint32_t mp[G::MW], rank2[kRows / 2], total2[kRows / 2];
 #pragma unroll
     for (int i = 0; i < G::MW; ++i) mp[i] = 0;
+    const bool full = (uint64_t)(tile + 1) * G::TILE <= n;
+    if (full) {
+        // every word of the tile exists and every bit of it counts: G lanes read the same word and take E bits each
+        const uint32_t *p = bitmap + (wave_e0 >> 5) + (uint32_t)(lane / G::G);
+        const uint32_t shift = (uint32_t)(lane % G::G) * E;
 #pragma unroll
-    for (int k = 0; k < kRows; ++k)
-        mp[k / G::RPM] |= bitmap_bits<S>(bitmap, wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E, n, n_words)
-                          << (E * (k % G::RPM));
+        for (int k = 0; k < kRows; ++k)
+            mp[k / G::RPM] |= ((p[k * G::WPR] >> shift) & ((1u << E) - 1u)) << (E * (k % G::RPM));
+    } else {
+#pragma unroll
+        for (int k = 0; k < kRows; ++k)
+            mp[k / G::RPM] |= bitmap_bits<S>(bitmap, wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E, n, n_words)
+                              << (E * (k % G::RPM));
+    }
     rank_rows<S>(mp, rank2, total2);
     uint32_t wave_total = 0;
 #pragma unroll
@@ -1001,7 +1011,6 @@ __device__ __forceinline__ void decompress_tile(const uint32_t *__restrict__ bit
         strip_fetch<S>(gsrc, pads[ph], cnts[ph], lane, fetched[ph]);
         g0 += phase_total;
     }
-    const bool full = (uint64_t)(tile + 1) * G::TILE <= n;
 #pragma unroll
     for (int ph = 0; ph < kPhases; ++ph) {
         if (ph != 0) wave_lds_sync();   // the previous phase's reads are done before the strip is reused
