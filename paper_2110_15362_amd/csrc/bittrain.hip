@@ -777,35 +777,34 @@ __device__ __forceinline__ void compress_tile(const void *in, const uint64_t n,
         uint32_t row_start = pad;
 #pragma unroll
         for (int k = r0; k < r0 + kPhaseRows; ++k) {
-            uint32_t r = row_start + BT_FIELD(rank2, k);
+            // byte offset of this lane's next kept element from the spare vector (negative: the strip lies before it)
+            int rb = ((int)(row_start + BT_FIELD(rank2, k)) - G::DUMP) * S;
+            unsigned char *const dump = strip + G::DUMP * S;
             const uint32_t mk = BT_MASK(S, mp, k);
             const uint32_t d[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
             // every element is written, a dropped one to a place nobody reads: a select on the address instead of
             // a branch around the write keeps the execution mask alone (half the instructions; measured 1 % on
             // compress, 4-8 % on the restoration of 16-bit tensors, where the same is done with the reads)
             if (S == 8) {
-                uint64_t *l = reinterpret_cast<uint64_t *>(strip);
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    const uint32_t keep = (mk >> j) & 1u;
-                    l[keep ? r : (uint32_t)G::DUMP] = ((uint64_t)d[2 * j + 1] << 32) | d[2 * j];
-                    r += keep;
+                    const int keep = (int)((mk >> j) & 1u);
+                    *reinterpret_cast<uint64_t *>(dump + __mul24(keep, rb)) = ((uint64_t)d[2 * j + 1] << 32) | d[2 * j];
+                    rb += keep * S;
                 }
             } else if (S == 4) {
-                uint32_t *l = reinterpret_cast<uint32_t *>(strip);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const uint32_t keep = (mk >> j) & 1u;
-                    l[keep ? r : (uint32_t)G::DUMP] = d[j];
-                    r += keep;
+                    const int keep = (int)((mk >> j) & 1u);
+                    *reinterpret_cast<uint32_t *>(dump + __mul24(keep, rb)) = d[j];
+                    rb += keep * S;
                 }
             } else {
-                uint16_t *l = reinterpret_cast<uint16_t *>(strip);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const uint32_t keep = (mk >> j) & 1u;
-                    l[keep ? r : (uint32_t)G::DUMP] = (uint16_t)(d[j >> 1] >> (16 * (j & 1)));
-                    r += keep;
+                    const int keep = (int)((mk >> j) & 1u);
+                    *reinterpret_cast<uint16_t *>(dump + __mul24(keep, rb)) = (uint16_t)(d[j >> 1] >> (16 * (j & 1)));
+                    rb += keep * S;
                 }
             }
             row_start += BT_FIELD(total2, k);
