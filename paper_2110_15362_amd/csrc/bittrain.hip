@@ -537,6 +537,10 @@ __device__ __forceinline__ uint64_t tile_prefix(char *ws, PrefixShared &sh, cons
         ws_store32(ws_count(ws, slot, cur), tile_total + 1);
     }
     zero_previous(ws, ep, slot, n_slots);
+    // what the waves before this one hold: read before the wait, so that after it only the prefix is missing
+    uint32_t before = 0;
+    for (uint32_t w = 0; w < wave; ++w) before += sh.wave_total[w];
+    before = (uint32_t)__builtin_amdgcn_readfirstlane((int)before);
     if (tid == 0) {
         uint64_t v;
         uint32_t spins = 0;
@@ -551,8 +555,7 @@ __device__ __forceinline__ uint64_t tile_prefix(char *ws, PrefixShared &sh, cons
         if (index_entry != nullptr) *index_entry = v - 1;
     }
     __syncthreads();
-    uint64_t prefix = sh.tile_prefix;
-    for (uint32_t w = 0; w < wave; ++w) prefix += sh.wave_total[w];
+    uint64_t prefix = sh.tile_prefix + before;
     // the same value in every lane: tell the compiler, so that addresses built on it stay scalar
     prefix = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(prefix >> 32)) << 32) |
              (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)prefix);
@@ -582,28 +585,39 @@ __device__ __forceinline__ void rank_rows(const uint32_t (&mp)[Geo<S>::MW], uint
 // stores.  LDS element `pad + i` corresponds to global element g0 + i, where pad makes
 // LDS byte 0 line up with a 16-byte boundary of the global buffer.  The first and
 // last vector go element by element, so nothing outside [g0, g0 + cnt) is touched.
+// All LDS reads of the inner vectors are issued before the first store and the two edge
+// vectors are left to 2 E lanes at the end: this runs after the tile has received its
+// prefix, where every instruction delays the tile's exit (a loop over the vectors with
+// the edge cases inside cost compress 2 % on fp32 and 6-7 % on 16-bit tensors).
 template <int S>
 __device__ __forceinline__ void strip_store(const unsigned char *strip, char *g0_ptr, const uint32_t pad,
                                             const uint32_t cnt, const int lane) {
     constexpr int E = Geo<S>::E;
+    static_assert(kPhaseRows * Geo<S>::ROW / E + 1 <= 2 + 4 * kWaveSize, "a phase must fit four inner vectors per lane");
     if (cnt == 0) return;
     char *gvec = g0_ptr - (size_t)pad * S;      // 16-byte aligned; may start before g0
-    const uint32_t lo_valid = pad, hi_valid = pad + cnt;
+    const uint32_t hi_valid = pad + cnt;
     const uint32_t n_vec = (hi_valid + E - 1) / E;
-    for (uint32_t v = lane; v < n_vec; v += kWaveSize) {
-        const uint32_t lo = v * E, hi = lo + E;
-        if (lo >= lo_valid && hi <= hi_valid) {
-            stream_store<kCompressNtStore>(reinterpret_cast<uint4 *>(gvec + (size_t)lo * S), *reinterpret_cast<const uint4 *>(strip + (size_t)lo * S));
-        } else {
+    // the inner vectors (all but the first and the last: at most 255, wholly inside the range), four to a lane
+    uint4 t[4];
 #pragma unroll
-            for (int j = 0; j < E; ++j) {
-                const uint32_t e = lo + j;
-                if (e >= lo_valid && e < hi_valid) {
-                    if (S == 8) reinterpret_cast<uint64_t *>(gvec)[e] = reinterpret_cast<const uint64_t *>(strip)[e];
-                    else if (S == 4) reinterpret_cast<uint32_t *>(gvec)[e] = reinterpret_cast<const uint32_t *>(strip)[e];
-                    else reinterpret_cast<uint16_t *>(gvec)[e] = reinterpret_cast<const uint16_t *>(strip)[e];
-                }
-            }
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t v = 1u + (uint32_t)lane + (uint32_t)kWaveSize * i;
+        if (v + 1 < n_vec) t[i] = *reinterpret_cast<const uint4 *>(strip + (size_t)v * kVecBytes);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t v = 1u + (uint32_t)lane + (uint32_t)kWaveSize * i;
+        if (v + 1 < n_vec) stream_store<kCompressNtStore>(reinterpret_cast<uint4 *>(gvec + (size_t)v * kVecBytes), t[i]);
+    }
+    // the first and the last vector, an element a lane: lane j < E element j of the first, lane E + j element j
+    // of the last, each only if it lies inside [pad, pad + cnt)
+    if (lane < 2 * E) {
+        const uint32_t e = lane < E ? (uint32_t)lane : (n_vec - 1) * E + (uint32_t)(lane - E);
+        if (e >= pad && e < hi_valid && (lane < E || n_vec > 1)) {
+            if (S == 8) reinterpret_cast<uint64_t *>(gvec)[e] = reinterpret_cast<const uint64_t *>(strip)[e];
+            else if (S == 4) reinterpret_cast<uint32_t *>(gvec)[e] = reinterpret_cast<const uint32_t *>(strip)[e];
+            else reinterpret_cast<uint16_t *>(gvec)[e] = reinterpret_cast<const uint16_t *>(strip)[e];
         }
     }
 }
