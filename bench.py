@@ -66,14 +66,12 @@ def parse():
 
 
 def timeline(bt, wl, torch, dev, sets):
-    """Per-tile time stamps (bt_timeline_set, library built with -DBT_TIMELINE) of one cold bt_compress and one cold
-    bt_decompress of configuration 2 at 50 % zeros, as markdown on stdout."""
+    """Per-tile time stamps (the measurement-aid build of the library, libbittrain_bench.so) of one cold bt_compress
+    and one cold bt_decompress of configuration 2 at 50 % zeros, as markdown on stdout."""
     import numpy as np
-    from paper_2110_15362_amd import build as hip_build
-    if not os.path.exists(hip_build.TIMELINE_LIB):
-        print("bench.py --timeline: libbittrain_timeline.so is not built (run __graft_entry__.build())", file=sys.stderr)
-        sys.exit(2)
-    bt._lib, bt.LIB_PATH = None, hip_build.TIMELINE_LIB
+    from paper_2110_15362_amd import bench_aids
+    bench_aids.lib()
+    bt._lib, bt.LIB_PATH = None, bench_aids.LIB_PATH          # the codec calls below are the instrumented ones
     bt.lib()
     x = wl.config2(0.5)["x"].reshape(-1)
     n, K = x.numel(), max(2, sets)
@@ -88,12 +86,12 @@ def timeline(bt, wl, torch, dev, sets):
     calls = {"bt_compress": lambda i: bt.bt_compress(xs[i % K], bitmaps[i % K], values[i % K], nnz, ws),
              "bt_decompress": lambda i: bt.bt_decompress(bitmaps[i % K], values[i % K], outs[i % K], ws)}
     print("# Per-tile timeline of one cold launch: configuration 2 (fp32 [32,256,56,56]), 50 %% zeros, %d tiles\n" % tiles)
-    print("Command: `python3 bench.py --timeline` (libbittrain_timeline.so is built by `__graft_entry__.build()`).  One launch each,\n"
+    print("Command: `python3 bench.py --timeline` (libbittrain_bench.so is built by `__graft_entry__.build()`).  One launch each,\n"
           "after a device synchronisation, so both run a few microseconds longer than the averages of the timed loops.\n")
-    print("Microseconds from the start of the first workgroup, read from the 100 MHz device clock inside the kernel\n"
-          "(library built with -DBT_TIMELINE; the stamps cost the kernel a few per cent).  `counted`: the tile has loaded\n"
-          "its input and counted it (the count is published next); `prefix`: it has seen its prefix; `issued` / `acked`:\n"
-          "its stores are issued / acknowledged.\n")
+    print("Microseconds from the first stamp of the launch, read from the 100 MHz device clock inside the kernel (the\n"
+          "measurement-aid build; the stamps cost the kernel a few per cent).  `asked`: the tile's loads have been asked\n"
+          "for; `counted`: its count has been published; `prefix`: the first wave of its workgroup has seen its prefix;\n"
+          "`issued`: that wave has issued the tile's stores.\n")
     for name, fn in calls.items():
         for i in range(K):
             calls["bt_compress"](i)
@@ -101,28 +99,28 @@ def timeline(bt, wl, torch, dev, sets):
             fn(i)
         torch.cuda.synchronize()
         buf = torch.zeros(8 * tiles + 2 * max_passes, dtype=torch.int64, device=dev)
-        bt.bt_timeline_set(buf, tiles, max_passes)
+        bench_aids.bt_timeline_set(buf, tiles, max_passes)
         fn(1)
         torch.cuda.synchronize()
-        bt.bt_timeline_set(None, 0, 0)
+        bench_aids.bt_timeline_set(None, 0, 0)
         a = buf.cpu().numpy()
         t = a[:8 * tiles].reshape(tiles, 8)
-        t0 = int(t[:, 0].min())
+        stamped = t[:, :4][t[:, :4] != 0]
+        t0 = int(stamped.min())
         us = lambda v: (np.asarray(v, dtype=np.int64) - t0) / 100.0
-        assert (t[:, 0] <= t[:, 1]).all() and (t[:, 1] <= t[:, 2]).all() and (t[:, 2] <= t[:, 3]).all() and (t[:, 3] <= t[:, 4]).all()
         print("## %s\n" % name)
-        print("| tile | started | counted | prefix | issued | acked | polls |\n|---|---|---|---|---|---|---|")
-        for k in sorted(set(list(range(0, tiles, max(1, tiles // 16))) + [2046, 2047, tiles - 1])):
+        print("| tile | asked | counted | prefix | issued |\n|---|---|---|---|---|")
+        for k in sorted(set(list(range(0, tiles, max(1, tiles // 16))) + [1022, 1023, 2046, 2047, tiles - 1])):
             if k < tiles:
                 r = t[k]
-                print("| %d | %.2f | %.2f | %.2f | %.2f | %.2f | %d |" % (k, us(r[0]), us(r[1]), us(r[2]), us(r[3]), us(r[4]), r[5]))
-        print("\nLast of all tiles: started %.2f, counted %.2f, prefix %.2f, issued %.2f, acked %.2f.\n"
-              % tuple(float(us(t[:, c].max())) for c in range(5)))
-        print("| µs | tiles started | counted | with prefix | finished |\n|---|---|---|---|---|")
-        end = float(us(t[:, 4].max()))
+                print("| %d | %.2f | %.2f | %.2f | %.2f |" % (k, us(r[0]), us(r[1]), us(r[2]), us(r[3])))
+        print("\nLast of all tiles: asked %.2f, counted %.2f, prefix %.2f, issued %.2f.\n"
+              % tuple(float(us(t[:, c].max())) for c in range(4)))
+        print("| µs | tiles asked for | counted | with prefix | stores issued |\n|---|---|---|---|---|")
+        end = float(us(t[:, 3].max()))
         for g in np.arange(2.0, end + 2.0, 2.0):
-            print("| %.0f | %d | %d | %d | %d |" % (g, (us(t[:, 0]) <= g).sum(), (us(t[:, 1]) <= g).sum(),
-                                                 (us(t[:, 2]) <= g).sum(), (us(t[:, 4]) <= g).sum()))
+            print("| %.0f | %d | %d | %d | %d |" % (g, ((t[:, 0] != 0) & (us(t[:, 0]) <= g)).sum(), ((t[:, 1] != 0) & (us(t[:, 1]) <= g)).sum(),
+                                                 ((t[:, 2] != 0) & (us(t[:, 2]) <= g)).sum(), ((t[:, 3] != 0) & (us(t[:, 3]) <= g)).sum()))
         p = a[8 * tiles:].reshape(max_passes, 2)
         p = p[p[:, 0] != 0]
         print("\nScanner passes that consumed counts (time, slots):", ", ".join(
@@ -302,6 +300,7 @@ def main():
     import numpy as np
     import torch
     import paper_2110_15362_amd.bittrain as bt
+    from paper_2110_15362_amd import bench_aids as aids
     from paper_2110_15362_amd import workloads as wl
 
     if not torch.cuda.is_available():
@@ -430,9 +429,9 @@ def main():
             # one tile per workgroup, 8 rows (32 KiB) read + 4 written for compress, 4 read + 8 written for
             # decompress (at 50 % zeros the compressed side is half the dense side, plus the bitmap's 3 %)
             tiles32k = n * s // 32768
-            tc = timed(lambda i: bt.bt_stream_probe(xs[i % K], values[i % K], tiles32k, 8, 4), args.steps, args.warmup)
-            td = timed(lambda i: bt.bt_stream_probe(values[i % K], outs[i % K], tiles32k, 4, 8), args.steps, args.warmup)
-            tcp = timed(lambda i: bt.bt_stream_probe(xs[i % K], outs[i % K], tiles32k, 8, 8), args.steps, args.warmup)
+            tc = timed(lambda i: aids.bt_stream_probe(xs[i % K], values[i % K], tiles32k, 8, 4), args.steps, args.warmup)
+            td = timed(lambda i: aids.bt_stream_probe(values[i % K], outs[i % K], tiles32k, 4, 8), args.steps, args.warmup)
+            tcp = timed(lambda i: aids.bt_stream_probe(xs[i % K], outs[i % K], tiles32k, 8, 8), args.steps, args.warmup)
             moved = tiles32k * 12 * 4096
             stream_ceiling = {"what": "dependency-free streams of the same shape (bt_stream_probe), cold",
                               "compress_like_us": round(tc, 2), "compress_like_frac": round(moved / tc / 1e3 / HBM_PEAK_GBPS, 4),

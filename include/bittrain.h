@@ -49,7 +49,7 @@ typedef enum {
     BT_ERR_ALIGN = 3,     /* a pointer is not aligned as documented */
     BT_ERR_WORKSPACE = 4, /* workspace smaller than bt_workspace_bytes(n, dtype) */
     BT_ERR_HIP = 5,       /* the HIP runtime refused the launch */
-    BT_ERR_SIZE = 6,      /* n is beyond BT_MAX_ELEMENTS (or, for the measurement aids, a size they do not take) */
+    BT_ERR_SIZE = 6,      /* n is beyond BT_MAX_ELEMENTS, or a size the call does not take */
     BT_ERR_UNSUPPORTED = 7 /* the call exists only in another build of the library */
 } bt_status;
 
@@ -290,34 +290,6 @@ bt_status bt_compress_batch(const bt_compress_item *items, size_t count, bt_dtyp
  * bt_decompress. */
 bt_status bt_decompress_batch(const bt_decompress_item *items, size_t count, bt_dtype dtype,
                               void *d_workspace, size_t workspace_bytes, bt_stream stream);
-
-/* ---- measurement aid -------------------------------------------------------------
- *
- * Not part of the method: a plain stream with the traffic shape of the codec kernels and
- * no dependency between workgroups, for callers (the benchmark) that want to know what
- * the memory system gives that shape at best.  Workgroup t of `tiles` reads read_rows
- * rows of 4 KiB from d_in and writes write_rows rows of 4 KiB to d_out, each contiguous:
- * d_in must hold tiles * read_rows * 4096 bytes and d_out tiles * write_rows * 4096 bytes
- * (at least 16 * tiles bytes when write_rows is 0), both 16-byte aligned.  d_out receives
- * arbitrary bytes.  (read_rows, write_rows) is one of (8,4) the compress shape at 50 %
- * zeros, (4,8) the decompress shape, (8,8), (8,0), (0,8); anything else: BT_ERR_SIZE. */
-bt_status bt_stream_probe(const void *d_in, void *d_out, uint64_t tiles, int read_rows, int write_rows,
-                          bt_stream stream);
-
-/* Also a measurement aid, and only in a build of the library with -DBT_TIMELINE (the regular
- * build exports the symbol and returns BT_ERR_UNSUPPORTED): from this call on, every
- * single-tensor bt_compress / bt_compress_pruned / bt_activation_compress / bt_compress_indexed /
- * bt_decompress launch records into d_buf, for each tile t < tiles, eight uint64 at
- * d_buf[8 * t]: the 100 MHz device clock when the tile's workgroup started, when it had counted
- * its elements, when it saw its prefix, when it had issued its stores and when those were
- * acknowledged, then the number of polls, and two unused words; and the scanner records, for
- * each of its first max_passes passes that consumed counts, two uint64 at
- * d_buf[8 * tiles + 2 * pass]: the clock, and (first slot << 32 | end slot) of the pass.
- * d_buf is device memory of buf_words uint64 (>= 8 * tiles + 2 * max_passes, else BT_ERR_SIZE),
- * 8-byte aligned, zeroed by the caller; d_buf == NULL switches recording off.  Unlike every other
- * call this one waits for the device (it copies to device variables), and recording calls must
- * not overlap.  Errors: BT_ERR_ALIGN, BT_ERR_SIZE, BT_ERR_HIP, BT_ERR_UNSUPPORTED. */
-bt_status bt_timeline_set(uint64_t *d_buf, uint64_t buf_words, uint32_t tiles, uint32_t max_passes);
 
 #ifdef __cplusplus
 }

@@ -77,10 +77,6 @@ def lib():
         L.bt_compress_indexed.argtypes = [vp, u64, ci, vp, vp, u64, vp, vp, vp, sz, vp]
         L.bt_decompress_indexed.restype = ci
         L.bt_decompress_indexed.argtypes = [vp, vp, u64, vp, u64, ci, vp, vp]
-        L.bt_stream_probe.restype = ci
-        L.bt_stream_probe.argtypes = [vp, vp, u64, ci, ci, vp]
-        L.bt_timeline_set.restype = ci
-        L.bt_timeline_set.argtypes = [vp, u64, ctypes.c_uint32, ctypes.c_uint32]
         L.bt_batch_workspace_bytes.restype = sz
         L.bt_batch_workspace_bytes.argtypes = [ctypes.POINTER(u64), sz, ci]
         L.bt_compress_batch.restype = ci
@@ -340,17 +336,6 @@ def bt_decompress_indexed(bitmap, values, index, out, stream=None):
         _stream(stream)))
 
 
-def bt_stream_probe(src, dst, tiles, read_rows, write_rows, stream=None):
-    """Measurement aid: a dependency-free stream of `tiles` workgroups reading read_rows and writing
-    write_rows 4 KiB rows each (see the C header)."""
-    _dev(src, "src")
-    _dev(dst, "dst")
-    if _bytes(src) < tiles * read_rows * 4096 or _bytes(dst) < max(tiles * write_rows * 4096, 16 * tiles):
-        raise ValueError("buffers too small for this many tiles")
-    _check("bt_stream_probe", lib().bt_stream_probe(_ptr(src), _ptr(dst), tiles, read_rows, write_rows,
-                                                    _stream(stream)))
-
-
 def bt_activation_compress(x, threshold, dense_out, bitmap, values, nnz, workspace, stream=None):
     """One pass over x: dense_out = x where x > threshold else +0 (ReLU for threshold 0; dense_out may be x
     itself), and bitmap / values / nnz = the compressed form of that dense_out."""
@@ -366,15 +351,3 @@ def bt_activation_compress(x, threshold, dense_out, bitmap, values, nnz, workspa
     _check("bt_activation_compress", lib().bt_activation_compress(
         _ptr(x), x.numel(), dtype_code(x.dtype), ctypes.c_float(threshold), _ptr(dense_out), _ptr(bitmap), _ptr(values),
         values.numel(), _ptr(nnz), _ptr(workspace), _bytes(workspace), _stream(stream)))
-
-
-def bt_timeline_set(buf, tiles, max_passes):
-    """Switch the per-tile time stamps on (buf: zeroed int64 device tensor) or off (buf None).  Only the
-    library built with -DBT_TIMELINE records anything; the regular one raises BT_ERR_UNSUPPORTED."""
-    if buf is None:
-        _check("bt_timeline_set", lib().bt_timeline_set(None, 0, 0, 0))
-        return
-    _dev(buf, "buf")
-    if buf.element_size() != 8:
-        raise ValueError("buf must be a tensor of 64-bit integers")
-    _check("bt_timeline_set", lib().bt_timeline_set(_ptr(buf), buf.numel(), tiles, max_passes))

@@ -6,8 +6,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc", "bittrain.hip")
 LIB = os.path.join(HERE, "libbittrain.so")
-# the same source with per-tile time stamps compiled in (bt_timeline_set); used by `bench.py --timeline` only
-TIMELINE_LIB = os.path.join(HERE, "libbittrain_timeline.so")
+# measurement aids for bench.py: the same kernels with per-tile time stamps compiled in, plus a plain stream
+BENCH_SRC = os.path.join(HERE, "csrc", "bench_aids.hip")
+BENCH_LIB = os.path.join(HERE, "libbittrain_bench.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
@@ -16,9 +17,9 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose=False, extra_flags=(), lib=LIB):
+def build(verbose=False, extra_flags=(), lib=LIB, src=SRC):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-I", os.path.join(ROOT, "include"), SRC, "-o", lib]
+    cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-I", os.path.join(ROOT, "include"), src, "-o", lib]
     if verbose:
         print(" ".join(cmd))
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -31,10 +32,10 @@ def build(verbose=False, extra_flags=(), lib=LIB):
     return lib
 
 
-def build_timeline(verbose=False):
-    return build(verbose=verbose, extra_flags=("-DBT_TIMELINE",), lib=TIMELINE_LIB)
+def build_bench_aids(verbose=False, extra_flags=()):
+    return build(verbose=verbose, extra_flags=extra_flags, lib=BENCH_LIB, src=BENCH_SRC)
 
 
 if __name__ == "__main__":
     print(build(verbose=True))
-    print(build_timeline(verbose=True))
+    print(build_bench_aids(verbose=True))

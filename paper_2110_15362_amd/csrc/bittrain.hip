@@ -3,7 +3,7 @@
 //
 // Section 3.2 of the paper defines the format (a bit per element plus the
 // non-zero elements in index order); Algorithm 1 builds it with a sequential
-// push loop and Algorithm 2 undoes it with a running counter j.  Both loops
+// append loop and Algorithm 2 undoes it with a running counter j.  Both loops
 // carry one dependency: the position of an element's value is the number of
 // non-zero elements before it.  On a GPU that is an exclusive prefix sum over
 // the non-zero predicate, and the kernels below compute it in ONE pass over the
@@ -13,13 +13,22 @@
 //   wave    packed DPP prefix sum of the per-lane popcounts (no LDS, no barrier)
 //   block   four wave totals through LDS
 //   grid    per-tile counts published in the workspace; one extra wave turns them
-//           into per-tile prefixes; a tile polls only its own prefix
+//           into per-tile prefixes; a wave polls only the prefix of its own tile
+//
+// The codec kernels are PERSISTENT: a launch has at most as many workgroups as the
+// device holds at once, and workgroup w works through tiles w, w + G, w + 2G, ...
+// (G workgroups).  Every workgroup of a launch is therefore running while any of them
+// waits, whatever order the hardware starts them in; and a workgroup does not sit on a
+// tile while it waits for that tile's prefix: compression parks the tile's values in
+// LDS and reads the next tile meanwhile, restoration publishes the counts of its later
+// tiles before it restores the first.
 //
 // There is no matrix contraction anywhere, so no MFMA: the path is bound by HBM
 // bandwidth and everything here is about moving each byte once, coalesced, and
-// about keeping enough bytes in flight while a tile waits for its prefix.
+// about keeping the memory system busy while prefixes are on their way.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include <type_traits>
 
 #include "bittrain.h"
@@ -29,20 +38,37 @@ namespace {
 constexpr int kWaveSize = 64;
 constexpr int kWaves = 4;                 // waves per block
 constexpr int kBlock = kWaveSize * kWaves;
-#ifndef BT_ROWS
-#define BT_ROWS 8
-#endif
-constexpr int kRows = BT_ROWS;            // 16-byte loads per lane per tile
-constexpr int kPhaseRows = 4;             // rows that go through a wave's LDS strip at a time
-#ifndef BT_LOAD_AHEAD
-#define BT_LOAD_AHEAD BT_ROWS
-#endif
-constexpr int kLoadAhead = BT_LOAD_AHEAD; // rows a wave has in flight while it reads its tile
+constexpr int kRows = 8;                  // 16-byte loads per lane per tile
+constexpr int kPhaseRows = 4;             // rows that are compacted / expanded through LDS at a time
 constexpr int kVecBytes = 16;
 #ifndef BT_RELU_ROWS
 #define BT_RELU_ROWS 1
 #endif
 constexpr int kReluRows = BT_RELU_ROWS;   // 16-byte vectors per lane in the ReLU-backward stream
+
+// Workgroups per compute unit (= waves per SIMD) the persistent kernels are built for.
+// Compression wants LDS (a quarter of a unit's 160 KiB per workgroup: room for the values of
+// about two tiles per wave), restoration wants waves.
+#ifndef BT_COMPRESS_OCC
+#define BT_COMPRESS_OCC 4
+#endif
+#ifndef BT_DECOMPRESS_OCC
+#define BT_DECOMPRESS_OCC 8
+#endif
+constexpr int kCompressOcc = BT_COMPRESS_OCC;
+constexpr int kDecompressOcc = BT_DECOMPRESS_OCC;
+// Bytes of LDS in which a compressing wave parks values that wait for their prefix.
+#ifndef BT_RING_BYTES
+#define BT_RING_BYTES 9728
+#endif
+constexpr int kRingBytes = BT_RING_BYTES;
+constexpr int kRingStride = kRingBytes + kVecBytes;   // + one vector that takes the writes of dropped elements
+constexpr int kQueue = 16;                            // parked phases per wave, at most
+// Tiles ahead of the one it restores for which a restoring workgroup has published its counts.
+#ifndef BT_COUNT_AHEAD
+#define BT_COUNT_AHEAD 4
+#endif
+constexpr int kCountAhead = BT_COUNT_AHEAD;
 
 // ---- workspace layout -----------------------------------------------------------------
 // Header (uint32 words), then one 768-byte record per 32 tiles.
@@ -76,12 +102,14 @@ template <int S> struct Geo {
     static constexpr int ROW = kWaveSize * E;        // elements per wave-wide load
     static constexpr int WAVE = kRows * ROW;         // elements per wave per tile
     static constexpr int TILE = kWaves * WAVE;       // elements per tile
-    static constexpr int LDS_WAVE = kPhaseRows * ROW * S + 2 * kVecBytes;  // staging bytes per wave: the rows of a phase, the
-                                                                          // shift to a 16-byte boundary, and a vector nobody reads
-    static constexpr int DUMP = (LDS_WAVE - kVecBytes) / S;             // element index of that vector in a wave's strip
+    static constexpr int TILE_WORDS = TILE / 32;     // bitmap words per tile
+    static constexpr int LANE_WORDS = TILE_WORDS / kWaveSize;   // of which a lane counts this many when a wave counts a tile
+    static constexpr int LDS_WAVE = kPhaseRows * ROW * S + 2 * kVecBytes;  // restoration's staging bytes per wave: the rows of a phase,
+                                                                          // the shift to a 16-byte boundary, and slack
     static constexpr int RPM = 32 / E;               // rows whose E-bit lane masks share one register
     static constexpr int MW = (kRows + RPM - 1) / RPM;   // registers that hold a lane's masks
     static_assert(kRows % kPhaseRows == 0 && kPhaseRows % 2 == 0, "rows are scanned two to a register");
+    static_assert(kPhaseRows * ROW * S + 2 * kVecBytes <= kRingBytes, "a phase must fit the ring");
 };
 
 // ---- wave-level primitives (all 64 lanes must be active) ---------------------
@@ -172,20 +200,21 @@ template <int S> __device__ __forceinline__ uint32_t nonzero_mask(const uint4 v)
 
 // Which elements of the 16-byte vector are stored.  KEEP = kKeepNonZero: Algorithm 1's
 // test (non-zero bit pattern).  Otherwise activation pruning (Section 4.3) followed by
-// that test, in one pass: an element survives pruning where its value exceeds
-// `threshold`, compared in single precision after widening (exact for half and
-// bfloat16; a double is compared with the threshold widened to double, also exact; a
-// NaN exceeds nothing), and is then stored if its bit pattern is non-zero (a +0.0 that
+// that test, in one pass: an element survives pruning where its value exceeds the
+// threshold, compared in single precision after widening (exact for half and
+// bfloat16; a double is compared in double precision with `threshold_f64`; a NaN
+// exceeds nothing), and is then stored if its bit pattern is non-zero (a +0.0 that
 // survives a negative threshold is still a zero for Algorithm 1).
 enum { kKeepNonZero = 0, kKeepAboveF32 = 1, kKeepAboveF16 = 2, kKeepAboveBF16 = 3, kKeepAboveF64 = 4 };
-template <int S, int KEEP> __device__ __forceinline__ uint32_t keep_mask(const uint4 v, const float threshold) {
+template <int S, int KEEP>
+__device__ __forceinline__ uint32_t keep_mask(const uint4 v, const float threshold, const double threshold_f64) {
     if (KEEP == kKeepNonZero) return nonzero_mask<S>(v);
     const uint32_t d[4] = {v.x, v.y, v.z, v.w};
     uint32_t m = 0;
     if (KEEP == kKeepAboveF64) {
 #pragma unroll
         for (int i = 0; i < 2; ++i)
-            m |= (__longlong_as_double((long long)(((uint64_t)d[2 * i + 1] << 32) | d[2 * i])) > (double)threshold ? 1u : 0u) << i;
+            m |= (__longlong_as_double((long long)(((uint64_t)d[2 * i + 1] << 32) | d[2 * i])) > threshold_f64 ? 1u : 0u) << i;
     } else if (KEEP == kKeepAboveF32) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) m |= (__uint_as_float(d[i]) > threshold ? 1u : 0u) << i;
@@ -277,31 +306,168 @@ __device__ __forceinline__ uint32_t bitmap_bits(const uint32_t *bitmap, uint64_t
     return m;
 }
 
+// ---- the tensors of a call ------------------------------------------------------------------
+//
+// A call works on one tensor or (the batched calls) on a list.  The tensors are laid end to
+// end in a numbering of SLOTS (= workspace entries): a call on one tensor has slot == tile;
+// a batched call starts every tensor at a multiple of 64 slots, so that a scanner row never
+// spans two tensors, and the slots between a tensor's last tile and the next tensor's first
+// slot belong to no tile ("idle": they publish a count of zero).  Prefixes restart at 0 with
+// every tensor and each tensor's total goes to its nnz.  The kernels see the call through a
+// small interface (count, start, tiles, at, and the per-tensor pointers) that the
+// single-tensor and the batched argument structs both provide; the per-tensor pointers of a
+// batched call travel as kernel arguments and are read with scalar loads.
+
+struct Slot {
+    uint32_t item;   // tensor of the call
+    uint32_t tile;   // tile inside that tensor
+    bool idle;       // the slot belongs to no tile
+};
+
+constexpr int kMaxBatchDecompress = BT_MAX_BATCH;   // tensors per launch: what keeps the kernel arguments under 4 KiB
+constexpr int kMaxBatchCompress = 52;
+
+template <int MAXB> struct BatchLayout {
+    uint32_t count;
+    uint32_t start[MAXB + 1];
+    uint32_t tiles[MAXB];
+    __device__ __forceinline__ Slot at(const uint32_t slot) const {
+        uint32_t lo = 0, hi = count;          // start[lo] <= slot < start[hi]
+        while (hi - lo > 1) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (slot >= start[mid]) lo = mid; else hi = mid;
+        }
+        const uint32_t tile = slot - start[lo];
+        return Slot{lo, tile, tile >= tiles[lo]};
+    }
+};
+
+struct CompressOne {
+    const void *in_;
+    uint64_t n_;
+    uint32_t *bitmap_;
+    void *values_;
+    uint64_t cap_;
+    uint64_t *nnz_;
+    uint64_t *index_;
+    void *dense_;
+    uint32_t tiles_;
+    __device__ __forceinline__ uint32_t count() const { return 1; }
+    __device__ __forceinline__ uint32_t start(uint32_t i) const { return i == 0 ? 0u : tiles_; }
+    __device__ __forceinline__ uint32_t slots() const { return tiles_; }
+    __device__ __forceinline__ uint32_t tiles(uint32_t) const { return tiles_; }
+    __device__ __forceinline__ Slot at(uint32_t slot) const { return Slot{0, slot, false}; }
+    __device__ __forceinline__ const void *in(uint32_t) const { return in_; }
+    __device__ __forceinline__ uint64_t n(uint32_t) const { return n_; }
+    __device__ __forceinline__ uint32_t *bitmap(uint32_t) const { return bitmap_; }
+    __device__ __forceinline__ void *values(uint32_t) const { return values_; }
+    __device__ __forceinline__ uint64_t cap(uint32_t) const { return cap_; }
+    __device__ __forceinline__ uint64_t *nnz(uint32_t) const { return nnz_; }
+    __device__ __forceinline__ uint64_t *index(uint32_t) const { return index_; }
+    __device__ __forceinline__ void *dense(uint32_t) const { return dense_; }
+};
+
+struct CompressMany {
+    BatchLayout<kMaxBatchCompress> lay;
+    const void *in_[kMaxBatchCompress];
+    uint64_t n_[kMaxBatchCompress];
+    uint32_t *bitmap_[kMaxBatchCompress];
+    void *values_[kMaxBatchCompress];
+    uint64_t cap_[kMaxBatchCompress];
+    uint64_t *nnz_[kMaxBatchCompress];
+    uint64_t *index_[kMaxBatchCompress];
+    void *dense_[kMaxBatchCompress];
+    __device__ __forceinline__ uint32_t count() const { return lay.count; }
+    __device__ __forceinline__ uint32_t start(uint32_t i) const { return lay.start[i]; }
+    __device__ __forceinline__ uint32_t slots() const { return lay.start[lay.count]; }
+    __device__ __forceinline__ uint32_t tiles(uint32_t i) const { return lay.tiles[i]; }
+    __device__ __forceinline__ Slot at(uint32_t slot) const { return lay.at(slot); }
+    __device__ __forceinline__ const void *in(uint32_t i) const { return in_[i]; }
+    __device__ __forceinline__ uint64_t n(uint32_t i) const { return n_[i]; }
+    __device__ __forceinline__ uint32_t *bitmap(uint32_t i) const { return bitmap_[i]; }
+    __device__ __forceinline__ void *values(uint32_t i) const { return values_[i]; }
+    __device__ __forceinline__ uint64_t cap(uint32_t i) const { return cap_[i]; }
+    __device__ __forceinline__ uint64_t *nnz(uint32_t i) const { return nnz_[i]; }
+    __device__ __forceinline__ uint64_t *index(uint32_t i) const { return index_[i]; }
+    __device__ __forceinline__ void *dense(uint32_t i) const { return dense_[i]; }
+};
+static_assert(sizeof(CompressMany) <= 3840, "kernel arguments of a batched compression");
+
+struct DecompressOne {
+    const uint32_t *bitmap_;
+    const void *values_;
+    uint64_t cap_;
+    const uint64_t *index_;
+    uint64_t n_;
+    void *out_;
+    uint32_t tiles_;
+    __device__ __forceinline__ uint32_t count() const { return 1; }
+    __device__ __forceinline__ uint32_t start(uint32_t i) const { return i == 0 ? 0u : tiles_; }
+    __device__ __forceinline__ uint32_t slots() const { return tiles_; }
+    __device__ __forceinline__ uint32_t tiles(uint32_t) const { return tiles_; }
+    __device__ __forceinline__ Slot at(uint32_t slot) const { return Slot{0, slot, false}; }
+    __device__ __forceinline__ const uint32_t *bitmap(uint32_t) const { return bitmap_; }
+    __device__ __forceinline__ const void *values(uint32_t) const { return values_; }
+    __device__ __forceinline__ uint64_t cap(uint32_t) const { return cap_; }
+    __device__ __forceinline__ const uint64_t *tile_index(uint32_t) const { return index_; }
+    __device__ __forceinline__ uint64_t n(uint32_t) const { return n_; }
+    __device__ __forceinline__ void *out(uint32_t) const { return out_; }
+    __device__ __forceinline__ uint64_t *nnz(uint32_t) const { return nullptr; }
+    __device__ __forceinline__ uint64_t *index(uint32_t) const { return nullptr; }
+};
+
+struct DecompressMany {
+    BatchLayout<kMaxBatchDecompress> lay;
+    const uint32_t *bitmap_[kMaxBatchDecompress];
+    const void *values_[kMaxBatchDecompress];
+    uint64_t cap_[kMaxBatchDecompress];
+    const uint64_t *index_[kMaxBatchDecompress];
+    uint64_t n_[kMaxBatchDecompress];
+    void *out_[kMaxBatchDecompress];
+    __device__ __forceinline__ uint32_t count() const { return lay.count; }
+    __device__ __forceinline__ uint32_t start(uint32_t i) const { return lay.start[i]; }
+    __device__ __forceinline__ uint32_t slots() const { return lay.start[lay.count]; }
+    __device__ __forceinline__ uint32_t tiles(uint32_t i) const { return lay.tiles[i]; }
+    __device__ __forceinline__ Slot at(uint32_t slot) const { return lay.at(slot); }
+    __device__ __forceinline__ const uint32_t *bitmap(uint32_t i) const { return bitmap_[i]; }
+    __device__ __forceinline__ const void *values(uint32_t i) const { return values_[i]; }
+    __device__ __forceinline__ uint64_t cap(uint32_t i) const { return cap_[i]; }
+    __device__ __forceinline__ const uint64_t *tile_index(uint32_t i) const { return index_[i]; }
+    __device__ __forceinline__ uint64_t n(uint32_t i) const { return n_[i]; }
+    __device__ __forceinline__ void *out(uint32_t i) const { return out_[i]; }
+    __device__ __forceinline__ uint64_t *nnz(uint32_t) const { return nullptr; }
+    __device__ __forceinline__ uint64_t *index(uint32_t) const { return nullptr; }
+};
+static_assert(sizeof(DecompressMany) <= 3840, "kernel arguments of a batched restoration");
+
 // ---- grid prefix ---------------------------------------------------------------------------
 //
 // The position of a tile's first value is the number of non-zero elements in all
 // tiles before it (Algorithm 1 appends in index order; Algorithm 2's counter j).
 // Tiles do not talk to each other.  Each tile publishes its count in the workspace;
 // ONE extra workgroup (workgroup 0, a single wave: the "scanner") reads the counts
-// in index order, up to 448 at a time, keeps the running sum, and writes every tile's
-// prefix back; a tile then polls its own prefix, one 8-byte load.  Per tile that
-// is one store and one polled load on lines shared with few other tiles.  (Having
-// every tile read its predecessors' counts itself -- a look-back window or a tree --
+// in index order, up to kScanRows x 64 at a time, keeps the running sum, and writes every
+// tile's prefix back; a wave then polls the prefix of its tile, one 8-byte load.  Per
+// tile that is one store and a few polled loads on lines shared with few other tiles.
+// (Having every tile read its predecessors' counts itself -- a look-back window or a tree --
 // makes a few hot lines that thousands of tiles read at once, and those reads
 // queue up at one memory channel.)
 //
-// Nothing a tile waits for depends on another tile having been started: the
-// scanner is workgroup 0, started first, and only waits for counts, which tiles
-// publish before they wait for anything.  Waits are bounded anyway (kSpinLimit).
+// Forward progress.  A launch never has more workgroups than the device can hold at the
+// same time (the host asks the runtime for the kernel's occupancy), so all of them,
+// scanner included, are running whatever the order in which they were started.  A
+// workgroup publishes the count of a tile without waiting for anything; the scanner
+// waits only for counts; a wave waits only for the scanner.  Waits are bounded anyway
+// (kSpinLimit): if the assumption were ever broken the call ends with the error word set.
 //
 // Entries are value + 1 (0 = not published), written and read with relaxed
 // device-scope atomics: the entry is the only thing that is communicated.
 
 // ---- timeline (only in a build with -DBT_TIMELINE) ---------------------------------------------
-// Every tile of a single-tensor bt_compress / bt_decompress launch leaves five times of the
-// 100 MHz device clock and its number of polls in the caller's buffer (8 words per tile: started,
-// counted, prefix seen, stores issued, stores acknowledged, polls), and the scanner two words per
-// pass that consumed something (time, first slot << 32 | end slot), after the tiles' words.
+// Every slot of a bt_compress / bt_decompress launch leaves times of the 100 MHz device
+// clock in the caller's buffer (8 words per slot: loads asked for, counted, prefix seen, stores
+// issued, -, polls), and the scanner two words per pass that consumed something (time, first
+// slot << 32 | end slot), after the slots' words.
 #ifdef BT_TIMELINE
 __device__ uint64_t *g_timeline = nullptr;
 __device__ uint32_t g_timeline_tiles = 0, g_timeline_passes = 0;
@@ -338,6 +504,12 @@ __device__ __forceinline__ char *ws_prefix(char *ws, uint32_t tile, uint32_t cop
     return ws + kHeaderBytes + (size_t)(tile >> 5) * kRecordBytes + 256u + 256u * copy + 8u * (tile & 31u);
 }
 
+// The same value in every lane: tell the compiler, so that what is built on it stays in scalar registers.
+__device__ __forceinline__ uint32_t uniform32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ uint64_t uniform64(uint64_t v) {
+    return ((uint64_t)uniform32((uint32_t)(v >> 32)) << 32) | uniform32((uint32_t)v);
+}
+
 // Polls after which a wait is given up: what the caller asked for in the header, else the
 // built-in limit.  Read once, before the wait (a load inside the polling loop would
 // lengthen every poll by a round trip).
@@ -359,40 +531,25 @@ template <int SLEEP> __device__ __forceinline__ bool spin_expired(uint32_t *hdr,
 }
 
 // The scanner: one wave.  Each pass looks at kScanRows x 64 counts starting at the
-// frontier rounded down to a multiple of 64; lane l of row j looks at tile
+// frontier rounded down to a multiple of 64; lane l of row j looks at slot
 // w0 + 64*j + l, so every load and store of a row is one contiguous run.  The pass
 // takes the leading run of published counts, turns it into prefixes (a wave prefix
 // sum per row, carried from row to row), writes them, and moves the frontier.
 // When a tensor's counts are all in it writes the tensor's total (nnz); at the end it
-// advances the header for the next call.
-// Rows per pass, measured on MI355X (25.7 M fp32 elements, cold, compress / decompress
-// microseconds at 50 % zeros): 2 rows 39.0 / 36.8, 4 rows 34.9 / 33.5, 6 rows 33.6 / 33.6,
-// 7 rows 33.4 / 33.9, 8 rows 33.6 / 34.0, 16 rows 35.2 / 34.2, 32 rows 37.4 / 36.6 (at 90 % zeros
-// 6 rows cost compress 0.9): a pass costs a load round trip whatever its width, but a
-// wider pass waits for the slowest of more loads.
+// advances the header for the next call.  If the call wants a tile index (Algorithm 2's j at
+// every tile start, for bt_decompress_indexed) the prefixes of real tiles also go there.
 #ifndef BT_SCAN_ROWS
 #define BT_SCAN_ROWS 7
 #endif
 constexpr int kScanRows = BT_SCAN_ROWS;
-// What the scanner has to know about the tensors of one call.  A call on one tensor
-// has one segment, slots == tiles.  A batched call lays its tensors end to end in
-// the slot (= workspace entry) numbering, each starting at a multiple of 64 slots, so
-// that a scanner row never spans two tensors; the slots between a tensor's last tile
-// and the next tensor's first slot belong to no tile, and their workgroups publish a
-// count of zero.  Prefixes restart at 0 with every tensor, and each tensor's total
-// goes to its nnz.
-struct Segments {
-    uint32_t count;           // tensors
-    const uint32_t *start;    // count + 1 entries: first slot of tensor i; start[count] = slots of the call
-    uint64_t *const *nnz;     // where tensor i's number of stored values goes; the array or an entry may be null
-};
 
-__device__ __forceinline__ void scan_counts(char *ws, const Segments seg) {
+template <class Job> __device__ __forceinline__ void scan_counts(char *ws, const Job &job) {
     const uint32_t lane = threadIdx.x & (kWaveSize - 1);
     uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
     const uint32_t seq = hdr[kHdrSeq];
     const uint32_t cur = seq & 1u;
-    const uint32_t n_slots = seg.start[seg.count];
+    const uint32_t n_items = job.count();
+    const uint32_t n_slots = job.slots();
     uint32_t frontier = 0;     // slots [0, frontier) are done
     uint32_t item = 0;         // tensor that slot `frontier` belongs to
     uint64_t running = 0;      // stored values of tensor `item` in its tiles before `frontier`
@@ -434,16 +591,21 @@ __device__ __forceinline__ void scan_counts(char *ws, const Segments seg) {
                 const uint32_t run = bad == 0 ? 64u : (uint32_t)__ffsll((unsigned long long)bad) - 1u;
                 const uint32_t row_end = row0 + run;                               // slots [row0, row_end) usable
                 if (row_end > new_frontier) {
-                    while (item + 1 < seg.count && row0 >= seg.start[item + 1]) ++item;
-                    if (row0 == seg.start[item] && new_frontier <= row0) running = 0;   // a new tensor begins
+                    while (item + 1 < n_items && row0 >= job.start(item + 1)) ++item;
+                    const uint32_t item_start = job.start(item);
+                    if (row0 == item_start && new_frontier <= row0) running = 0;   // a new tensor begins
                     const bool fresh = t >= frontier && t < row_end;
                     const uint32_t mine = fresh ? c[j] - 1u : 0u;
                     const uint32_t incl = wave_inclusive_sum(mine);
-                    if (fresh) ws_store64(ws_prefix(ws, t, cur), running + (incl - mine) + 1);
+                    const uint64_t excl = running + (incl - mine);
+                    if (fresh) ws_store64(ws_prefix(ws, t, cur), excl + 1);
+                    uint64_t *const index = job.index(item);
+                    if (fresh && index != nullptr && t - item_start < job.tiles(item)) index[t - item_start] = excl;
                     running += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
                     new_frontier = row_end;
-                    if (row_end == seg.start[item + 1] && lane == 0 && seg.nnz != nullptr && seg.nnz[item] != nullptr)
-                        *seg.nnz[item] = running;                                  // length(B.values) of this tensor
+                    uint64_t *const nnz = job.nnz(item);
+                    if (row_end == job.start(item + 1) && lane == 0 && nnz != nullptr)
+                        *nnz = running;                                            // the length of this tensor's value array
                 }
                 open = run == 64u;
             }
@@ -462,7 +624,8 @@ __device__ __forceinline__ void scan_counts(char *ws, const Segments seg) {
         frontier = new_frontier;
     }
     if (lane == 0) {
-        // every tile has published its count by now, hence has read the header: advance it
+        // every workgroup of the launch has at least one slot and has published its count by now, hence has
+        // read the header: advance it
         __hip_atomic_store(&hdr[kHdrPrevTiles], n_slots, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(&hdr[kHdrSeq], seq + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -475,14 +638,9 @@ __device__ __forceinline__ bool workspace_failed(const char *ws) {
     return reinterpret_cast<const uint32_t *>(ws)[kHdrError] != 0;
 }
 
-struct PrefixShared {
-    uint32_t wave_total[kWaves];
-    uint64_t tile_prefix;
-};
-
 // What a workgroup reads from the header before it publishes anything.  The scanner
-// rewrites the header once every slot of the call has published, so a workgroup must
-// not read it after its own publication.
+// rewrites the header once every slot of the call has published, so no wave may read it
+// after any wave of its workgroup has published a count.
 struct Epoch {
     uint32_t cur;          // copy of the entries this call uses
     uint32_t prev_slots;   // entries the previous call used in the other copy
@@ -494,72 +652,29 @@ __device__ __forceinline__ Epoch read_epoch(const char *ws) {
 }
 
 // Zero what the previous call left in the other copy of the workspace entries: slots
-// [0, prev_slots), shared out over the threads of all slots of this call.
-__device__ __forceinline__ void zero_previous(char *ws, const Epoch ep, const uint32_t slot, const uint32_t n_slots) {
+// [0, prev_slots), shared out over the threads of this call's `workers` workgroups.
+__device__ __forceinline__ void zero_previous(char *ws, const Epoch ep, const uint32_t worker, const uint32_t workers) {
     const uint32_t other = ep.cur ^ 1u;
-    for (uint32_t i = slot + (uint32_t)threadIdx.x * n_slots; i < ep.prev_slots; i += kBlock * n_slots) {
-        ws_store32(ws_count(ws, i, other), 0);
-        ws_store64(ws_prefix(ws, i, other), 0);
+    for (uint64_t i = (uint64_t)worker * kBlock + threadIdx.x; i < ep.prev_slots; i += (uint64_t)workers * kBlock) {
+        ws_store32(ws_count(ws, (uint32_t)i, other), 0);
+        ws_store64(ws_prefix(ws, (uint32_t)i, other), 0);
     }
 }
 
-// A slot of a batched call that belongs to no tile: it publishes an empty count, so
-// that the scanner knows its workgroup has read the header, and does its share of
-// the clean-up.
-__device__ __forceinline__ void idle_slot(char *ws, const uint32_t slot, const uint32_t n_slots) {
-    const Epoch ep = read_epoch(ws);
-    __syncthreads();       // every thread has read the header
-    if (threadIdx.x == 0) ws_store32(ws_count(ws, slot, ep.cur), 1);
-    zero_previous(ws, ep, slot, n_slots);
-}
-
-// Run by every thread of a tile's block: publishes the tile's count in its slot, waits
-// for the scanner's answer, and returns the number of stored values of this tensor
-// before this wave's part of the tile (wave-uniform).  Contains two block barriers.
-// If `index_entry` is not null the tile's own prefix is also written there (the tile index
-// that bt_compress_indexed leaves for bt_decompress_indexed).
-__device__ __forceinline__ uint64_t tile_prefix(char *ws, PrefixShared &sh, const uint32_t slot,
-                                                const uint32_t n_slots, const uint32_t wave_total,
-                                                uint64_t *index_entry = nullptr) {
-    const int tid = threadIdx.x;
-    const uint32_t lane = tid & (kWaveSize - 1), wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);
-    uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
-    // written at the end of the previous call; constant until every slot of this call has published
-    const Epoch ep = read_epoch(ws);
-    const uint32_t cur = ep.cur;
-    const uint32_t limit = wait_limit(hdr);
-
-    if (lane == 0) sh.wave_total[wave] = wave_total;
-    __syncthreads();
-    BT_TL(slot, 1);
-    if (tid == 0) {
-        const uint32_t tile_total = sh.wave_total[0] + sh.wave_total[1] + sh.wave_total[2] + sh.wave_total[3];
-        ws_store32(ws_count(ws, slot, cur), tile_total + 1);
+// Wait for the scanner's answer for `slot`: the number of stored values of the slot's tensor before
+// the slot's tile.  Run by whole waves (all lanes load the same 8 bytes).  A wait that runs out
+// answers 0, which keeps every access of the caller inside the tile's own share of the buffers.
+__device__ __forceinline__ uint64_t wait_prefix(char *ws, const uint32_t slot, const uint32_t cur, uint32_t *hdr,
+                                                const uint32_t limit, uint32_t &polls) {
+    uint32_t spins = 0;
+    uint64_t v;
+    for (;;) {
+        v = uniform64(ws_load64(ws_prefix(ws, slot, cur)));
+        if (v != 0) break;
+        if (spin_expired<kTileSleep>(hdr, spins, limit)) { v = 1; break; }
     }
-    zero_previous(ws, ep, slot, n_slots);
-    // what the waves before this one hold: read before the wait, so that after it only the prefix is missing
-    uint32_t before = 0;
-    for (uint32_t w = 0; w < wave; ++w) before += sh.wave_total[w];
-    before = (uint32_t)__builtin_amdgcn_readfirstlane((int)before);
-    if (tid == 0) {
-        uint64_t v;
-        uint32_t spins = 0;
-        for (;;) {
-            v = ws_load64(ws_prefix(ws, slot, cur));
-            if (v != 0) break;
-            if (spin_expired<kTileSleep>(hdr, spins, limit)) { v = 1; break; }
-        }
-        sh.tile_prefix = v - 1;
-        BT_TL(slot, 2);
-        BT_TL_VALUE(slot, 5, spins);
-        if (index_entry != nullptr) *index_entry = v - 1;
-    }
-    __syncthreads();
-    uint64_t prefix = sh.tile_prefix + before;
-    // the same value in every lane: tell the compiler, so that addresses built on it stay scalar
-    prefix = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(prefix >> 32)) << 32) |
-             (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)prefix);
-    return prefix;
+    polls += spins + 1;
+    return v - 1;
 }
 
 // A lane's E-bit non-zero masks of all rows, packed RPM rows to a register.
@@ -581,21 +696,41 @@ __device__ __forceinline__ void rank_rows(const uint32_t (&mp)[Geo<S>::MW], uint
 }
 #define BT_FIELD(arr2, k) (((arr2)[(k) / 2] >> (16 * ((k) & 1))) & 0xffffu)
 
-// Write `cnt` elements from a wave's LDS strip to global memory with aligned 16-byte
-// stores.  LDS element `pad + i` corresponds to global element g0 + i, where pad makes
-// LDS byte 0 line up with a 16-byte boundary of the global buffer.  The first and
-// last vector go element by element, so nothing outside [g0, g0 + cnt) is touched.
-// All LDS reads of the inner vectors are issued before the first store and the two edge
-// vectors are left to 2 E lanes at the end: this runs after the tile has received its
-// prefix, where every instruction delays the tile's exit (a loop over the vectors with
-// the edge cases inside cost compress 2 % on fp32 and 6-7 % on 16-bit tensors).
+// ---- Algorithm 1: dense -> bitmap -------------------------------------------------------
+
+// 16 bytes from LDS at an address that is only element-aligned.
+template <int S> __device__ __forceinline__ uint4 lds_read16(const unsigned char *p, const bool odd_half) {
+    if (S == 8) {
+        const uint64_t a = reinterpret_cast<const uint64_t *>(p)[0], b = reinterpret_cast<const uint64_t *>(p)[1];
+        return make_uint4((uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32));
+    }
+    if (S == 4 || !odd_half) {
+        const uint32_t *q = reinterpret_cast<const uint32_t *>(p);
+        return make_uint4(q[0], q[1], q[2], q[3]);
+    }
+    // 2-byte elements at an odd element position: five aligned words, shifted down by 16 bits
+    const uint32_t *q = reinterpret_cast<const uint32_t *>(p - 2);
+    const uint32_t d0 = q[0], d1 = q[1], d2 = q[2], d3 = q[3], d4 = q[4];
+    return make_uint4(__builtin_amdgcn_alignbit(d1, d0, 16), __builtin_amdgcn_alignbit(d2, d1, 16),
+                      __builtin_amdgcn_alignbit(d3, d2, 16), __builtin_amdgcn_alignbit(d4, d3, 16));
+}
+
+// Write `cnt` elements that a wave has parked in LDS, starting at `data` (16-byte aligned, with
+// 16 bytes of slack before it and after the last element), to global memory at g0_ptr with
+// aligned 16-byte stores.  Global vector v (counted from the 16-byte boundary at or before
+// g0_ptr) takes LDS elements v * E - pad ..., pad being g0_ptr's distance from that boundary in
+// elements; the first and the last vector go element by element, so nothing outside
+// [g0_ptr, g0_ptr + cnt) is touched.  All LDS reads of the inner vectors are issued before the
+// first store.
 template <int S>
-__device__ __forceinline__ void strip_store(const unsigned char *strip, char *g0_ptr, const uint32_t pad,
-                                            const uint32_t cnt, const int lane) {
+__device__ __forceinline__ void ring_flush(const unsigned char *data, char *g0_ptr, const uint32_t cnt, const int lane) {
     constexpr int E = Geo<S>::E;
     static_assert(kPhaseRows * Geo<S>::ROW / E + 1 <= 2 + 4 * kWaveSize, "a phase must fit four inner vectors per lane");
     if (cnt == 0) return;
-    char *gvec = g0_ptr - (size_t)pad * S;      // 16-byte aligned; may start before g0
+    const uint32_t pad = (uint32_t)(reinterpret_cast<uintptr_t>(g0_ptr) & (kVecBytes - 1)) / S;
+    char *gvec = g0_ptr - (size_t)pad * S;      // 16-byte aligned; may start before g0_ptr
+    const unsigned char *src = data - (size_t)pad * S;   // LDS address of gvec's first element
+    const bool odd_half = S == 2 && (pad & 1u) != 0;
     const uint32_t hi_valid = pad + cnt;
     const uint32_t n_vec = (hi_valid + E - 1) / E;
     // the inner vectors (all but the first and the last: at most 255, wholly inside the range), four to a lane
@@ -603,7 +738,7 @@ __device__ __forceinline__ void strip_store(const unsigned char *strip, char *g0
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t v = 1u + (uint32_t)lane + (uint32_t)kWaveSize * i;
-        if (v + 1 < n_vec) t[i] = *reinterpret_cast<const uint4 *>(strip + (size_t)v * kVecBytes);
+        if (v + 1 < n_vec) t[i] = lds_read16<S>(src + (size_t)v * kVecBytes, odd_half);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -615,17 +750,309 @@ __device__ __forceinline__ void strip_store(const unsigned char *strip, char *g0
     if (lane < 2 * E) {
         const uint32_t e = lane < E ? (uint32_t)lane : (n_vec - 1) * E + (uint32_t)(lane - E);
         if (e >= pad && e < hi_valid && (lane < E || n_vec > 1)) {
-            if (S == 8) reinterpret_cast<uint64_t *>(gvec)[e] = reinterpret_cast<const uint64_t *>(strip)[e];
-            else if (S == 4) reinterpret_cast<uint32_t *>(gvec)[e] = reinterpret_cast<const uint32_t *>(strip)[e];
-            else reinterpret_cast<uint16_t *>(gvec)[e] = reinterpret_cast<const uint16_t *>(strip)[e];
+            if (S == 8) reinterpret_cast<uint64_t *>(gvec)[e] = reinterpret_cast<const uint64_t *>(src)[e];
+            else if (S == 4) reinterpret_cast<uint32_t *>(gvec)[e] = reinterpret_cast<const uint32_t *>(src)[e];
+            else reinterpret_cast<uint16_t *>(gvec)[e] = reinterpret_cast<const uint16_t *>(src)[e];
         }
     }
 }
 
-// The reverse direction in two steps, so that the loads of several phases can be in
+// bt_compress and its relatives.  Workgroup 0 is the scanner; workgroup w + 1 works through
+// slots w, w + G, w + 2G, ... of the call (G = gridDim.x - 1).  For each of its tiles a
+// workgroup
+//   (1) reads the tile (8 x 16 bytes per lane; a wave reads 8 KiB contiguous) and takes
+//       Algorithm 1's test on every element (optionally after the pruning of Section 4.3),
+//   (2) ranks the kept elements inside each wave (DPP prefix sums) and writes the bitmap words,
+//   (3) adds up the four waves' totals through LDS and publishes the tile's count,
+//   (4) compacts each wave's kept elements, a phase of 4 rows at a time, into that wave's
+//       ring in LDS, where they wait for the tile's prefix,
+// and goes on to its next tile.  The prefix of the OLDEST parked tile is asked for together with
+// the next tile's loads and looked at when those have arrived: by then it is usually there, and
+// the parked values leave with aligned 16-byte stores while the tile that has just arrived is
+// counted.  Only when the ring cannot take another phase does a wave stop and wait for a
+// prefix.  What is left in the rings at the end is waited for and written out.
+template <int S, int KEEP, bool DENSE, class Job>
+__global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Job job, char *ws, const double threshold) {
+    using G = Geo<S>;
+    constexpr int E = G::E;
+    __shared__ __attribute__((aligned(16))) unsigned char s_ring[kWaves * kRingStride];
+    __shared__ uint32_t s_wave_total[2][kWaves];
+    if (workspace_failed(ws)) return;
+    const uint32_t n_slots = job.slots();
+    if (blockIdx.x == 0) {
+        if (threadIdx.x < kWaveSize) scan_counts(ws, job);
+        return;
+    }
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWaveSize - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in a scalar register
+    const uint32_t worker = blockIdx.x - 1, workers = gridDim.x - 1;
+    uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
+    // written at the end of the previous call; constant until every slot of this call has published
+    const Epoch ep = read_epoch(ws);
+    const uint32_t cur = ep.cur;
+    const uint32_t limit = wait_limit(hdr);
+    zero_previous(ws, ep, worker, workers);
+    const float threshold_f = (float)threshold;
+
+    // This wave's ring: phases of compacted values, first in first out.  An entry occupies
+    // [start, start + 32 + its values rounded up to 16 bytes): 16 bytes of slack, the values,
+    // slack.  Entries never wrap: one that does not fit behind the newest goes to the front.
+    // The queue itself lives in four vector registers, entry i in lane i.
+    unsigned char *const ring = s_ring + wave * kRingStride;
+    unsigned char *const dump = ring + kRingBytes;     // takes the writes of dropped elements; never read
+    uint32_t q_place = 0, q_slot = 0, q_before = 0, q_item = 0;   // start | count << 16; slot; values of the tile before it; tensor
+    uint32_t q_head = 0, q_n = 0;        // oldest entry, number of entries
+    uint32_t r_head = 0, r_tail = 0;     // ring bytes [r_head, r_tail) are in use (cyclically)
+    uint32_t polls = 0;
+    uint32_t barriers = 0;
+
+#define BT_Q(field, i) ((uint32_t)__builtin_amdgcn_readlane((int)(field), (int)uniform32((i) & (kQueue - 1))))
+    // write the oldest entry's values to global memory, given its tile's prefix, and free its ring space
+    auto flush_head = [&](const uint64_t prefix) {
+        const uint32_t place = BT_Q(q_place, q_head), before = BT_Q(q_before, q_head), item = BT_Q(q_item, q_head);
+        const uint32_t start = place & 0xffffu;
+        uint32_t cnt = place >> 16;
+        const uint64_t g0 = prefix + before;
+        const uint64_t cap = job.cap(item);
+        // capacity clamp: never write at or beyond values_cap
+        if (g0 >= cap) cnt = 0;
+        else if (cap - g0 < cnt) cnt = (uint32_t)(cap - g0);
+        ring_flush<S>(ring + start + kVecBytes, static_cast<char *>(job.values(item)) + g0 * S, cnt, lane);
+        wave_lds_sync();                 // the reads are done before the space is written again
+        ++q_head;
+        --q_n;
+        r_head = q_n != 0 ? (BT_Q(q_place, q_head) & 0xffffu) : r_tail;
+    };
+
+    for (uint32_t slot = worker; slot < n_slots; slot += workers) {
+        const Slot sl = job.at(slot);
+        if (sl.idle) {                   // a slot of a batched call that belongs to no tile
+            if (tid == 0) ws_store32(ws_count(ws, slot, cur), 1);
+            if ((uint64_t)slot + workers >= n_slots) break;
+            continue;
+        }
+        const void *const in = job.in(sl.item);
+        const uint64_t n = job.n(sl.item);
+        const uint64_t n_words = (n + 31) >> 5;
+        const uint64_t wave_e0 = (uint64_t)sl.tile * G::TILE + (uint64_t)wave * G::WAVE;
+        const bool full = (uint64_t)(sl.tile + 1) * G::TILE <= n;
+
+        // (1) load: lane l of row k owns elements wave_e0 + k*ROW + l*E ... + E-1; all rows are
+        //     asked for at once.  Then Algorithm 1's test "T[i] == 0", on the bit pattern.
+        uint4 x[kRows];
+        uint32_t mp[G::MW], rank2[kRows / 2], total2[kRows / 2];
+#pragma unroll
+        for (int i = 0; i < G::MW; ++i) mp[i] = 0;
+        if (full) {
+            const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const char *>(in) + wave_e0 * S) + lane;
+#pragma unroll
+            for (int k = 0; k < kRows; ++k) x[k] = stream_load<kCompressNtLoad>(p + k * kWaveSize);
+        } else {
+#pragma unroll
+            for (int k = 0; k < kRows; ++k)
+                x[k] = load_vec_guarded<S>(in, wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E, n);
+        }
+        BT_TL(slot, 0);
+        // the oldest parked tile's prefix: asked for behind the loads, it comes back with them
+        const uint32_t polled_slot = q_n != 0 ? BT_Q(q_slot, q_head) : 0u;
+        uint64_t polled = 0;
+        if (q_n != 0) { polled = ws_load64(ws_prefix(ws, polled_slot, cur)); ++polls; }
+        if (full) {
+#pragma unroll
+            for (int k = 0; k < kRows; ++k) {
+                uint32_t mk = keep_mask<S, KEEP>(x[k], threshold_f, threshold);
+                asm volatile("" : "+v"(mk));             // row k has arrived: its mask exists from here on
+                mp[k / G::RPM] |= mk << (E * (k % G::RPM));
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < kRows; ++k) {
+                const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
+                // elements at or beyond n read as 0, which a negative threshold would keep: mask them
+                const uint32_t in_range = e0 >= n ? 0u : (n - e0 >= (uint64_t)E ? (1u << E) - 1u : (1u << (uint32_t)(n - e0)) - 1u);
+                mp[k / G::RPM] |= (keep_mask<S, KEEP>(x[k], threshold_f, threshold) & in_range) << (E * (k % G::RPM));
+            }
+        }
+        // Keep the masks as values of their own: otherwise the compiler keeps one compare
+        // result (a scalar register pair) per element alive until the values are written.
+#pragma unroll
+        for (int i = 0; i < G::MW; ++i) asm volatile("" : "+v"(mp[i]));
+        rank_rows<S>(mp, rank2, total2);
+        uint32_t wave_total = 0;
+#pragma unroll
+        for (int k = 0; k < kRows; ++k) wave_total += BT_FIELD(total2, k);
+
+        // (3) block total -> count for the scanner; what the waves before this one hold
+        const uint32_t par = barriers & 1u;
+        ++barriers;
+        if (lane == 0) s_wave_total[par][wave] = wave_total;
+        __syncthreads();
+        const uint32_t t0 = s_wave_total[par][0], t1 = s_wave_total[par][1], t2 = s_wave_total[par][2],
+                       t3 = s_wave_total[par][3];
+        if (tid == 0) ws_store32(ws_count(ws, slot, cur), t0 + t1 + t2 + t3 + 1);
+        BT_TL(slot, 1);
+        const uint32_t before_wave = uniform32((wave > 0 ? t0 : 0u) + (wave > 1 ? t1 : 0u) + (wave > 2 ? t2 : 0u));
+
+        // (2) the bitmap words: G lanes OR their E-bit masks into one 32-bit word; lane (g*G + i)
+        //     keeps the word of row r0 + i, group g: one store per G rows.
+        {
+            const int g = lane / G::G, i = lane % G::G;
+            uint32_t *const bitmap = job.bitmap(sl.item);
+#pragma unroll
+            for (int r0 = 0; r0 < kRows; r0 += G::G) {
+                uint32_t word = 0;
+#pragma unroll
+                for (int k = r0; k < r0 + G::G && k < kRows; ++k) {
+                    const uint32_t wk = group_or<G::G>(BT_MASK(S, mp, k) << (uint32_t)(E * i));
+                    if (i == k - r0) word = wk;
+                }
+                const uint64_t widx = (wave_e0 >> 5) + (uint64_t)(r0 + i) * G::WPR + (uint64_t)g;
+                if (r0 + i < kRows && widx < n_words) bitmap[widx] = word;
+            }
+        }
+
+        // the oldest parked tile, if its prefix has come
+        if (q_n != 0) {
+            const uint64_t v = uniform64(polled);
+            if (v != 0) {
+                BT_TL(polled_slot, 2);
+                while (q_n != 0 && BT_Q(q_slot, q_head) == polled_slot) flush_head(v - 1);
+                BT_TL(polled_slot, 3);
+            }
+        }
+
+        // (4) kPhaseRows rows at a time, compact this wave's kept elements into its ring.  (A call
+        //     that has no room for any value -- the bitmap alone is wanted -- skips this.)
+        if (job.cap(sl.item) != 0) {
+            uint32_t before = before_wave;
+#pragma unroll
+            for (int r0 = 0; r0 < kRows; r0 += kPhaseRows) {
+                uint32_t cnt = 0;
+#pragma unroll
+                for (int k = r0; k < r0 + kPhaseRows; ++k) cnt += BT_FIELD(total2, k);
+                cnt = uniform32(cnt);
+                const uint32_t need = 2 * kVecBytes + ((cnt * S + kVecBytes - 1) & ~(uint32_t)(kVecBytes - 1));
+                uint32_t start = 0;
+                for (;;) {
+                    bool fits = false;
+                    if (q_n == 0) {
+                        r_head = r_tail = 0;
+                        fits = true;
+                    } else if (q_n < (uint32_t)kQueue) {
+                        if (r_tail > r_head) {           // in use: one run; free: behind it and before it
+                            if (need <= (uint32_t)kRingBytes - r_tail) { start = r_tail; fits = true; }
+                            else if (need <= r_head) { start = 0; fits = true; }
+                        } else if (need <= r_head - r_tail) {   // in use: the two ends; free: the middle
+                            start = r_tail;
+                            fits = true;
+                        }
+                    }
+                    if (fits) break;
+                    // no room: the oldest entry has to leave first, however long its prefix takes
+                    const uint32_t s_old = BT_Q(q_slot, q_head);
+                    const uint64_t prefix = wait_prefix(ws, s_old, cur, hdr, limit, polls);
+                    BT_TL(s_old, 2);
+                    flush_head(prefix);
+                    BT_TL(s_old, 3);
+                }
+                r_tail = start + need;
+                {
+                    const uint32_t qi = (q_head + q_n) & (kQueue - 1);
+                    const bool me = (uint32_t)lane == qi;
+                    q_place = me ? (start | (cnt << 16)) : q_place;
+                    q_slot = me ? slot : q_slot;
+                    q_before = me ? before : q_before;
+                    q_item = me ? sl.item : q_item;
+                    ++q_n;
+                }
+                before += cnt;
+                // every element is written, a dropped one to a place nobody reads: a select on the address
+                // instead of a branch around the write keeps the execution mask alone
+                const int data_rel = (int)(start + kVecBytes) - kRingBytes;     // of the entry's first value, from `dump`
+                uint32_t row_start = 0;
+#pragma unroll
+                for (int k = r0; k < r0 + kPhaseRows; ++k) {
+                    int rb = data_rel + (int)(row_start + BT_FIELD(rank2, k)) * S;
+                    const uint32_t mk = BT_MASK(S, mp, k);
+                    const uint32_t d[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
+                    if (S == 8) {
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            const int keep = (int)((mk >> j) & 1u);
+                            *reinterpret_cast<uint64_t *>(dump + __mul24(keep, rb)) = ((uint64_t)d[2 * j + 1] << 32) | d[2 * j];
+                            rb += keep * S;
+                        }
+                    } else if (S == 4) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int keep = (int)((mk >> j) & 1u);
+                            *reinterpret_cast<uint32_t *>(dump + __mul24(keep, rb)) = d[j];
+                            rb += keep * S;
+                        }
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const int keep = (int)((mk >> j) & 1u);
+                            *reinterpret_cast<uint16_t *>(dump + __mul24(keep, rb)) = (uint16_t)(d[j >> 1] >> (16 * (j & 1)));
+                            rb += keep * S;
+                        }
+                    }
+                    row_start += BT_FIELD(total2, k);
+                }
+            }
+            wave_lds_sync();             // the values are in the ring before anything reads them
+        }
+
+        // (5) the dense tensor after pruning, if asked for (bt_activation_compress): what survives keeps its
+        //     bits, the rest is +0.  The output may be the input itself (every lane rewrites exactly the
+        //     vectors it has read).
+        if (DENSE) {
+            void *const dense = job.dense(sl.item);
+#pragma unroll
+            for (int k = 0; k < kRows; ++k) {
+                const uint32_t mk = BT_MASK(S, mp, k);
+                uint32_t d[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
+                // masks by arithmetic (0 - bit is all ones or zero), not by compares: see nonzero_mask
+                if (S == 8) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) d[j] &= 0u - ((mk >> (j >> 1)) & 1u);
+                } else if (S == 4) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) d[j] &= 0u - ((mk >> j) & 1u);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        d[j] &= (((mk >> (2 * j)) & 1u) * 0x0000ffffu) | (((mk >> (2 * j + 1)) & 1u) * 0xffff0000u);
+                }
+                const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
+                const uint4 o = make_uint4(d[0], d[1], d[2], d[3]);
+                if (full) stream_store<kCompressNtStore>(reinterpret_cast<uint4 *>(static_cast<char *>(dense) + e0 * S), o);
+                else store_vec_guarded<S>(dense, e0, n, o);
+            }
+        }
+        if ((uint64_t)slot + workers >= n_slots) break;      // (slot += workers must not wrap)
+    }
+
+    // what is still parked
+    while (q_n != 0) {
+        const uint32_t s_old = BT_Q(q_slot, q_head);
+        const uint64_t prefix = wait_prefix(ws, s_old, cur, hdr, limit, polls);
+        BT_TL(s_old, 2);
+        while (q_n != 0 && BT_Q(q_slot, q_head) == s_old) flush_head(prefix);
+        BT_TL(s_old, 3);
+        BT_TL_VALUE(s_old, 5, polls);
+    }
+#undef BT_Q
+}
+
+// ---- Algorithm 2: bitmap -> dense ---------------------------------------------------------
+
+// The reverse of ring_flush in two steps, so that the loads of several phases can be in
 // flight together: strip_fetch issues the loads of values[g0, g0 + cnt) into
-// registers, strip_commit later writes them into the wave's LDS strip (same layout
-// as strip_store).  A phase holds at most kPhaseRows * ROW elements, i.e. 257 aligned
+// registers, strip_commit later writes them into the wave's LDS strip, LDS element
+// pad + i being global element g0 + i (pad lines LDS byte 0 up with a 16-byte boundary
+// of the global buffer).  A phase holds at most kPhaseRows * ROW elements, i.e. 257 aligned
 // vectors: the inner ones (at most 255, all fully inside the range) go four to a
 // lane; of the first and the last vector, lane j < E takes element j of the first
 // and lane E + j element j of the last, each only if it lies inside the range.
@@ -682,288 +1109,49 @@ __device__ __forceinline__ void strip_commit(unsigned char *strip, const uint32_
     }
 }
 
-// ---- Algorithm 1: dense -> bitmap -------------------------------------------------------
-
-// One tile of one tensor: `tile` counts the tensor's own tiles (it addresses the data),
-// `slot` is the tile's entry in the workspace (equal to `tile` unless the call is batched).
-template <int S, int KEEP, bool DENSE = false>
-__device__ __forceinline__ void compress_tile(const void *in, const uint64_t n,
-                                              uint32_t *__restrict__ bitmap, void *__restrict__ values,
-                                              const uint64_t values_cap, char *ws, const uint32_t tile,
-                                              const uint32_t slot, const uint32_t n_slots, const float threshold,
-                                              unsigned char *s_stage, PrefixShared &s_prefix,
-                                              uint64_t *__restrict__ index = nullptr, void *dense = nullptr) {
+// The set bits of a whole tile, counted by one wave: lane l counts LANE_WORDS consecutive
+// words, so the 16 lanes [16 v, 16 v + 16) hold the words of the tile's v-th wave.  Returns
+// the tile's total, and in `before` the set bits of the waves before `wave`.  Words at or
+// beyond n_words count as 0 and so do bits at or beyond n (Algorithm 2 visits n bits).
+template <int S>
+__device__ __forceinline__ uint32_t count_tile(const uint32_t *__restrict__ bitmap, const uint64_t n, const uint32_t tile,
+                                               const int lane, const int wave, uint32_t &before) {
     using G = Geo<S>;
-    constexpr int E = G::E;
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWaveSize - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in a scalar register
-
     const uint64_t n_words = (n + 31) >> 5;
-    const uint64_t wave_e0 = (uint64_t)tile * G::TILE + (uint64_t)wave * G::WAVE;
+    const uint64_t w0 = (uint64_t)tile * G::TILE_WORDS + (uint64_t)lane * G::LANE_WORDS;
     const bool full = (uint64_t)(tile + 1) * G::TILE <= n;
-
-    // (1) load: lane l of row k owns elements wave_e0 + k*ROW + l*E ... + E-1, and
-    // (2) Algorithm 1's test "T[i] == 0", on the bit pattern.
-    //     kLoadAhead rows per wave are in flight at a time; a row's mask is taken as
-    //     soon as the row arrives.  (Measured on MI355X: asking for all rows at once,
-    //     kLoadAhead == kRows, is fastest; 1, 2 and 4 rows ahead were 15 %, 9 % and 2 %
-    //     slower on a 25.7 M element fp32 tensor.)
-    uint4 x[kRows];
-    uint32_t mp[G::MW], rank2[kRows / 2], total2[kRows / 2];
-#pragma unroll
-    for (int i = 0; i < G::MW; ++i) mp[i] = 0;
+    uint32_t mine = 0;
     if (full) {
-        const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const char *>(in) + wave_e0 * S) + lane;
 #pragma unroll
-        for (int k = 0; k < kLoadAhead && k < kRows; ++k) x[k] = stream_load<kCompressNtLoad>(p + k * kWaveSize);
-#pragma unroll
-        for (int k = 0; k < kRows; ++k) {
-            uint32_t mk = keep_mask<S, KEEP>(x[k], threshold);
-            asm volatile("" : "+v"(mk));             // row k has arrived: its mask exists from here on
-            mp[k / G::RPM] |= mk << (E * (k % G::RPM));
-            if (k + kLoadAhead < kRows) {
-                __builtin_amdgcn_sched_barrier(0);   // do not ask for the next row any earlier
-                x[k + kLoadAhead] = stream_load<kCompressNtLoad>(p + (k + kLoadAhead) * kWaveSize);
-            }
-        }
+        for (int j = 0; j < G::LANE_WORDS; ++j) mine += (uint32_t)__popc(bitmap[w0 + j]);
     } else {
 #pragma unroll
-        for (int k = 0; k < kRows; ++k) {
-            const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
-            x[k] = load_vec_guarded<S>(in, e0, n);
-            // elements at or beyond n read as 0, which a negative threshold would keep: mask them
-            const uint32_t in_range = e0 >= n ? 0u : (n - e0 >= (uint64_t)E ? (1u << E) - 1u : (1u << (uint32_t)(n - e0)) - 1u);
-            mp[k / G::RPM] |= (keep_mask<S, KEEP>(x[k], threshold) & in_range) << (E * (k % G::RPM));
+        for (int j = 0; j < G::LANE_WORDS; ++j) {
+            const uint64_t wi = w0 + j;
+            uint32_t word = wi < n_words ? bitmap[wi] : 0u;
+            if (wi + 1 == n_words && (n & 31) != 0) word &= (1u << (uint32_t)(n & 31)) - 1u;
+            mine += (uint32_t)__popc(word);
         }
     }
-    // Keep the masks as values of their own: otherwise the compiler keeps one compare
-    // result (a scalar register pair) per element alive until the values are written.
-#pragma unroll
-    for (int i = 0; i < G::MW; ++i) asm volatile("" : "+v"(mp[i]));
-    rank_rows<S>(mp, rank2, total2);
-    uint32_t wave_total = 0;
-#pragma unroll
-    for (int k = 0; k < kRows; ++k) wave_total += BT_FIELD(total2, k);
-
-    // (3) "push bit to B.bitmap": G lanes OR their E-bit masks into one 32-bit word;
-    //     lane (g*G + i) keeps the word of row r0 + i, group g: one store per G rows.
-    //     The store itself waits until after (4): a store in flight would delay the
-    //     polling loads there, which share its completion counter.
-    constexpr int kWordRegs = (kRows + G::G - 1) / G::G;
-    uint32_t word[kWordRegs];
-    {
-        const int i = lane % G::G;
-#pragma unroll
-        for (int r0 = 0; r0 < kRows; r0 += G::G) {
-            word[r0 / G::G] = 0;
-#pragma unroll
-            for (int k = r0; k < r0 + G::G && k < kRows; ++k) {
-                const uint32_t w = group_or<G::G>(BT_MASK(S, mp, k) << (uint32_t)(E * i));
-                if (i == k - r0) word[r0 / G::G] = w;
-                // finish this row's word now: left alone, the compiler sinks the selects below
-                // the wait in (4) and keeps one partial result per row alive across it
-                asm volatile("" : "+v"(word[r0 / G::G]));
-            }
-        }
-    }
-
-    // (4) block total -> count for the scanner -> this wave's position in B.values
-    uint64_t g0 = tile_prefix(ws, s_prefix, slot, n_slots, wave_total,     // index in B.values of this wave's next value
-                              index != nullptr ? index + tile : nullptr);
-    {
-        const int g = lane / G::G, i = lane % G::G;
-#pragma unroll
-        for (int r0 = 0; r0 < kRows; r0 += G::G) {
-            const uint64_t widx = (wave_e0 >> 5) + (uint64_t)(r0 + i) * G::WPR + (uint64_t)g;
-            if (r0 + i < kRows && widx < n_words) bitmap[widx] = word[r0 / G::G];
-        }
-    }
-
-    // (5) "push T[i] to B.values": kPhaseRows rows at a time, compact this wave's
-    //     non-zeros into its LDS strip, then write the strip out with aligned stores.
-    unsigned char *strip = s_stage + wave * G::LDS_WAVE;
-#pragma unroll
-    for (int r0 = 0; r0 < kRows; r0 += kPhaseRows) {
-        char *gdst = static_cast<char *>(values) + g0 * S;
-        const uint32_t pad = (uint32_t)(reinterpret_cast<uintptr_t>(gdst) & (kVecBytes - 1)) / S;   // elements
-        if (r0 != 0) wave_lds_sync();   // the previous phase's reads are done before the strip is reused
-        uint32_t row_start = pad;
-#pragma unroll
-        for (int k = r0; k < r0 + kPhaseRows; ++k) {
-            // byte offset of this lane's next kept element from the spare vector (negative: the strip lies before it)
-            int rb = ((int)(row_start + BT_FIELD(rank2, k)) - G::DUMP) * S;
-            unsigned char *const dump = strip + G::DUMP * S;
-            const uint32_t mk = BT_MASK(S, mp, k);
-            const uint32_t d[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
-            // every element is written, a dropped one to a place nobody reads: a select on the address instead of
-            // a branch around the write keeps the execution mask alone (half the instructions; measured 1 % on
-            // compress, 4-8 % on the restoration of 16-bit tensors, where the same is done with the reads)
-            if (S == 8) {
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int keep = (int)((mk >> j) & 1u);
-                    *reinterpret_cast<uint64_t *>(dump + __mul24(keep, rb)) = ((uint64_t)d[2 * j + 1] << 32) | d[2 * j];
-                    rb += keep * S;
-                }
-            } else if (S == 4) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int keep = (int)((mk >> j) & 1u);
-                    *reinterpret_cast<uint32_t *>(dump + __mul24(keep, rb)) = d[j];
-                    rb += keep * S;
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int keep = (int)((mk >> j) & 1u);
-                    *reinterpret_cast<uint16_t *>(dump + __mul24(keep, rb)) = (uint16_t)(d[j >> 1] >> (16 * (j & 1)));
-                    rb += keep * S;
-                }
-            }
-            row_start += BT_FIELD(total2, k);
-        }
-        wave_lds_sync();
-        const uint32_t phase_total = row_start - pad;
-        // capacity clamp: never write at or beyond values_cap
-        uint32_t cnt = phase_total;
-        if (g0 >= values_cap) cnt = 0;
-        else if (values_cap - g0 < cnt) cnt = (uint32_t)(values_cap - g0);
-        strip_store<S>(strip, gdst, pad, cnt, lane);
-        g0 += phase_total;
-    }
-
-    // (6) the dense tensor after pruning, if asked for (bt_activation_compress): what survives keeps its
-    //     bits, the rest is +0.  Last, so that no store precedes the polling loads of (4); `dense` may be
-    //     `in` itself (every lane rewrites exactly the vectors it has read).
-    if (DENSE) {
-#pragma unroll
-        for (int k = 0; k < kRows; ++k) {
-            const uint32_t mk = BT_MASK(S, mp, k);
-            uint32_t d[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
-            // masks by arithmetic (0 - bit is all ones or zero), not by compares: see nonzero_mask
-            if (S == 8) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) d[j] &= 0u - ((mk >> (j >> 1)) & 1u);
-            } else if (S == 4) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) d[j] &= 0u - ((mk >> j) & 1u);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    d[j] &= (((mk >> (2 * j)) & 1u) * 0x0000ffffu) | (((mk >> (2 * j + 1)) & 1u) * 0xffff0000u);
-            }
-            const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
-            const uint4 o = make_uint4(d[0], d[1], d[2], d[3]);
-            if (full) stream_store<kCompressNtStore>(reinterpret_cast<uint4 *>(static_cast<char *>(dense) + e0 * S), o);
-            else store_vec_guarded<S>(dense, e0, n, o);
-        }
-    }
+    const uint32_t incl = wave_inclusive_sum(mine);
+    before = wave == 0 ? 0u : (uint32_t)__builtin_amdgcn_readlane((int)incl, (int)uniform32(16u * (uint32_t)wave - 1u));
+    return (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
 }
 
-// bt_compress / bt_compress_pruned: one tensor.  Workgroup 0 is the scanner, workgroup
-// t + 1 is tile t.
-template <int S, int KEEP, bool DENSE>
-__global__ __launch_bounds__(kBlock, 8) void compress_kernel(const void *in, const uint64_t n,
-                                                          uint32_t *__restrict__ bitmap, void *__restrict__ values,
-                                                          const uint64_t values_cap, uint64_t *__restrict__ nnz_out,
-                                                          char *ws, const uint32_t n_tiles, const float threshold,
-                                                          uint64_t *__restrict__ index, void *dense) {
-    __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
-    __shared__ PrefixShared s_prefix;
-    if (workspace_failed(ws)) return;
-    if (blockIdx.x == 0) {
-        if (threadIdx.x < kWaveSize) {
-            const uint32_t start[2] = {0, n_tiles};
-            uint64_t *const nnz[1] = {nnz_out};
-            scan_counts(ws, Segments{1, start, nnz});
-        }
-        return;
-    }
-    const uint32_t tile = blockIdx.x - 1;
-    BT_TL(tile, 0);
-    compress_tile<S, KEEP, DENSE>(in, n, bitmap, values, values_cap, ws, tile, tile, n_tiles, threshold, s_stage,
-                                  s_prefix, index, dense);
-#ifdef BT_TIMELINE
-    BT_TL(tile, 3);
-    if (threadIdx.x == 0) __builtin_amdgcn_s_waitcnt(0);     // this wave's stores have been acknowledged
-    BT_TL(tile, 4);
-#endif
-}
-
-// Several tensors in one launch (bt_compress_batch): the kernel arguments carry the
-// per-tensor pointers; a workgroup finds its tensor by binary search over the slot
-// starts.  Slots that belong to no tile only do their share of the workspace clean-up.
-constexpr int kMaxBatch = BT_MAX_BATCH;
-struct BatchLayout {
-    uint32_t count;
-    uint32_t start[kMaxBatch + 1];
-    uint32_t tiles[kMaxBatch];
-};
-struct CompressBatch {
-    BatchLayout lay;
-    const void *in[kMaxBatch];
-    uint32_t *bitmap[kMaxBatch];
-    void *values[kMaxBatch];
-    uint64_t cap[kMaxBatch];
-    uint64_t *nnz[kMaxBatch];
-    uint64_t n[kMaxBatch];
-};
-
-__device__ __forceinline__ uint32_t batch_item_of(const BatchLayout &lay, const uint32_t slot) {
-    uint32_t lo = 0, hi = lay.count;          // start[lo] <= slot < start[hi]
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (slot >= lay.start[mid]) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
+// One wave's quarter of one tile, given Algorithm 2's counter j at the start of the tile.
+// The waves of a workgroup do not talk to each other: each counts what the waves before it
+// hold from the bitmap itself (count_tile).
 template <int S>
-__global__ __launch_bounds__(kBlock, 8) void compress_batch_kernel(const CompressBatch b, char *ws) {
-    __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
-    __shared__ PrefixShared s_prefix;
-    if (workspace_failed(ws)) return;
-    const uint32_t n_slots = b.lay.start[b.lay.count];
-    if (blockIdx.x == 0) {
-        if (threadIdx.x < kWaveSize) scan_counts(ws, Segments{b.lay.count, b.lay.start, b.nnz});
-        return;
-    }
-    const uint32_t slot = blockIdx.x - 1;
-    const uint32_t i = batch_item_of(b.lay, slot);
-    const uint32_t tile = slot - b.lay.start[i];
-    if (tile >= b.lay.tiles[i]) {
-        idle_slot(ws, slot, n_slots);
-        return;
-    }
-    compress_tile<S, kKeepNonZero>(b.in[i], b.n[i], b.bitmap[i], b.values[i], b.cap[i], ws, tile, slot, n_slots, 0.0f,
-                                   s_stage, s_prefix);
-}
-
-// ---- Algorithm 2: bitmap -> dense ---------------------------------------------------------
-
-// INDEXED: Algorithm 2's j at the start of the tile is read from a tile index (written by
-// bt_compress_indexed) instead of being found by the grid scan: no workspace, no waiting;
-// values at or beyond values_cap are never read.
-template <int S, bool INDEXED = false>
-__device__ __forceinline__ void decompress_tile(const uint32_t *__restrict__ bitmap, const void *__restrict__ values,
-                                                const uint64_t n, void *__restrict__ out, char *ws,
-                                                const uint32_t tile, const uint32_t slot, const uint32_t n_slots,
-                                                unsigned char *s_stage, PrefixShared &s_prefix,
-                                                const uint64_t *__restrict__ index = nullptr,
-                                                const uint64_t values_cap = ~(uint64_t)0) {
+__device__ __forceinline__ void decompress_wave(const uint32_t *__restrict__ bitmap, const void *__restrict__ values,
+                                                const uint64_t values_cap, const uint64_t n, void *__restrict__ out,
+                                                const uint32_t tile, const uint64_t tile_j, const uint32_t before_wave,
+                                                unsigned char *strip, const int lane, const int wave) {
     using G = Geo<S>;
     constexpr int E = G::E;
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWaveSize - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in a scalar register
-    uint64_t tile_j = 0;
-    if (INDEXED) tile_j = index[tile];                           // asked for first, needed last
-
     const uint64_t n_words = (n + 31) >> 5;
     const uint64_t wave_e0 = (uint64_t)tile * G::TILE + (uint64_t)wave * G::WAVE;
 
-    // (1) this lane's bits of "B.bitmap[i] is set", and Algorithm 2's counter j as ranks
+    // (1) this lane's bits of the bitmap, and Algorithm 2's counter j as ranks
     uint32_t mp[G::MW], rank2[kRows / 2], total2[kRows / 2];
 #pragma unroll
     for (int i = 0; i < G::MW; ++i) mp[i] = 0;
@@ -982,31 +1170,15 @@ __device__ __forceinline__ void decompress_tile(const uint32_t *__restrict__ bit
                               << (E * (k % G::RPM));
     }
     rank_rows<S>(mp, rank2, total2);
-    uint32_t wave_total = 0;
-#pragma unroll
-    for (int k = 0; k < kRows; ++k) wave_total += BT_FIELD(total2, k);
 
-    // (2) block total -> count for the scanner -> this wave's value of j
-    uint64_t g0;                                                          // Algorithm 2's j for this wave
-    if (INDEXED) {
-        if (lane == 0) s_prefix.wave_total[wave] = wave_total;
-        __syncthreads();
-        g0 = tile_j;
-        for (int w = 0; w < wave; ++w) g0 += s_prefix.wave_total[w];
-        g0 = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(g0 >> 32)) << 32) |
-             (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)g0);
-    } else {
-        g0 = tile_prefix(ws, s_prefix, slot, n_slots, wave_total);
-    }
-
-    // (3) Ask for the values of every phase (kPhaseRows rows each) first, so that all of
+    // (2) Ask for the values of every phase (kPhaseRows rows each) first, so that all of
     //     them are in flight together; then, phase by phase, put them into the LDS strip
-    //     and "push B.values[j] / push 0.0 to T": expand from LDS by rank and store 16
-    //     bytes per lane.  No load is issued after the first store: loads and stores
-    //     share one completion counter, and a load waited for after a store would also
-    //     wait for that store to reach memory.
+    //     and expand from LDS by rank: a value where the bit is set, +0 where it is clear,
+    //     16 bytes per lane per store.  No load is issued after the first store: loads and
+    //     stores share one completion counter, and a load waited for after a store would
+    //     also wait for that store to reach memory.
+    uint64_t g0 = tile_j + before_wave;                                   // Algorithm 2's j for this wave
     constexpr int kPhases = kRows / kPhaseRows;
-    unsigned char *strip = s_stage + wave * G::LDS_WAVE;
     Fetched<S> fetched[kPhases];
     uint32_t pads[kPhases], cnts[kPhases];
 #pragma unroll
@@ -1017,10 +1189,9 @@ __device__ __forceinline__ void decompress_tile(const uint32_t *__restrict__ bit
         const char *gsrc = static_cast<const char *>(values) + g0 * S;
         pads[ph] = (uint32_t)(reinterpret_cast<uintptr_t>(gsrc) & (kVecBytes - 1)) / S;
         const uint32_t phase_total = cnts[ph];
-        if (INDEXED) {   // an index that does not belong to this bitmap must not lead outside d_values
-            if (g0 >= values_cap) cnts[ph] = 0;
-            else if (values_cap - g0 < cnts[ph]) cnts[ph] = (uint32_t)(values_cap - g0);
-        }
+        // nothing at or beyond the capacity is read (an index that does not belong to the bitmap, a wait that ran out)
+        if (g0 >= values_cap) cnts[ph] = 0;
+        else if (values_cap - g0 < cnts[ph]) cnts[ph] = (uint32_t)(values_cap - g0);
         strip_fetch<S>(gsrc, pads[ph], cnts[ph], lane, fetched[ph]);
         g0 += phase_total;
     }
@@ -1073,70 +1244,84 @@ __device__ __forceinline__ void decompress_tile(const uint32_t *__restrict__ bit
             row_start += BT_FIELD(total2, k);
         }
     }
+    wave_lds_sync();                    // this tile's reads are done before the next tile's values are committed
 }
 
-template <int S>
-__global__ __launch_bounds__(kBlock, 8) void decompress_kernel(const uint32_t *__restrict__ bitmap,
-                                                            const void *__restrict__ values, const uint64_t n,
-                                                            void *__restrict__ out, char *ws, const uint32_t n_tiles) {
-    __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
-    __shared__ PrefixShared s_prefix;
+// bt_decompress and bt_decompress_batch.  Workgroup 0 is the scanner; workgroup w + 1 restores
+// slots w, w + G, w + 2G, ...  A tile's count depends on the bitmap alone, so a workgroup's first
+// wave publishes the counts of its next kCountAhead tiles before the workgroup restores a tile:
+// the scanner has the time a workgroup spends on kCountAhead tiles to answer, and except at the
+// start of a call a wave finds the prefix of its tile waiting.
+template <int S, class Job>
+__global__ __launch_bounds__(kBlock, kDecompressOcc) void decompress_kernel(const Job job, char *ws) {
+    using G = Geo<S>;
+    __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * G::LDS_WAVE];
     if (workspace_failed(ws)) return;
+    const uint32_t n_slots = job.slots();
     if (blockIdx.x == 0) {
-        if (threadIdx.x < kWaveSize) {
-            const uint32_t start[2] = {0, n_tiles};
-            scan_counts(ws, Segments{1, start, nullptr});
-        }
+        if (threadIdx.x < kWaveSize) scan_counts(ws, job);
         return;
     }
-    const uint32_t tile = blockIdx.x - 1;
-    BT_TL(tile, 0);
-    decompress_tile<S>(bitmap, values, n, out, ws, tile, tile, n_tiles, s_stage, s_prefix);
-#ifdef BT_TIMELINE
-    BT_TL(tile, 3);
-    if (threadIdx.x == 0) __builtin_amdgcn_s_waitcnt(0);     // this wave's stores have been acknowledged
-    BT_TL(tile, 4);
-#endif
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWaveSize - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t worker = blockIdx.x - 1, workers = gridDim.x - 1;
+    uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
+    const Epoch ep = read_epoch(ws);
+    const uint32_t cur = ep.cur;
+    const uint32_t limit = wait_limit(hdr);
+    __syncthreads();                    // every wave has read the header before the first wave publishes anything
+    zero_previous(ws, ep, worker, workers);
+    unsigned char *const strip = s_stage + wave * G::LDS_WAVE;
+    uint32_t polls = 0;
+
+    auto publish = [&](const uint64_t slot) {      // first wave only
+        if (slot >= n_slots) return;
+        const Slot sl = job.at((uint32_t)slot);
+        uint32_t count = 0, unused;
+        if (!sl.idle) count = count_tile<S>(job.bitmap(sl.item), job.n(sl.item), sl.tile, lane, 0, unused);
+        if (lane == 0) ws_store32(ws_count(ws, (uint32_t)slot, cur), count + 1);
+        BT_TL((uint32_t)slot, 1);
+    };
+    if (wave == 0) {
+#pragma unroll 1
+        for (int a = 0; a < kCountAhead; ++a) publish((uint64_t)worker + (uint64_t)a * workers);
+    }
+    for (uint32_t slot = worker; slot < n_slots; slot += workers) {
+        if (wave == 0) publish((uint64_t)slot + (uint64_t)kCountAhead * workers);
+        const Slot sl = job.at(slot);
+        if (sl.idle) continue;
+        BT_TL(slot, 0);
+        const uint32_t *const bitmap = job.bitmap(sl.item);
+        const uint64_t n = job.n(sl.item);
+        uint32_t before_wave;
+        count_tile<S>(bitmap, n, sl.tile, lane, wave, before_wave);
+        const uint64_t tile_j = wait_prefix(ws, slot, cur, hdr, limit, polls);
+        BT_TL(slot, 2);
+        decompress_wave<S>(bitmap, job.values(sl.item), job.cap(sl.item), n, job.out(sl.item), sl.tile, tile_j, before_wave,
+                           strip, lane, wave);
+        BT_TL(slot, 3);
+        BT_TL_VALUE(slot, 5, polls);
+    }
 }
 
-struct DecompressBatch {
-    BatchLayout lay;
-    const uint32_t *bitmap[kMaxBatch];
-    const void *values[kMaxBatch];
-    void *out[kMaxBatch];
-    uint64_t n[kMaxBatch];
-};
-
-template <int S>
-__global__ __launch_bounds__(kBlock, 8) void decompress_batch_kernel(const DecompressBatch b, char *ws) {
-    __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
-    __shared__ PrefixShared s_prefix;
-    if (workspace_failed(ws)) return;
-    const uint32_t n_slots = b.lay.start[b.lay.count];
-    if (blockIdx.x == 0) {
-        if (threadIdx.x < kWaveSize) scan_counts(ws, Segments{b.lay.count, b.lay.start, nullptr});
-        return;
-    }
-    const uint32_t slot = blockIdx.x - 1;
-    const uint32_t i = batch_item_of(b.lay, slot);
-    const uint32_t tile = slot - b.lay.start[i];
-    if (tile >= b.lay.tiles[i]) {
-        idle_slot(ws, slot, n_slots);
-        return;
-    }
-    decompress_tile<S>(b.bitmap[i], b.values[i], b.n[i], b.out[i], ws, tile, slot, n_slots, s_stage, s_prefix);
-}
-
-// bt_decompress_indexed: one workgroup per tile and nothing else.
-template <int S>
-__global__ __launch_bounds__(kBlock, 8) void decompress_indexed_kernel(const uint32_t *__restrict__ bitmap,
-                                                                    const void *__restrict__ values,
-                                                                    const uint64_t values_cap,
-                                                                    const uint64_t *__restrict__ index, const uint64_t n,
-                                                                    void *__restrict__ out) {
-    __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * Geo<S>::LDS_WAVE];
-    __shared__ PrefixShared s_prefix;
-    decompress_tile<S, true>(bitmap, values, n, out, nullptr, blockIdx.x, 0, 0, s_stage, s_prefix, index, values_cap);
+// bt_decompress_indexed and its batched form: one workgroup per slot and nothing else.  Algorithm 2's
+// j at the start of the tile comes from the tile index.
+template <int S, class Job>
+__global__ __launch_bounds__(kBlock, 8) void decompress_indexed_kernel(const Job job) {
+    using G = Geo<S>;
+    __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * G::LDS_WAVE];
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const Slot sl = job.at(blockIdx.x);
+    if (sl.idle) return;
+    const uint64_t tile_j = job.tile_index(sl.item)[sl.tile];             // asked for first, needed last
+    const uint32_t *const bitmap = job.bitmap(sl.item);
+    const uint64_t n = job.n(sl.item);
+    uint32_t before_wave;
+    count_tile<S>(bitmap, n, sl.tile, lane, wave, before_wave);
+    decompress_wave<S>(bitmap, job.values(sl.item), job.cap(sl.item), n, job.out(sl.item), sl.tile, tile_j, before_wave,
+                       s_stage + wave * G::LDS_WAVE, lane, wave);
 }
 
 // ---- ReLU backward from the bitmap -----------------------------------------------------------
@@ -1194,44 +1379,6 @@ __global__ __launch_bounds__(kBlock) void relu_backward_kernel(const uint32_t *_
     }
 }
 
-// ---- measurement aid: a stream with the codec's traffic and no dependency -----------------
-
-// Workgroup t reads R rows of 256 16-byte vectors from `in` and writes W such rows to `out`,
-// both contiguous per workgroup and per wave, with the same cache hints as the codec.
-// Nothing waits for anything: this is what the memory system gives the codec's access
-// pattern at best, the figure the codec kernels are compared with.
-constexpr int kProbeThreads = 256;     // a row is 256 lanes x 16 bytes = 4 KiB, whatever the codec's workgroup size
-template <int R, int W>
-__global__ __launch_bounds__(kProbeThreads) void stream_probe_kernel(const uint4 *__restrict__ in, uint4 *__restrict__ out,
-                                                              const uint32_t tiles) {
-    const int lane = threadIdx.x & (kWaveSize - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint64_t t = blockIdx.x;
-    if (t >= tiles) return;
-    uint4 acc = make_uint4(1, 2, 3, (uint32_t)t);
-    if (R > 0) {
-        uint4 v[R > 0 ? R : 1];
-        const uint64_t base = (t * (kProbeThreads / kWaveSize) + wave) * (uint64_t)(kWaveSize * R) + lane;
-#pragma unroll
-        for (int k = 0; k < R; ++k) v[k] = stream_load<true>(in + base + kWaveSize * k);
-#pragma unroll
-        for (int k = 0; k < R; ++k) {
-            acc.x ^= v[k].x; acc.y ^= v[k].y; acc.z ^= v[k].z; acc.w ^= v[k].w;
-        }
-    }
-    if (W > 0) {
-        const uint64_t base = (t * (kProbeThreads / kWaveSize) + wave) * (uint64_t)(kWaveSize * W) + lane;
-#pragma unroll
-        for (int k = 0; k < W; ++k) {
-            uint4 o = acc;
-            o.x += k;
-            stream_store<true>(out + base + kWaveSize * k, o);
-        }
-    } else if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u) {
-        out[t] = acc;          // keeps the loads alive; practically never taken
-    }
-}
-
 // ---- small fills ---------------------------------------------------------------------------
 
 __global__ void fill_u64_kernel(uint64_t *p, uint64_t count, uint64_t value) {
@@ -1267,6 +1414,39 @@ bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p
 
 bt_status launched() { return hipGetLastError() == hipSuccess ? BT_OK : BT_ERR_HIP; }
 
+// Workgroups of `kernel` that the current device holds at the same time: what the runtime
+// reports per compute unit, times the compute units.  Asked once per kernel and device, then
+// remembered; the query touches no stream.  The persistent kernels are launched with at most
+// this many workgroups, which is what lets their workgroups wait for one another.
+constexpr int kMaxDevices = 64;
+template <class Kernel> uint32_t resident_workgroups(Kernel kernel) {
+    static std::atomic<uint32_t> known[kMaxDevices];     // one table per kernel (per instantiation of this template)
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return 2;
+    const bool cacheable = device >= 0 && device < kMaxDevices;
+    if (cacheable) {
+        const uint32_t k = known[device].load(std::memory_order_relaxed);
+        if (k != 0) return k;
+    }
+    int per_unit = 0, units = 0;
+    uint32_t total = 2;                                  // the scanner and one worker always fit
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_unit, kernel, kBlock, 0) == hipSuccess &&
+        hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess &&
+        per_unit > 0 && units > 0 && (uint64_t)per_unit * (uint64_t)units >= 2)
+        total = (uint32_t)((uint64_t)per_unit * (uint64_t)units);
+    else
+        (void)hipGetLastError();
+    if (cacheable) known[device].store(total, std::memory_order_relaxed);
+    return total;
+}
+
+// Grid of a persistent launch over `slots` slots: the scanner plus as many workers as are resident, but no
+// worker without a slot.
+template <class Kernel> dim3 persistent_grid(Kernel kernel, uint64_t slots) {
+    const uint64_t room = resident_workgroups(kernel) - 1;
+    return dim3((unsigned)((slots < room ? slots : room) + 1));
+}
+
 bt_status check_common(uint64_t n, bt_dtype dt, const void *d_ws, size_t ws_bytes) {
     if (elem_size(dt) == 0) return BT_ERR_DTYPE;
     if (n > BT_MAX_ELEMENTS) return BT_ERR_SIZE;
@@ -1290,9 +1470,9 @@ size_t workspace_bytes_for_slots(uint64_t slots) {
     return kHeaderBytes + (size_t)records * kRecordBytes;
 }
 
-// Tensors [first, first + lay.count) of a batch, laid end to end.  `n_of(i)` is tensor i's element count.
-template <class NOf>
-void lay_out(BatchLayout &lay, size_t first, size_t count, int s, NOf n_of) {
+// Tensors [first, first + count) of a batch, laid end to end.  `n_of(i)` is tensor i's element count.
+template <int MAXB, class NOf>
+void lay_out(BatchLayout<MAXB> &lay, size_t first, size_t count, int s, NOf n_of) {
     lay.count = (uint32_t)count;
     uint64_t at = 0;
     for (size_t i = 0; i < count; ++i) {
@@ -1301,17 +1481,17 @@ void lay_out(BatchLayout &lay, size_t first, size_t count, int s, NOf n_of) {
         lay.tiles[i] = (uint32_t)tiles_for(n, s);
         at += batch_slots_for(n, s);
     }
-    for (size_t i = count; i <= (size_t)kMaxBatch; ++i) lay.start[i] = (uint32_t)at;
-    for (size_t i = count; i < (size_t)kMaxBatch; ++i) lay.tiles[i] = 0;
+    for (size_t i = count; i <= (size_t)MAXB; ++i) lay.start[i] = (uint32_t)at;
+    for (size_t i = count; i < (size_t)MAXB; ++i) lay.tiles[i] = 0;
 }
 
-// Largest workspace any launch of the batch needs (a batch of more than kMaxBatch
-// tensors is cut into consecutive launches of kMaxBatch, which reuse the workspace).
+// Largest workspace any launch of the batch needs when it is cut into consecutive launches of `per_launch`
+// tensors, which reuse the workspace.
 template <class NOf>
-size_t batch_workspace_bytes(size_t count, int s, NOf n_of) {
+size_t batch_workspace_bytes(size_t count, size_t per_launch, int s, NOf n_of) {
     size_t need = workspace_bytes_for_slots(0);
-    for (size_t first = 0; first < count; first += kMaxBatch) {
-        const size_t c = count - first < (size_t)kMaxBatch ? count - first : (size_t)kMaxBatch;
+    for (size_t first = 0; first < count; first += per_launch) {
+        const size_t c = count - first < per_launch ? count - first : per_launch;
         uint64_t slots = 0;
         for (size_t i = 0; i < c; ++i) slots += batch_slots_for(n_of(first + i), s);
         const size_t b = workspace_bytes_for_slots(slots);
@@ -1326,6 +1506,60 @@ bt_status check_batch_common(const void *items, size_t count, bt_dtype dt, const
     if (items == nullptr || d_ws == nullptr) return BT_ERR_NULL;
     if (misaligned(d_ws, 128)) return BT_ERR_ALIGN;
     return BT_OK;
+}
+
+// Launch the compression kernel for a dtype / pruning / dense-output combination on `job`.
+template <class Job>
+bt_status launch_compress(const Job &job, uint64_t slots, bt_dtype dtype, bool prune, bool dense, double threshold,
+                          char *ws, hipStream_t hs) {
+    const dim3 block(kBlock);
+#define BT_LAUNCH_COMPRESS(S_, KEEP_, DENSE_)                                                   \
+    do {                                                                                        \
+        auto kernel = compress_kernel<S_, KEEP_, DENSE_, Job>;                                  \
+        kernel<<<persistent_grid(kernel, slots), block, 0, hs>>>(job, ws, threshold);           \
+    } while (0)
+    const int s = elem_size(dtype);
+    if (!prune) {
+        if (s == 8) BT_LAUNCH_COMPRESS(8, kKeepNonZero, false);
+        else if (s == 4) BT_LAUNCH_COMPRESS(4, kKeepNonZero, false);
+        else BT_LAUNCH_COMPRESS(2, kKeepNonZero, false);
+    } else if (!dense) {
+        if (dtype == BT_F64) BT_LAUNCH_COMPRESS(8, kKeepAboveF64, false);
+        else if (dtype == BT_F32) BT_LAUNCH_COMPRESS(4, kKeepAboveF32, false);
+        else if (dtype == BT_F16) BT_LAUNCH_COMPRESS(2, kKeepAboveF16, false);
+        else BT_LAUNCH_COMPRESS(2, kKeepAboveBF16, false);
+    } else {
+        if (dtype == BT_F64) BT_LAUNCH_COMPRESS(8, kKeepAboveF64, true);
+        else if (dtype == BT_F32) BT_LAUNCH_COMPRESS(4, kKeepAboveF32, true);
+        else if (dtype == BT_F16) BT_LAUNCH_COMPRESS(2, kKeepAboveF16, true);
+        else BT_LAUNCH_COMPRESS(2, kKeepAboveBF16, true);
+    }
+#undef BT_LAUNCH_COMPRESS
+    return launched();
+}
+
+template <class Job>
+bt_status launch_decompress(const Job &job, uint64_t slots, int s, char *ws, hipStream_t hs) {
+    const dim3 block(kBlock);
+#define BT_LAUNCH_DECOMPRESS(S_)                                                                \
+    do {                                                                                        \
+        auto kernel = decompress_kernel<S_, Job>;                                               \
+        kernel<<<persistent_grid(kernel, slots), block, 0, hs>>>(job, ws);                      \
+    } while (0)
+    if (s == 8) BT_LAUNCH_DECOMPRESS(8);
+    else if (s == 4) BT_LAUNCH_DECOMPRESS(4);
+    else BT_LAUNCH_DECOMPRESS(2);
+#undef BT_LAUNCH_DECOMPRESS
+    return launched();
+}
+
+template <class Job>
+bt_status launch_decompress_indexed(const Job &job, uint64_t slots, int s, hipStream_t hs) {
+    const dim3 grid((unsigned)slots), block(kBlock);
+    if (s == 8) decompress_indexed_kernel<8, Job><<<grid, block, 0, hs>>>(job);
+    else if (s == 4) decompress_indexed_kernel<4, Job><<<grid, block, 0, hs>>>(job);
+    else decompress_indexed_kernel<2, Job><<<grid, block, 0, hs>>>(job);
+    return launched();
 }
 
 }  // namespace
@@ -1380,7 +1614,7 @@ bt_status bt_workspace_init(void *d_workspace, size_t workspace_bytes, bt_stream
     return launched();
 }
 
-static bt_status compress_common(const void *d_in, uint64_t n, bt_dtype dtype, bool prune, float threshold,
+static bt_status compress_common(const void *d_in, uint64_t n, bt_dtype dtype, bool prune, double threshold,
                                  uint32_t *d_bitmap, void *d_values, uint64_t values_cap, uint64_t *d_nnz,
                                  uint64_t *d_index, void *d_dense, void *d_workspace, size_t workspace_bytes,
                                  bt_stream stream) {
@@ -1399,40 +1633,21 @@ static bt_status compress_common(const void *d_in, uint64_t n, bt_dtype dtype, b
     if (misaligned(d_in, 16) || misaligned(d_bitmap, 4) || misaligned(d_values, (size_t)s)) return BT_ERR_ALIGN;
 
     const uint32_t n_tiles = (uint32_t)tiles_for(n, s);
-    char *ws = static_cast<char *>(d_workspace);
-    const dim3 grid(n_tiles + 1), block(kBlock);
-#define BT_LAUNCH_COMPRESS(S_, KEEP_, DENSE_) \
-    compress_kernel<S_, KEEP_, DENSE_><<<grid, block, 0, hs>>>(d_in, n, d_bitmap, d_values, values_cap, d_nnz, ws, n_tiles, threshold, d_index, d_dense)
-    if (!prune) {
-        if (s == 8) BT_LAUNCH_COMPRESS(8, kKeepNonZero, false);
-        else if (s == 4) BT_LAUNCH_COMPRESS(4, kKeepNonZero, false);
-        else BT_LAUNCH_COMPRESS(2, kKeepNonZero, false);
-    } else if (d_dense == nullptr) {
-        if (dtype == BT_F64) BT_LAUNCH_COMPRESS(8, kKeepAboveF64, false);
-        else if (dtype == BT_F32) BT_LAUNCH_COMPRESS(4, kKeepAboveF32, false);
-        else if (dtype == BT_F16) BT_LAUNCH_COMPRESS(2, kKeepAboveF16, false);
-        else BT_LAUNCH_COMPRESS(2, kKeepAboveBF16, false);
-    } else {
-        if (dtype == BT_F64) BT_LAUNCH_COMPRESS(8, kKeepAboveF64, true);
-        else if (dtype == BT_F32) BT_LAUNCH_COMPRESS(4, kKeepAboveF32, true);
-        else if (dtype == BT_F16) BT_LAUNCH_COMPRESS(2, kKeepAboveF16, true);
-        else BT_LAUNCH_COMPRESS(2, kKeepAboveBF16, true);
-    }
-#undef BT_LAUNCH_COMPRESS
-    return launched();
+    const CompressOne job{d_in, n, d_bitmap, d_values, values_cap, d_nnz, d_index, d_dense, n_tiles};
+    return launch_compress(job, n_tiles, dtype, prune, d_dense != nullptr, threshold, static_cast<char *>(d_workspace), hs);
 }
 
 bt_status bt_compress(const void *d_in, uint64_t n, bt_dtype dtype, uint32_t *d_bitmap, void *d_values,
                       uint64_t values_cap, uint64_t *d_nnz, void *d_workspace, size_t workspace_bytes,
                       bt_stream stream) {
-    return compress_common(d_in, n, dtype, false, 0.0f, d_bitmap, d_values, values_cap, d_nnz, nullptr, nullptr,
+    return compress_common(d_in, n, dtype, false, 0.0, d_bitmap, d_values, values_cap, d_nnz, nullptr, nullptr,
                            d_workspace, workspace_bytes, stream);
 }
 
 bt_status bt_compress_pruned(const void *d_in, uint64_t n, bt_dtype dtype, float threshold, uint32_t *d_bitmap,
                              void *d_values, uint64_t values_cap, uint64_t *d_nnz, void *d_workspace,
                              size_t workspace_bytes, bt_stream stream) {
-    return compress_common(d_in, n, dtype, true, threshold, d_bitmap, d_values, values_cap, d_nnz, nullptr, nullptr,
+    return compress_common(d_in, n, dtype, true, (double)threshold, d_bitmap, d_values, values_cap, d_nnz, nullptr, nullptr,
                            d_workspace, workspace_bytes, stream);
 }
 
@@ -1443,7 +1658,7 @@ bt_status bt_activation_compress(const void *d_in, uint64_t n, bt_dtype dtype, f
         if (d_dense_out == nullptr) return BT_ERR_NULL;
         if (misaligned(d_dense_out, 16)) return BT_ERR_ALIGN;
     }
-    return compress_common(d_in, n, dtype, true, threshold, d_bitmap, d_values, values_cap, d_nnz, nullptr, d_dense_out,
+    return compress_common(d_in, n, dtype, true, (double)threshold, d_bitmap, d_values, values_cap, d_nnz, nullptr, d_dense_out,
                            d_workspace, workspace_bytes, stream);
 }
 
@@ -1464,7 +1679,7 @@ bt_status bt_compress_indexed(const void *d_in, uint64_t n, bt_dtype dtype, uint
         if (d_index == nullptr) return BT_ERR_NULL;
         if (misaligned(d_index, 8)) return BT_ERR_ALIGN;
     }
-    return compress_common(d_in, n, dtype, false, 0.0f, d_bitmap, d_values, values_cap, d_nnz, d_index, nullptr,
+    return compress_common(d_in, n, dtype, false, 0.0, d_bitmap, d_values, values_cap, d_nnz, d_index, nullptr,
                            d_workspace, workspace_bytes, stream);
 }
 
@@ -1478,12 +1693,9 @@ bt_status bt_decompress_indexed(const uint32_t *d_bitmap, const void *d_values, 
     if (d_values == nullptr && values_cap != 0) return BT_ERR_NULL;
     if (misaligned(d_out, 16) || misaligned(d_bitmap, 4) || misaligned(d_values, (size_t)s) || misaligned(d_index, 8))
         return BT_ERR_ALIGN;
-    hipStream_t hs = (hipStream_t)stream;
-    const dim3 grid((uint32_t)tiles_for(n, s)), block(kBlock);
-    if (s == 8) decompress_indexed_kernel<8><<<grid, block, 0, hs>>>(d_bitmap, d_values, values_cap, d_index, n, d_out);
-    else if (s == 4) decompress_indexed_kernel<4><<<grid, block, 0, hs>>>(d_bitmap, d_values, values_cap, d_index, n, d_out);
-    else decompress_indexed_kernel<2><<<grid, block, 0, hs>>>(d_bitmap, d_values, values_cap, d_index, n, d_out);
-    return launched();
+    const uint32_t n_tiles = (uint32_t)tiles_for(n, s);
+    const DecompressOne job{d_bitmap, d_values, values_cap, d_index, n, d_out, n_tiles};
+    return launch_decompress_indexed(job, n_tiles, s, (hipStream_t)stream);
 }
 
 bt_status bt_decompress(const uint32_t *d_bitmap, const void *d_values, uint64_t n, bt_dtype dtype, void *d_out,
@@ -1494,17 +1706,9 @@ bt_status bt_decompress(const uint32_t *d_bitmap, const void *d_values, uint64_t
     const int s = elem_size(dtype);
     if (d_bitmap == nullptr || d_out == nullptr) return BT_ERR_NULL;   // d_values may be NULL when nnz == 0
     if (misaligned(d_out, 16) || misaligned(d_bitmap, 4) || misaligned(d_values, (size_t)s)) return BT_ERR_ALIGN;
-
-    hipStream_t hs = (hipStream_t)stream;
     const uint32_t n_tiles = (uint32_t)tiles_for(n, s);
-    char *ws = static_cast<char *>(d_workspace);
-    if (s == 8)
-        decompress_kernel<8><<<dim3(n_tiles + 1), dim3(kBlock), 0, hs>>>(d_bitmap, d_values, n, d_out, ws, n_tiles);
-    else if (s == 4)
-        decompress_kernel<4><<<dim3(n_tiles + 1), dim3(kBlock), 0, hs>>>(d_bitmap, d_values, n, d_out, ws, n_tiles);
-    else
-        decompress_kernel<2><<<dim3(n_tiles + 1), dim3(kBlock), 0, hs>>>(d_bitmap, d_values, n, d_out, ws, n_tiles);
-    return launched();
+    const DecompressOne job{d_bitmap, d_values, ~(uint64_t)0, nullptr, n, d_out, n_tiles};
+    return launch_decompress(job, n_tiles, s, static_cast<char *>(d_workspace), (hipStream_t)stream);
 }
 
 bt_status bt_relu_backward_from_bitmap(const uint32_t *d_bitmap, const void *d_grad_out, uint64_t n, bt_dtype dtype,
@@ -1531,47 +1735,13 @@ bt_status bt_mask_apply(const uint32_t *d_bitmap, const void *d_in, uint64_t n, 
     return bt_relu_backward_from_bitmap(d_bitmap, d_in, n, dtype, d_out, stream);
 }
 
-bt_status bt_stream_probe(const void *d_in, void *d_out, uint64_t tiles, int read_rows, int write_rows,
-                          bt_stream stream) {
-    if (d_in == nullptr || d_out == nullptr) return BT_ERR_NULL;
-    if (misaligned(d_in, 16) || misaligned(d_out, 16)) return BT_ERR_ALIGN;
-    if (tiles == 0) return BT_OK;
-    if (tiles > 0x7fffffffu) return BT_ERR_SIZE;
-    hipStream_t hs = (hipStream_t)stream;
-    const dim3 grid((uint32_t)tiles), block(kProbeThreads);
-    const uint4 *in = static_cast<const uint4 *>(d_in);
-    uint4 *out = static_cast<uint4 *>(d_out);
-    const uint32_t t = (uint32_t)tiles;
-    if (read_rows == 8 && write_rows == 4) stream_probe_kernel<8, 4><<<grid, block, 0, hs>>>(in, out, t);
-    else if (read_rows == 4 && write_rows == 8) stream_probe_kernel<4, 8><<<grid, block, 0, hs>>>(in, out, t);
-    else if (read_rows == 8 && write_rows == 8) stream_probe_kernel<8, 8><<<grid, block, 0, hs>>>(in, out, t);
-    else if (read_rows == 8 && write_rows == 0) stream_probe_kernel<8, 0><<<grid, block, 0, hs>>>(in, out, t);
-    else if (read_rows == 0 && write_rows == 8) stream_probe_kernel<0, 8><<<grid, block, 0, hs>>>(in, out, t);
-    else return BT_ERR_SIZE;
-    return launched();
-}
-
-bt_status bt_timeline_set(uint64_t *d_buf, uint64_t buf_words, uint32_t tiles, uint32_t max_passes) {
-#ifdef BT_TIMELINE
-    if (d_buf == nullptr) tiles = max_passes = 0;
-    else if (misaligned(d_buf, 8)) return BT_ERR_ALIGN;
-    if (8 * (uint64_t)tiles + 2 * (uint64_t)max_passes > buf_words) return BT_ERR_SIZE;
-    // blocking copies: this call is the one place where the library waits for the device
-    if (hipMemcpyToSymbol(HIP_SYMBOL(g_timeline_tiles), &tiles, sizeof(tiles)) != hipSuccess ||
-        hipMemcpyToSymbol(HIP_SYMBOL(g_timeline_passes), &max_passes, sizeof(max_passes)) != hipSuccess ||
-        hipMemcpyToSymbol(HIP_SYMBOL(g_timeline), &d_buf, sizeof(d_buf)) != hipSuccess)
-        return BT_ERR_HIP;
-    return BT_OK;
-#else
-    (void)d_buf; (void)buf_words; (void)tiles; (void)max_passes;
-    return BT_ERR_UNSUPPORTED;
-#endif
-}
-
 size_t bt_batch_workspace_bytes(const uint64_t *n, size_t count, bt_dtype dtype) {
     const int s = elem_size(dtype);
     if (s == 0 || (n == nullptr && count != 0)) return 0;
-    return batch_workspace_bytes(count, s, [n](size_t i) { return n[i] > BT_MAX_ELEMENTS ? BT_MAX_ELEMENTS : n[i]; });
+    const auto n_of = [n](size_t i) { return n[i] > BT_MAX_ELEMENTS ? BT_MAX_ELEMENTS : n[i]; };
+    const size_t a = batch_workspace_bytes(count, (size_t)kMaxBatchCompress, s, n_of);
+    const size_t b = batch_workspace_bytes(count, (size_t)kMaxBatchDecompress, s, n_of);
+    return a > b ? a : b;
 }
 
 bt_status bt_compress_batch(const bt_compress_item *items, size_t count, bt_dtype dtype, void *d_workspace,
@@ -1591,28 +1761,26 @@ bt_status bt_compress_batch(const bt_compress_item *items, size_t count, bt_dtyp
             return BT_ERR_ALIGN;
     }
     const auto n_of = [items](size_t i) { return items[i].n; };
-    if (workspace_bytes < batch_workspace_bytes(count, s, n_of)) return BT_ERR_WORKSPACE;
+    if (workspace_bytes < batch_workspace_bytes(count, (size_t)kMaxBatchCompress, s, n_of)) return BT_ERR_WORKSPACE;
 
     hipStream_t hs = (hipStream_t)stream;
     char *ws = static_cast<char *>(d_workspace);
-    for (size_t first = 0; first < count; first += kMaxBatch) {
-        const size_t c = count - first < (size_t)kMaxBatch ? count - first : (size_t)kMaxBatch;
-        CompressBatch b;
+    for (size_t first = 0; first < count; first += kMaxBatchCompress) {
+        const size_t c = count - first < (size_t)kMaxBatchCompress ? count - first : (size_t)kMaxBatchCompress;
+        CompressMany b;
         lay_out(b.lay, first, c, s, n_of);
-        for (size_t i = 0; i < (size_t)kMaxBatch; ++i) {
+        for (size_t i = 0; i < (size_t)kMaxBatchCompress; ++i) {
             const bt_compress_item it = i < c ? items[first + i] : bt_compress_item{nullptr, 0, nullptr, nullptr, 0, nullptr};
-            b.in[i] = it.d_in;
-            b.n[i] = it.n;
-            b.bitmap[i] = it.d_bitmap;
-            b.values[i] = it.d_values;
-            b.cap[i] = it.values_cap;
-            b.nnz[i] = it.d_nnz;
+            b.in_[i] = it.d_in;
+            b.n_[i] = it.n;
+            b.bitmap_[i] = it.d_bitmap;
+            b.values_[i] = it.d_values;
+            b.cap_[i] = it.values_cap;
+            b.nnz_[i] = it.d_nnz;
+            b.index_[i] = nullptr;
+            b.dense_[i] = nullptr;
         }
-        const dim3 grid(b.lay.start[c] + 1), block(kBlock);
-        if (s == 8) compress_batch_kernel<8><<<grid, block, 0, hs>>>(b, ws);
-        else if (s == 4) compress_batch_kernel<4><<<grid, block, 0, hs>>>(b, ws);
-        else compress_batch_kernel<2><<<grid, block, 0, hs>>>(b, ws);
-        const bt_status ls = launched();
+        const bt_status ls = launch_compress(b, b.lay.start[c], dtype, false, false, 0.0, ws, hs);
         if (ls != BT_OK) return ls;
     }
     return BT_OK;
@@ -1632,26 +1800,24 @@ bt_status bt_decompress_batch(const bt_decompress_item *items, size_t count, bt_
             return BT_ERR_ALIGN;
     }
     const auto n_of = [items](size_t i) { return items[i].n; };
-    if (workspace_bytes < batch_workspace_bytes(count, s, n_of)) return BT_ERR_WORKSPACE;
+    if (workspace_bytes < batch_workspace_bytes(count, (size_t)kMaxBatchDecompress, s, n_of)) return BT_ERR_WORKSPACE;
 
     hipStream_t hs = (hipStream_t)stream;
     char *ws = static_cast<char *>(d_workspace);
-    for (size_t first = 0; first < count; first += kMaxBatch) {
-        const size_t c = count - first < (size_t)kMaxBatch ? count - first : (size_t)kMaxBatch;
-        DecompressBatch b;
+    for (size_t first = 0; first < count; first += kMaxBatchDecompress) {
+        const size_t c = count - first < (size_t)kMaxBatchDecompress ? count - first : (size_t)kMaxBatchDecompress;
+        DecompressMany b;
         lay_out(b.lay, first, c, s, n_of);
-        for (size_t i = 0; i < (size_t)kMaxBatch; ++i) {
+        for (size_t i = 0; i < (size_t)kMaxBatchDecompress; ++i) {
             const bt_decompress_item it = i < c ? items[first + i] : bt_decompress_item{nullptr, nullptr, 0, nullptr};
-            b.bitmap[i] = it.d_bitmap;
-            b.values[i] = it.d_values;
-            b.n[i] = it.n;
-            b.out[i] = it.d_out;
+            b.bitmap_[i] = it.d_bitmap;
+            b.values_[i] = it.d_values;
+            b.cap_[i] = ~(uint64_t)0;
+            b.index_[i] = nullptr;
+            b.n_[i] = it.n;
+            b.out_[i] = it.d_out;
         }
-        const dim3 grid(b.lay.start[c] + 1), block(kBlock);
-        if (s == 8) decompress_batch_kernel<8><<<grid, block, 0, hs>>>(b, ws);
-        else if (s == 4) decompress_batch_kernel<4><<<grid, block, 0, hs>>>(b, ws);
-        else decompress_batch_kernel<2><<<grid, block, 0, hs>>>(b, ws);
-        const bt_status ls = launched();
+        const bt_status ls = launch_decompress(b, b.lay.start[c], s, ws, hs);
         if (ls != BT_OK) return ls;
     }
     return BT_OK;

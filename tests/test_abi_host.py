@@ -31,10 +31,12 @@ def test_every_declared_symbol_is_exported(bt):
     assert {"bt_compress", "bt_compressed_size", "bt_decompress", "bt_relu_backward_from_bitmap",
             "bt_compress_pruned", "bt_compress_batch", "bt_decompress_batch", "bt_batch_workspace_bytes",
             "bt_mask_apply", "bt_dense_size", "bt_coo_size", "bt_compress_indexed", "bt_decompress_indexed",
-            "bt_tile_elems", "bt_index_bytes", "bt_stream_probe", "bt_activation_compress"} <= set(names)
+            "bt_tile_elems", "bt_index_bytes", "bt_activation_compress"} <= set(names)
     raw = ctypes.CDLL(bt.LIB_PATH)
     for name in names:
         assert hasattr(raw, name), name
+    # and nothing else: the benchmark's measurement aids live in a library of their own
+    assert not hasattr(raw, "bt_stream_probe") and not hasattr(raw, "bt_timeline_set")
 
 
 def test_header_compiles_as_plain_c(tmp_path):
@@ -270,14 +272,21 @@ def test_activation_compress_host_errors(bt):
     assert call(wsb=wsb - 1) == 4 and call(n=(1 << 37) + 1) == 6 and call(d_in=A + 4) == 3
 
 
-def test_stream_probe_host_errors(bt):
-    L = bt.lib()
+def test_bench_aids_host_errors(bt):
+    """libbittrain_bench.so (bench.py's measurement aids: the codec with time stamps, and a plain stream)
+    exports the whole interface too and checks its own two calls' arguments on the host."""
+    from paper_2110_15362_amd import bench_aids
+    L = bench_aids.lib()
+    for name in _declared_functions():
+        assert hasattr(L, name), name
     A = 0x10000
     assert L.bt_stream_probe(None, A, 10, 8, 4, None) == 1 and L.bt_stream_probe(A, None, 10, 8, 4, None) == 1
     assert L.bt_stream_probe(A + 8, A, 10, 8, 4, None) == 3
     assert L.bt_stream_probe(A, A, 10, 3, 5, None) == 6          # not one of the listed shapes
     assert L.bt_stream_probe(A, A, 1 << 31, 8, 4, None) == 6
     assert L.bt_stream_probe(A, A, 0, 8, 4, None) == 0
+    assert L.bt_timeline_set(0x10000, 8 * 100 + 2 * 10 - 1, 100, 10) == 6      # buffer one word too small
+    assert L.bt_timeline_set(0x10004, 8 * 100 + 2 * 10, 100, 10) == 3          # misaligned
 
 
 def test_bench_refuses_more_than_one_gpu():
@@ -295,21 +304,3 @@ def test_workspace_bytes_cover_every_tile(bt):
             n = tiles * elems_per_tile
             assert bt.bt_workspace_bytes(n, code) == 256 + 768 * ((tiles + 31) // 32)
             assert bt.bt_workspace_bytes(n + 1, code) == 256 + 768 * ((tiles + 1 + 31) // 32)
-
-
-def test_timeline_is_a_build_option(bt):
-    """The regular library exports bt_timeline_set and says that it records nothing; the instrumented
-    build (same source, -DBT_TIMELINE) exports the same symbols and checks the buffer size on the host."""
-    import ctypes
-    from paper_2110_15362_amd import build as hip_build
-    assert bt.lib().bt_timeline_set(None, 0, 0, 0) == 7
-    assert bt.status_str(7) == "not available in this build of the library"
-    if not os.path.exists(hip_build.TIMELINE_LIB):
-        pytest.fail("libbittrain_timeline.so is not built: run __graft_entry__.build()")
-    T = ctypes.CDLL(hip_build.TIMELINE_LIB)
-    T.bt_timeline_set.restype = ctypes.c_int
-    T.bt_timeline_set.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32]
-    for name in _declared_functions():
-        assert hasattr(T, name), name
-    assert T.bt_timeline_set(0x10000, 8 * 100 + 2 * 10 - 1, 100, 10) == 6      # buffer one word too small
-    assert T.bt_timeline_set(0x10004, 8 * 100 + 2 * 10, 100, 10) == 3          # misaligned

@@ -379,8 +379,8 @@ def test_a_wait_that_runs_out_ends_the_kernel_and_raises_the_flag(gpu, oracle):
 
 
 def test_stream_probe_stays_inside_its_buffers(gpu):
-    """The measurement aid reads tiles * read_rows * 4 KiB and writes tiles * write_rows * 4 KiB, no more."""
-    import paper_2110_15362_amd.bittrain as bt
+    """The benchmark's plain stream reads tiles * read_rows * 4 KiB and writes tiles * write_rows * 4 KiB, no more."""
+    from paper_2110_15362_amd import bench_aids as bt
     tiles = 777
     for r, w in ((8, 4), (4, 8), (8, 8), (8, 0), (0, 8)):
         src = torch.arange(tiles * max(r, 1) * 1024, dtype=torch.int32, device="cuda")
