@@ -86,7 +86,7 @@ size_t bt_bitmap_bytes(uint64_t n);
 /* Bytes of scratch that bt_compress / bt_decompress need for a tensor of n
  * elements: a 256-byte header plus 24 bytes per tile of the single-pass grid
  * scan (a tile is 32 KiB of dense data: 4096 eight-byte, 8192 four-byte or 16384
- * two-byte elements), in records of 32 tiles.  Monotone in n; 0 for an unknown dtype. */
+ * two-byte elements), in blocks of 256 tiles.  Monotone in n; 0 for an unknown dtype. */
 size_t bt_workspace_bytes(uint64_t n, bt_dtype dtype);
 
 /* Size in bytes of one element, 0 for an unknown dtype. */

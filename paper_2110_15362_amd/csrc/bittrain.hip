@@ -28,6 +28,7 @@
 // about keeping the memory system busy while prefixes are on their way.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <atomic>
 #include <type_traits>
 
@@ -50,19 +51,29 @@ constexpr int kReluRows = BT_RELU_ROWS;   // 16-byte vectors per lane in the ReL
 // Compression wants LDS (a quarter of a unit's 160 KiB per workgroup: room for the values of
 // about two tiles per wave), restoration wants waves.
 #ifndef BT_COMPRESS_OCC
-#define BT_COMPRESS_OCC 4
+#define BT_COMPRESS_OCC 3
 #endif
 #ifndef BT_DECOMPRESS_OCC
-#define BT_DECOMPRESS_OCC 8
+#define BT_DECOMPRESS_OCC 6
 #endif
 constexpr int kCompressOcc = BT_COMPRESS_OCC;
 constexpr int kDecompressOcc = BT_DECOMPRESS_OCC;
 // Bytes of LDS in which a compressing wave parks values that wait for their prefix.
 #ifndef BT_RING_BYTES
-#define BT_RING_BYTES 9728
+#define BT_RING_BYTES 12288
 #endif
 constexpr int kRingBytes = BT_RING_BYTES;
-constexpr int kRingStride = kRingBytes + kVecBytes;   // + one vector that takes the writes of dropped elements
+// Tiles a compressing wave has on their way at a time (1 or 2), and the pace at which the workgroups of a launch
+// ask for their first tile (nanoseconds per workgroup; 0: all at once).
+#ifndef BT_TILES_AHEAD
+#define BT_TILES_AHEAD 2
+#endif
+#ifndef BT_PACE_NS
+#define BT_PACE_NS 0
+#endif
+constexpr int kTilesAhead = BT_TILES_AHEAD;
+constexpr int kPaceNs = BT_PACE_NS;
+constexpr int kRingStride = kRingBytes + kWaveSize * 8;   // + a place per lane that takes the writes of dropped elements
 constexpr int kQueue = 16;                            // parked phases per wave, at most
 // Tiles ahead of the one it restores for which a restoring workgroup has published its counts.
 #ifndef BT_COUNT_AHEAD
@@ -71,20 +82,22 @@ constexpr int kQueue = 16;                            // parked phases per wave,
 constexpr int kCountAhead = BT_COUNT_AHEAD;
 
 // ---- workspace layout -----------------------------------------------------------------
-// Header (uint32 words), then one 768-byte record per 32 tiles.
+// Header (uint32 words), then one 6 KiB block per 256 slots.
 constexpr int kHdrSeq = 0;       // calls completed on this workspace; its low bit picks the copy in use
-constexpr int kHdrPrevTiles = 1; // tiles of the previous call (what it left behind in the other copy)
+constexpr int kHdrPrevTiles = 1; // slots of the previous call (what it left behind in the other copy)
 constexpr int kHdrError = BT_WS_ERROR_WORD;           // set if a wait was given up
 constexpr int kHdrSpinLimit = BT_WS_WAIT_LIMIT_WORD;  // polls before a wait is given up; 0: kSpinLimit
 constexpr size_t kHeaderBytes = 256;
-// Record of 32 tiles, two copies c = 0, 1 of everything, in separate 128-byte lines:
-//   [128*c, 128*c + 128)          uint32 count + 1 of each tile, written by the tile
-//   [256 + 256*c, 256*c + 512)    uint64 prefix + 1 of each tile, written by the scanner
+constexpr size_t kHdrSpare = 128;      // bytes [128, 256) of the header take stores that mean nothing (see the scanner)
+// Block of 256 slots, two copies c = 0, 1 of everything:
+//   [1024*c, 1024*c + 1024)            uint32 count + 1 of each slot, written by the slot's workgroup
+//   [2048 + 2048*c, 2048*c + 4096)     uint64 prefix + 1 of each slot, written by the scanner
 // 0 means "not published yet".  A call uses copy (seq & 1) and zeroes what the
 // previous call left in the other copy, so the copy the next call uses is clean
-// when it starts and no clearing launch is ever needed.
-constexpr size_t kRecordBytes = 768;
-constexpr int kTilesPerRecord = 32;
+// when it starts and no clearing launch is ever needed.  The layout depends only on the
+// slot number, never on the size of the workspace or of the call.
+constexpr int kSlotsPerBlock = 256;
+constexpr size_t kBlockBytes = 6144;
 constexpr uint32_t kSpinLimit = 1u << 20; // polls before a wait is given up
 #ifndef BT_SCANNER_SLEEP
 #define BT_SCANNER_SLEEP 1
@@ -137,6 +150,14 @@ template <int G> __device__ __forceinline__ uint32_t group_or(uint32_t x) {
     if (G >= 8) x |= BT_DPP(0, x, 0x141, 0xf, true);   // row_half_mirror: lane i <-> 7 - i
     if (G == 16) x |= BT_DPP(0, x, 0x140, 0xf, true);  // row_mirror: lane i <-> 15 - i
     return x;
+}
+
+// A workgroup barrier that orders LDS traffic only.  (__syncthreads() also waits for every global load
+// and store of the wave, which would make a wave that has the next tile's loads in flight wait for them.)
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 // Order LDS traffic between the lanes of one wave (no block barrier involved).
@@ -446,7 +467,7 @@ static_assert(sizeof(DecompressMany) <= 3840, "kernel arguments of a batched res
 // tiles before it (Algorithm 1 appends in index order; Algorithm 2's counter j).
 // Tiles do not talk to each other.  Each tile publishes its count in the workspace;
 // ONE extra workgroup (workgroup 0, a single wave: the "scanner") reads the counts
-// in index order, up to kScanRows x 64 at a time, keeps the running sum, and writes every
+// in index order, kScanGroups x 256 at a time, keeps the running sum, and writes every
 // tile's prefix back; a wave then polls the prefix of its tile, one 8-byte load.  Per
 // tile that is one store and a few polled loads on lines shared with few other tiles.
 // (Having every tile read its predecessors' counts itself -- a look-back window or a tree --
@@ -497,11 +518,11 @@ __device__ __forceinline__ void ws_store32(void *p, uint32_t v) {
 }
 // count + 1 of `tile` in copy c
 __device__ __forceinline__ char *ws_count(char *ws, uint32_t tile, uint32_t copy) {
-    return ws + kHeaderBytes + (size_t)(tile >> 5) * kRecordBytes + 128u * copy + 4u * (tile & 31u);
+    return ws + kHeaderBytes + (size_t)(tile >> 8) * kBlockBytes + 1024u * copy + 4u * (tile & 255u);
 }
 // prefix + 1 of `tile` in copy c
 __device__ __forceinline__ char *ws_prefix(char *ws, uint32_t tile, uint32_t copy) {
-    return ws + kHeaderBytes + (size_t)(tile >> 5) * kRecordBytes + 256u + 256u * copy + 8u * (tile & 31u);
+    return ws + kHeaderBytes + (size_t)(tile >> 8) * kBlockBytes + 2048u + 2048u * copy + 8u * (tile & 255u);
 }
 
 // The same value in every lane: tell the compiler, so that what is built on it stays in scalar registers.
@@ -530,104 +551,221 @@ template <int SLEEP> __device__ __forceinline__ bool spin_expired(uint32_t *hdr,
     return false;
 }
 
-// The scanner: one wave.  Each pass looks at kScanRows x 64 counts starting at the
-// frontier rounded down to a multiple of 64; lane l of row j looks at slot
-// w0 + 64*j + l, so every load and store of a row is one contiguous run.  The pass
-// takes the leading run of published counts, turns it into prefixes (a wave prefix
-// sum per row, carried from row to row), writes them, and moves the frontier.
-// When a tensor's counts are all in it writes the tensor's total (nnz); at the end it
-// advances the header for the next call.  If the call wants a tile index (Algorithm 2's j at
-// every tile start, for bt_decompress_indexed) the prefixes of real tiles also go there.
-#ifndef BT_SCAN_ROWS
-#define BT_SCAN_ROWS 7
+// The scanner.  A pass of one of its waves looks at the kScanGroups x 256 slots of a window.  Lane l takes the four consecutive slots 4l .. 4l + 3 of a block, so the
+// counts of a block are one 16-byte load per lane and its prefixes two 16-byte stores; the
+// 16 lanes of a DPP row hold 64 consecutive slots, the unit in which batched tensors are laid
+// out.  The pass takes the leading run of published counts, turns it into prefixes (four
+// adds inside the lane, four DPP steps inside the row, the rows chained through scalar
+// registers, where a tensor's total is also taken and the sum restarts at a tensor's first
+// row), writes them, and moves the frontier.  At the end it advances the header for the
+// next call.
+//
+// The passes are pipelined.  On this hardware one counter tracks a wave's loads and
+// stores alike, in order of issue: a load that is waited for after a store also waits for
+// that store to reach memory, which would make a pass cost two round trips.  So the counts
+// of the NEXT window are asked for before the prefixes of the current one are stored, and
+// every pass issues exactly the same instructions behind its loads (a lane with nothing to
+// store writes to a spare line of the header), so that the wait for the counts can leave
+// precisely those stores outstanding.
+#ifndef BT_SCAN_GROUPS
+#define BT_SCAN_GROUPS 1
 #endif
-constexpr int kScanRows = BT_SCAN_ROWS;
+constexpr int kScanGroups = BT_SCAN_GROUPS;
 
-template <class Job> __device__ __forceinline__ void scan_counts(char *ws, const Job &job) {
+// Inclusive prefix sum inside each row of 16 lanes.
+__device__ __forceinline__ uint32_t row_inclusive_sum(uint32_t x) {
+    x += BT_DPP(0, x, 0x111, 0xf, true);   // row_shr:1
+    x += BT_DPP(0, x, 0x112, 0xf, true);   // row_shr:2
+    x += BT_DPP(0, x, 0x114, 0xf, true);   // row_shr:4
+    x += BT_DPP(0, x, 0x118, 0xf, true);   // row_shr:8
+    return x;
+}
+
+// The four waves of workgroup 0 share the work: the call's slots are cut into windows of
+// kScanGroups x 256, window k belongs to wave k mod 4.  A wave polls the counts of its window from
+// the start, whether or not the frontier has reached it; it may turn them into prefixes once the
+// wave before it has finished the window before and handed over the running sum (through LDS).
+// So up to four windows' counts are on their way at a time, and when the frontier enters a
+// window that window's counts are mostly there already: a memory round trip (several
+// microseconds when the memory system is busy) is paid once per four windows, not once per window.
+struct ScanShared {
+    uint64_t running[kWaves];   // a wave's running sum at the end of the window it finished last
+    uint32_t item[kWaves];      //   and the tensor that window ended in
+    uint32_t done[kWaves];      // 1 + the window a wave finished last (0: none yet)
+};
+
+template <class Job> __device__ __forceinline__ void scan_counts(char *ws, const Job &job, ScanShared &sh) {
     const uint32_t lane = threadIdx.x & (kWaveSize - 1);
+    const uint32_t wave = uniform32(threadIdx.x >> 6);
     uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
     const uint32_t seq = hdr[kHdrSeq];
     const uint32_t cur = seq & 1u;
     const uint32_t n_items = job.count();
     const uint32_t n_slots = job.slots();
-    uint32_t frontier = 0;     // slots [0, frontier) are done
-    uint32_t item = 0;         // tensor that slot `frontier` belongs to
-    uint64_t running = 0;      // stored values of tensor `item` in its tiles before `frontier`
-    uint32_t spins = 0;
+    const uint32_t last_block = (n_slots - 1) >> 8;
+    constexpr uint32_t kWindow = 256u * kScanGroups;
+    const uint32_t n_windows = (n_slots + kWindow - 1) / kWindow;
     const uint32_t limit = wait_limit(hdr);
+    char *const nowhere = ws + kHdrSpare + 8u * (lane & 15u);
+    if (lane == 0) sh.done[wave] = 0;
+    __syncthreads();
 #ifdef BT_TIMELINE
     uint64_t *const timeline = g_timeline;      // read once: a load in the loop would join the scanner's waits
-    uint32_t timeline_pass = 0;
+    uint32_t timeline_pass = wave;
 #endif
-    while (frontier < n_slots) {
-        const uint32_t w0 = frontier & ~63u;
-        uint32_t c[kScanRows];
+    // counts of the blocks b0, b0 + 1, ...: no branch around a load; blocks beyond the call read the last block
+    // and are not looked at.  Two 8-byte atomic loads per lane and block (there is no 16-byte one).
+    auto ask = [&](bt_u4 (&c)[kScanGroups], const uint32_t b0) {
 #pragma unroll
-        for (int j = 0; j < kScanRows; ++j) {
-            const uint32_t t = w0 + 64u * j + lane;
-            c[j] = 0;
-            if (t < n_slots)
-                c[j] = __hip_atomic_load(reinterpret_cast<const uint32_t *>(ws_count(ws, t, cur)), __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
+        for (int j = 0; j < kScanGroups; ++j) {
+            const uint32_t b = b0 + j < last_block ? b0 + j : last_block;
+            const char *const p = ws_count(ws, 256u * b + 4u * lane, cur);
+            const uint64_t lo = ws_load64(p), hi = ws_load64(p + 8);
+            c[j].x = (uint32_t)lo; c[j].y = (uint32_t)(lo >> 32); c[j].z = (uint32_t)hi; c[j].w = (uint32_t)(hi >> 32);
         }
-        // Look at every row before writing anything: on this hardware one counter tracks
-        // loads and stores alike, so a load waited for after a store also waits for that
-        // store to reach memory.
-        uint64_t usable_lanes[kScanRows];
+    };
+    const auto store_behind = [&](char *p0, char *p1, char *p2, char *p3, const uint64_t v0, const uint64_t v1,
+                                  const uint64_t v2, const uint64_t v3) {
+        ws_store64(p0, v0);
+        ws_store64(p1, v1);
+        ws_store64(p2, v2);
+        ws_store64(p3, v3);
+    };
+    for (uint32_t window = wave; window < n_windows; window += kWaves) {
+        const uint32_t b0 = window * kScanGroups;
+        const uint32_t window_end = kWindow * (window + 1) < n_slots ? kWindow * (window + 1) : n_slots;
+        uint32_t frontier = kWindow * window;     // slots [window start, frontier) are done
+        bool mine = window == 0;                  // the window before this one is finished, its sums are known
+        uint32_t item = 0;                        // tensor that slot `frontier` belongs to
+        uint64_t running = 0;                     // stored values of tensor `item` in its tiles before `frontier`
+        uint32_t spins = 0;
+        bt_u4 c[kScanGroups];
+        ask(c, b0);
 #pragma unroll
-        for (int j = 0; j < kScanRows; ++j) {
-            const uint32_t t = w0 + 64u * j + lane;
-            usable_lanes[j] = __ballot(t < frontier || (t < n_slots && c[j] != 0));   // done before, or published
-        }
-        // rows are consumed in order while every slot of the row is usable
-        bool open = true;
-        uint32_t new_frontier = frontier;
+        for (int j = 0; j < kScanGroups; ++j)     // as many stores behind these loads as behind all later ones
+            store_behind(nowhere, nowhere, nowhere, nowhere, 0, 0, 0, 0);
+        while (frontier < window_end) {
+            // (1) how far the leading run of usable slots goes: done before, published, or beyond the call
+            uint32_t run_end = frontier;
+            {
+                bool open = true;
 #pragma unroll
-        for (int j = 0; j < kScanRows; ++j) {
-            const uint32_t row0 = w0 + 64u * j;
-            const uint32_t t = row0 + lane;
-            if (open && row0 < n_slots) {
-                const uint64_t bad = ~usable_lanes[j];                             // lanes that stop the run
-                const uint32_t run = bad == 0 ? 64u : (uint32_t)__ffsll((unsigned long long)bad) - 1u;
-                const uint32_t row_end = row0 + run;                               // slots [row0, row_end) usable
-                if (row_end > new_frontier) {
-                    while (item + 1 < n_items && row0 >= job.start(item + 1)) ++item;
-                    const uint32_t item_start = job.start(item);
-                    if (row0 == item_start && new_frontier <= row0) running = 0;   // a new tensor begins
-                    const bool fresh = t >= frontier && t < row_end;
-                    const uint32_t mine = fresh ? c[j] - 1u : 0u;
-                    const uint32_t incl = wave_inclusive_sum(mine);
-                    const uint64_t excl = running + (incl - mine);
-                    if (fresh) ws_store64(ws_prefix(ws, t, cur), excl + 1);
-                    uint64_t *const index = job.index(item);
-                    if (fresh && index != nullptr && t - item_start < job.tiles(item)) index[t - item_start] = excl;
-                    running += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-                    new_frontier = row_end;
-                    uint64_t *const nnz = job.nnz(item);
-                    if (row_end == job.start(item + 1) && lane == 0 && nnz != nullptr)
-                        *nnz = running;                                            // the length of this tensor's value array
+                for (int j = 0; j < kScanGroups; ++j) {
+                    const uint32_t s0 = 256u * (b0 + j) + 4u * lane;
+                    const uint32_t cc[4] = {c[j].x, c[j].y, c[j].z, c[j].w};
+                    uint32_t lane_run = 0;
+                    bool ok = true;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        ok = ok && (s0 + k >= n_slots || s0 + k < frontier || cc[k] != 0);
+                        lane_run += ok ? 1u : 0u;
+                    }
+                    const uint64_t whole = __ballot(lane_run == 4);
+                    const uint32_t first_short = whole == ~(uint64_t)0 ? 64u : (uint32_t)__ffsll((unsigned long long)~whole) - 1u;
+                    const uint32_t short_run = (uint32_t)__builtin_amdgcn_readlane((int)lane_run, (int)(first_short & 63u));
+                    uint32_t end = 256u * (b0 + j) + (first_short == 64u ? 256u : 4u * first_short + short_run);
+                    if (end > n_slots) end = n_slots;
+                    if (open && b0 + j <= last_block && end > run_end) run_end = end;
+                    open = open && first_short == 64u;
                 }
-                open = run == 64u;
             }
-        }
-        if (new_frontier == frontier) {
-            if (spin_expired<kScannerSleep>(hdr, spins, limit)) return;
-            continue;
-        }
+            if (!mine) {
+                // Has the wave before this one finished the window before?  If every count of this window is here
+                // already there is nothing to ask memory for: wait for the hand-over in LDS, which is quick to poll.
+                const uint32_t before = (wave + kWaves - 1) & (kWaves - 1);
+                for (;;) {
+                    const uint32_t d = __hip_atomic_load(&sh.done[before], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    if (uniform32(d) == window) {     // it has finished window - 1
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");   // LDS only: no wait for global memory
+                        running = uniform64(sh.running[before]);
+                        item = uniform32(sh.item[before]);
+                        mine = true;
+                        break;
+                    }
+                    if (run_end != window_end) break;
+                    if (spin_expired<kScannerSleep>(hdr, spins, limit)) return;
+                }
+            }
+            const uint32_t new_frontier = mine ? run_end : frontier;
+            // (2) prefixes of the fresh slots [frontier, new_frontier)
+            uint32_t in_lane[kScanGroups][3];      // sums of a lane's first one, two, three counts
+            uint32_t in_row[kScanGroups];          // a lane's place inside its row of 64 slots
+            uint64_t base[kScanGroups];            // what comes before the lane's row
+#pragma unroll
+            for (int j = 0; j < kScanGroups; ++j) {
+                const uint32_t s0 = 256u * (b0 + j) + 4u * lane;
+                const uint32_t cc[4] = {c[j].x, c[j].y, c[j].z, c[j].w};
+                uint32_t m[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) m[k] = (s0 + k >= frontier && s0 + k < new_frontier) ? cc[k] - 1u : 0u;
+                in_lane[j][0] = m[0];
+                in_lane[j][1] = m[0] + m[1];
+                in_lane[j][2] = in_lane[j][1] + m[2];
+                const uint32_t total = in_lane[j][2] + m[3];
+                const uint32_t incl = row_inclusive_sum(total);
+                in_row[j] = incl - total;
+                uint64_t row_base[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t row0 = 256u * (b0 + j) + 64u * r;
+                    const uint32_t row_total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 16 * r + 15);
+                    const uint32_t lo = row0 > frontier ? row0 : frontier;
+                    const uint32_t hi = row0 + 64u < new_frontier ? row0 + 64u : new_frontier;
+                    if (lo < hi) {                                                     // the row has fresh slots
+                        while (item + 1 < n_items && row0 >= job.start(item + 1)) ++item;
+                        if (row0 == job.start(item) && frontier <= row0) running = 0;  // a new tensor begins
+                        row_base[r] = running;
+                        running += row_total;
+                        uint64_t *const nnz = job.nnz(item);
+                        if (hi == job.start(item + 1) && lane == 0 && nnz != nullptr)
+                            *nnz = running;                                            // the length of this tensor's value array
+                    }
+                }
+                const uint32_t r = lane >> 4;
+                base[j] = r == 0 ? row_base[0] : r == 1 ? row_base[1] : r == 2 ? row_base[2] : row_base[3];
+            }
+            if (new_frontier == frontier) {
+                if (spin_expired<kScannerSleep>(hdr, spins, limit)) return;
+            }
 #ifdef BT_TIMELINE
-        if (timeline != nullptr && lane == 0 && timeline_pass < g_timeline_passes) {
-            timeline[8 * (size_t)g_timeline_tiles + 2 * timeline_pass] = wall_clock64();
-            timeline[8 * (size_t)g_timeline_tiles + 2 * timeline_pass + 1] = ((uint64_t)frontier << 32) | new_frontier;
-            ++timeline_pass;
-        }
+            else if (timeline != nullptr && lane == 0 && timeline_pass < g_timeline_passes) {
+                timeline[8 * (size_t)g_timeline_tiles + 2 * timeline_pass] = wall_clock64();
+                timeline[8 * (size_t)g_timeline_tiles + 2 * timeline_pass + 1] = ((uint64_t)frontier << 32) | new_frontier;
+                timeline_pass += kWaves;
+            }
 #endif
-        frontier = new_frontier;
-    }
-    if (lane == 0) {
-        // every workgroup of the launch has at least one slot and has published its count by now, hence has
-        // read the header: advance it
-        __hip_atomic_store(&hdr[kHdrPrevTiles], n_slots, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&hdr[kHdrSeq], seq + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // (3) the window again, for what was not published yet: asked for before (4), see above
+            bt_u4 c_next[kScanGroups];
+            ask(c_next, b0);
+            // (4) now the stores: a fresh slot's prefix to its entry, everything else to the spare line
+#pragma unroll
+            for (int j = 0; j < kScanGroups; ++j) {
+                const uint32_t s0 = 256u * (b0 + j) + 4u * lane;
+                bool fresh[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) fresh[k] = s0 + k >= frontier && s0 + k < new_frontier;
+                const uint64_t at = base[j] + in_row[j] + 1;
+                char *const p = ws_prefix(ws, s0 < n_slots ? s0 : 0u, cur);
+                store_behind(fresh[0] ? p : nowhere, fresh[1] ? p + 8 : nowhere, fresh[2] ? p + 16 : nowhere,
+                             fresh[3] ? p + 24 : nowhere, at, at + in_lane[j][0], at + in_lane[j][1], at + in_lane[j][2]);
+            }
+#pragma unroll
+            for (int j = 0; j < kScanGroups; ++j) c[j] = c_next[j];
+            frontier = new_frontier;
+        }
+        // the window is finished: hand the sums over to the wave that has the next one
+        if (lane == 0) {
+            sh.running[wave] = running;
+            sh.item[wave] = item;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");   // LDS only: the prefix stores are not waited for
+            __hip_atomic_store(&sh.done[wave], window + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        if (window + 1 == n_windows && lane == 0) {
+            // every workgroup of the launch has at least one slot and has published its count by now, hence has
+            // read the header: advance it
+            __hip_atomic_store(&hdr[kHdrPrevTiles], n_slots, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&hdr[kHdrSeq], seq + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 
@@ -738,12 +876,20 @@ __device__ __forceinline__ void ring_flush(const unsigned char *data, char *g0_p
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t v = 1u + (uint32_t)lane + (uint32_t)kWaveSize * i;
+#ifdef BT_EXP_FLUSH_B128
+        if (v + 1 < n_vec) t[i] = *reinterpret_cast<const uint4 *>(data + (size_t)v * kVecBytes);
+#else
         if (v + 1 < n_vec) t[i] = lds_read16<S>(src + (size_t)v * kVecBytes, odd_half);
+#endif
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t v = 1u + (uint32_t)lane + (uint32_t)kWaveSize * i;
+#ifdef BT_EXP_NO_FLUSH_STORE
+        if (v + 1 < n_vec && t[i].x == 0x12345678u && t[i].y == 0x9abcdef1u) stream_store<kCompressNtStore>(reinterpret_cast<uint4 *>(gvec + (size_t)v * kVecBytes), t[i]);
+#else
         if (v + 1 < n_vec) stream_store<kCompressNtStore>(reinterpret_cast<uint4 *>(gvec + (size_t)v * kVecBytes), t[i]);
+#endif
     }
     // the first and the last vector, an element a lane: lane j < E element j of the first, lane E + j element j
     // of the last, each only if it lies inside [pad, pad + cnt)
@@ -777,10 +923,10 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
     constexpr int E = G::E;
     __shared__ __attribute__((aligned(16))) unsigned char s_ring[kWaves * kRingStride];
     __shared__ uint32_t s_wave_total[2][kWaves];
-    if (workspace_failed(ws)) return;
+    __shared__ ScanShared s_scan;
     const uint32_t n_slots = job.slots();
     if (blockIdx.x == 0) {
-        if (threadIdx.x < kWaveSize) scan_counts(ws, job);
+        if (!workspace_failed(ws)) scan_counts(ws, job, s_scan);
         return;
     }
     const int tid = threadIdx.x;
@@ -788,6 +934,42 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in a scalar register
     const uint32_t worker = blockIdx.x - 1, workers = gridDim.x - 1;
     uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
+
+    // (1) load: lane l of row k owns elements wave_e0 + k*ROW + l*E ... + E-1 of its wave's part of the tile; all
+    //     rows of a tile are asked for at once.  The first tile is asked for before anything else is done.
+    //     xa and xb take turns: as soon as a tile has arrived the next one is asked for, into the other buffer, so that
+    //     the work on a tile (ranks, bitmap, compaction) does not leave the memory system idle.
+    uint4 xa[kRows], xb[kRows];
+    // Always the same eight loads, whatever the slot: from the tile if it is a whole tile, else (no such slot, a slot
+    // that belongs to no tile, a tensor's ragged last tile) from somewhere harmless in the workspace.  The number
+    // of loads behind the other buffer's loads then never depends on the data, and the wait for one buffer can leave
+    // exactly the other buffer's loads outstanding.  A ragged tile is loaded when its turn comes (see below).
+    // (a line of the workspace's first block that depends on the wave, so that no line has many readers)
+    const uint4 *const nowhere = reinterpret_cast<const uint4 *>(ws + kHeaderBytes + ((worker * kWaves + (uint32_t)wave) * 64u) % (uint32_t)kBlockBytes);
+    auto ask_tile = [&](uint4 (&x)[kRows], const uint64_t slot64) {
+        const uint4 *p = nowhere;
+        uint32_t row_stride = 0;
+        if (slot64 < n_slots) {
+            const Slot sl = job.at((uint32_t)slot64);
+            if (!sl.idle && (uint64_t)(sl.tile + 1) * G::TILE <= job.n(sl.item)) {
+                const uint64_t wave_e0 = (uint64_t)sl.tile * G::TILE + (uint64_t)wave * G::WAVE;
+                p = reinterpret_cast<const uint4 *>(static_cast<const char *>(job.in(sl.item)) + wave_e0 * S) + lane;
+                row_stride = kWaveSize;
+            }
+            BT_TL((uint32_t)slot64, 0);
+        }
+#pragma unroll
+        for (int k = 0; k < kRows; ++k) x[k] = stream_load<kCompressNtLoad>(p + k * row_stride);
+    };
+    if (kPaceNs != 0) {
+        // the first tiles are asked for in index order, at about the pace at which memory serves them: asked for all at
+        // once they would all arrive together, at the end of the burst, and the scan could not start before that
+        const uint64_t until = wall_clock64() + (uint64_t)worker * kPaceNs / 10;     // the clock ticks every 10 ns
+        while ((uint64_t)wall_clock64() < until) __builtin_amdgcn_s_sleep(1);
+    }
+    ask_tile(xa, worker);
+
+    if (workspace_failed(ws)) return;
     // written at the end of the previous call; constant until every slot of this call has published
     const Epoch ep = read_epoch(ws);
     const uint32_t cur = ep.cur;
@@ -800,11 +982,11 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
     // slack.  Entries never wrap: one that does not fit behind the newest goes to the front.
     // The queue itself lives in four vector registers, entry i in lane i.
     unsigned char *const ring = s_ring + wave * kRingStride;
-    unsigned char *const dump = ring + kRingBytes;     // takes the writes of dropped elements; never read
+    unsigned char *const dump = ring + kRingBytes + lane * S;   // takes this lane's writes of dropped elements; never read
     uint32_t q_place = 0, q_slot = 0, q_before = 0, q_item = 0;   // start | count << 16; slot; values of the tile before it; tensor
     uint32_t q_head = 0, q_n = 0;        // oldest entry, number of entries
     uint32_t r_head = 0, r_tail = 0;     // ring bytes [r_head, r_tail) are in use (cyclically)
-    uint32_t polls = 0;
+    uint32_t polls = 0, blocked = 0;
     uint32_t barriers = 0;
 
 #define BT_Q(field, i) ((uint32_t)__builtin_amdgcn_readlane((int)(field), (int)uniform32((i) & (kQueue - 1))))
@@ -815,6 +997,9 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
         uint32_t cnt = place >> 16;
         const uint64_t g0 = prefix + before;
         const uint64_t cap = job.cap(item);
+        // Algorithm 2's j at the start of this tile, for bt_decompress_indexed: the tile's first wave leaves it
+        uint64_t *const index = job.index(item);
+        if (index != nullptr && wave == 0 && before == 0 && lane == 0) index[BT_Q(q_slot, q_head) - job.start(item)] = prefix;
         // capacity clamp: never write at or beyond values_cap
         if (g0 >= cap) cnt = 0;
         else if (cap - g0 < cnt) cnt = (uint32_t)(cap - g0);
@@ -824,40 +1009,44 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
         --q_n;
         r_head = q_n != 0 ? (BT_Q(q_place, q_head) & 0xffffu) : r_tail;
     };
+    // The oldest parked tile's prefix is asked for while a tile is worked on and looked at when the NEXT tile
+    // is worked on: a wave's loads come back in the order they were issued, so the answer cannot be seen before
+    // the other buffer's loads, which are older, have landed -- and those land just before the next tile's turn.
+    // The load is issued whether or not anything is parked (a spare line of the header then), so that the
+    // number of memory operations behind a tile's loads does not depend on it.
+    uint32_t polled_slot = 0;
+    uint64_t polled = 0;
+    bool polling = false;
+    auto ask_prefix = [&]() {
+        polling = q_n != 0;
+        polled_slot = polling ? BT_Q(q_slot, q_head) : 0u;
+        polled = ws_load64(polling ? ws_prefix(ws, polled_slot, cur) : ws + kHdrSpare);
+        ++polls;
+    };
 
-    for (uint32_t slot = worker; slot < n_slots; slot += workers) {
+    // one tile: `x` holds its elements (asked for two tiles ago); at the end `x` is asked to fetch the tile after next
+    auto work_on = [&](uint4 (&x)[kRows], uint4 (&x_next)[kRows], const uint32_t slot) {
         const Slot sl = job.at(slot);
         if (sl.idle) {                   // a slot of a batched call that belongs to no tile
             if (tid == 0) ws_store32(ws_count(ws, slot, cur), 1);
-            if ((uint64_t)slot + workers >= n_slots) break;
-            continue;
+            ask_tile(x_next, (uint64_t)slot + workers);
+            return;
         }
-        const void *const in = job.in(sl.item);
         const uint64_t n = job.n(sl.item);
         const uint64_t n_words = (n + 31) >> 5;
         const uint64_t wave_e0 = (uint64_t)sl.tile * G::TILE + (uint64_t)wave * G::WAVE;
         const bool full = (uint64_t)(sl.tile + 1) * G::TILE <= n;
 
-        // (1) load: lane l of row k owns elements wave_e0 + k*ROW + l*E ... + E-1; all rows are
-        //     asked for at once.  Then Algorithm 1's test "T[i] == 0", on the bit pattern.
-        uint4 x[kRows];
+        // Algorithm 1's test, on the bit pattern (optionally after the pruning of Section 4.3)
         uint32_t mp[G::MW], rank2[kRows / 2], total2[kRows / 2];
 #pragma unroll
         for (int i = 0; i < G::MW; ++i) mp[i] = 0;
-        if (full) {
-            const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const char *>(in) + wave_e0 * S) + lane;
-#pragma unroll
-            for (int k = 0; k < kRows; ++k) x[k] = stream_load<kCompressNtLoad>(p + k * kWaveSize);
-        } else {
+        if (!full) {                     // a ragged last tile: not asked for in advance; elements at or beyond n read as 0
+            const void *const in = job.in(sl.item);
 #pragma unroll
             for (int k = 0; k < kRows; ++k)
                 x[k] = load_vec_guarded<S>(in, wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E, n);
         }
-        BT_TL(slot, 0);
-        // the oldest parked tile's prefix: asked for behind the loads, it comes back with them
-        const uint32_t polled_slot = q_n != 0 ? BT_Q(q_slot, q_head) : 0u;
-        uint64_t polled = 0;
-        if (q_n != 0) { polled = ws_load64(ws_prefix(ws, polled_slot, cur)); ++polls; }
         if (full) {
 #pragma unroll
             for (int k = 0; k < kRows; ++k) {
@@ -878,6 +1067,13 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
         // result (a scalar register pair) per element alive until the values are written.
 #pragma unroll
         for (int i = 0; i < G::MW; ++i) asm volatile("" : "+v"(mp[i]));
+        // The tile has arrived and its elements have been looked at: ask for the next one now, into the other
+        // buffer (this one is needed until the tile's values are parked), and behind it for the prefix of the oldest
+        // parked tile; what the previous turn asked about has come back with this tile's elements.
+        const bool answered = polling;
+        const uint32_t answered_slot = polled_slot;
+        const uint64_t answer = polled;
+        if (kTilesAhead == 2) ask_tile(x_next, (uint64_t)slot + workers);
         rank_rows<S>(mp, rank2, total2);
         uint32_t wave_total = 0;
 #pragma unroll
@@ -887,7 +1083,7 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
         const uint32_t par = barriers & 1u;
         ++barriers;
         if (lane == 0) s_wave_total[par][wave] = wave_total;
-        __syncthreads();
+        lds_barrier();
         const uint32_t t0 = s_wave_total[par][0], t1 = s_wave_total[par][1], t2 = s_wave_total[par][2],
                        t3 = s_wave_total[par][3];
         if (tid == 0) ws_store32(ws_count(ws, slot, cur), t0 + t1 + t2 + t3 + 1);
@@ -912,19 +1108,19 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
             }
         }
 
-        // the oldest parked tile, if its prefix has come
-        if (q_n != 0) {
-            const uint64_t v = uniform64(polled);
+        // the tile that was the oldest parked one a turn ago, if its prefix had come
+        if (answered) {
+            const uint64_t v = uniform64(answer);
             if (v != 0) {
-                BT_TL(polled_slot, 2);
-                while (q_n != 0 && BT_Q(q_slot, q_head) == polled_slot) flush_head(v - 1);
-                BT_TL(polled_slot, 3);
+                BT_TL(answered_slot, 2);
+                while (q_n != 0 && BT_Q(q_slot, q_head) == answered_slot) flush_head(v - 1);
+                BT_TL(answered_slot, 3);
             }
         }
 
         // (4) kPhaseRows rows at a time, compact this wave's kept elements into its ring.  (A call
-        //     that has no room for any value -- the bitmap alone is wanted -- skips this.)
-        if (job.cap(sl.item) != 0) {
+        //     that has no room for any value and wants no tile index -- the bitmap alone is wanted -- skips this.)
+        if (job.cap(sl.item) != 0 || job.index(sl.item) != nullptr) {
             uint32_t before = before_wave;
 #pragma unroll
             for (int r0 = 0; r0 < kRows; r0 += kPhaseRows) {
@@ -950,6 +1146,7 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
                     }
                     if (fits) break;
                     // no room: the oldest entry has to leave first, however long its prefix takes
+                    ++blocked;
                     const uint32_t s_old = BT_Q(q_slot, q_head);
                     const uint64_t prefix = wait_prefix(ws, s_old, cur, hdr, limit, polls);
                     BT_TL(s_old, 2);
@@ -969,8 +1166,9 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
                 before += cnt;
                 // every element is written, a dropped one to a place nobody reads: a select on the address
                 // instead of a branch around the write keeps the execution mask alone
-                const int data_rel = (int)(start + kVecBytes) - kRingBytes;     // of the entry's first value, from `dump`
+                const int data_rel = (int)(start + kVecBytes) - kRingBytes - lane * S;   // of the entry's first value, from this lane's spare place
                 uint32_t row_start = 0;
+#ifndef BT_EXP_NO_COMPACT
 #pragma unroll
                 for (int k = r0; k < r0 + kPhaseRows; ++k) {
                     int rb = data_rel + (int)(row_start + BT_FIELD(rank2, k)) * S;
@@ -1000,6 +1198,7 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
                     }
                     row_start += BT_FIELD(total2, k);
                 }
+#endif
             }
             wave_lds_sync();             // the values are in the ring before anything reads them
         }
@@ -1031,7 +1230,18 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
                 else store_vec_guarded<S>(dense, e0, n, o);
             }
         }
-        if ((uint64_t)slot + workers >= n_slots) break;      // (slot += workers must not wrap)
+        // the tile after next takes this buffer: its loads are the last memory operations of the turn
+        if (kTilesAhead == 1) ask_tile(x_next, (uint64_t)slot + workers);   // one buffer: the next tile can only be asked for now
+        ask_prefix();
+    };
+
+    for (uint64_t slot = worker; slot < n_slots; slot += kTilesAhead * (uint64_t)workers) {
+        if (kTilesAhead == 1) {
+            work_on(xa, xa, (uint32_t)slot);
+        } else {
+            work_on(xa, xb, (uint32_t)slot);
+            if (slot + workers < n_slots) work_on(xb, xa, (uint32_t)(slot + workers));
+        }
     }
 
     // what is still parked
@@ -1042,7 +1252,9 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
         while (q_n != 0 && BT_Q(q_slot, q_head) == s_old) flush_head(prefix);
         BT_TL(s_old, 3);
         BT_TL_VALUE(s_old, 5, polls);
+        BT_TL_VALUE(s_old, 6, blocked);
     }
+    (void)blocked;
 #undef BT_Q
 }
 
@@ -1256,10 +1468,11 @@ template <int S, class Job>
 __global__ __launch_bounds__(kBlock, kDecompressOcc) void decompress_kernel(const Job job, char *ws) {
     using G = Geo<S>;
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * G::LDS_WAVE];
+    __shared__ ScanShared s_scan;
     if (workspace_failed(ws)) return;
     const uint32_t n_slots = job.slots();
     if (blockIdx.x == 0) {
-        if (threadIdx.x < kWaveSize) scan_counts(ws, job);
+        scan_counts(ws, job, s_scan);
         return;
     }
     const int tid = threadIdx.x;
@@ -1430,9 +1643,19 @@ template <class Kernel> uint32_t resident_workgroups(Kernel kernel) {
     }
     int per_unit = 0, units = 0;
     uint32_t total = 2;                                  // the scanner and one worker always fit
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_unit, kernel, kBlock, 0) == hipSuccess &&
+    // the runtime's figure, and not more than the LDS of a compute unit (160 KiB) holds when a workgroup's share is
+    // rounded up generously (the runtime has been seen to count a workgroup's LDS without its allocation granule)
+    hipFuncAttributes attr;
+    int lds_limit = 1 << 20;
+    if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(kernel)) == hipSuccess && attr.sharedSizeBytes > 0)
+        lds_limit = (int)(163840 / ((attr.sharedSizeBytes + 4095) / 4096 * 4096));
+    else
+        (void)hipGetLastError();
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_unit, kernel, kBlock, 0) == hipSuccess && per_unit > lds_limit)
+        per_unit = lds_limit;
+    if (per_unit > 0 &&
         hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess &&
-        per_unit > 0 && units > 0 && (uint64_t)per_unit * (uint64_t)units >= 2)
+        units > 0 && (uint64_t)per_unit * (uint64_t)units >= 2)
         total = (uint32_t)((uint64_t)per_unit * (uint64_t)units);
     else
         (void)hipGetLastError();
@@ -1443,7 +1666,10 @@ template <class Kernel> uint32_t resident_workgroups(Kernel kernel) {
 // Grid of a persistent launch over `slots` slots: the scanner plus as many workers as are resident, but no
 // worker without a slot.
 template <class Kernel> dim3 persistent_grid(Kernel kernel, uint64_t slots) {
-    const uint64_t room = resident_workgroups(kernel) - 1;
+    uint64_t room = resident_workgroups(kernel) - 1;
+#ifdef BT_EXPERIMENT
+    if (const char *e = getenv("BT_WORKERS")) { const uint64_t w = strtoull(e, nullptr, 10); if (w >= 1 && w < room) room = w; }
+#endif
     return dim3((unsigned)((slots < room ? slots : room) + 1));
 }
 
@@ -1465,9 +1691,9 @@ uint64_t batch_slots_for(uint64_t n, int s) {
 }
 
 size_t workspace_bytes_for_slots(uint64_t slots) {
-    uint64_t records = (slots + kTilesPerRecord - 1) / kTilesPerRecord;
-    if (records == 0) records = 1;
-    return kHeaderBytes + (size_t)records * kRecordBytes;
+    uint64_t blocks = (slots + kSlotsPerBlock - 1) / kSlotsPerBlock;
+    if (blocks == 0) blocks = 1;
+    return kHeaderBytes + (size_t)blocks * kBlockBytes;
 }
 
 // Tensors [first, first + count) of a batch, laid end to end.  `n_of(i)` is tensor i's element count.

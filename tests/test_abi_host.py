@@ -128,11 +128,13 @@ def test_batch_workspace_bytes_and_host_errors(bt):
 
     def expect(ns, code):
         # every tensor takes its tiles rounded up to whole rows of 64 slots (at least one row);
-        # 24 bytes per slot in records of 32 slots, plus the 256-byte header; launches of 64 tensors
-        need = 256 + 768
-        for first in range(0, len(ns), 64):
-            slots = sum(max(1, -(-(-(-n // tile[code])) // 64)) * 64 for n in ns[first:first + 64])
-            need = max(need, 256 + 768 * -(-slots // 32))
+        # 24 bytes per slot in blocks of 256 slots, plus the 256-byte header; the largest launch decides,
+        # whether the batch is cut into launches of 52 tensors (compression) or of 64 (restoration)
+        need = 256 + 6144
+        for per_launch in (52, 64):
+            for first in range(0, len(ns), per_launch):
+                slots = sum(max(1, -(-(-(-n // tile[code])) // 64)) * 64 for n in ns[first:first + per_launch])
+                need = max(need, 256 + 6144 * -(-slots // 256))
         return need
 
     for code in (f32, f16):
@@ -298,9 +300,9 @@ def test_bench_refuses_more_than_one_gpu():
 
 
 def test_workspace_bytes_cover_every_tile(bt):
-    # 256-byte header + one 768-byte record per 32 tiles of 32 KiB of dense data
+    # 256-byte header + one 6 KiB block per 256 tiles of 32 KiB of dense data
     for code, elems_per_tile in ((bt.BT_F32, 8192), (bt.BT_F16, 16384), (bt.BT_BF16, 16384), (bt.BT_F64, 4096)):
-        for tiles in (1, 32, 33, 3136, 100000):
+        for tiles in (1, 255, 256, 257, 3136, 100000):
             n = tiles * elems_per_tile
-            assert bt.bt_workspace_bytes(n, code) == 256 + 768 * ((tiles + 31) // 32)
-            assert bt.bt_workspace_bytes(n + 1, code) == 256 + 768 * ((tiles + 1 + 31) // 32)
+            assert bt.bt_workspace_bytes(n, code) == 256 + 6144 * ((tiles + 255) // 256)
+            assert bt.bt_workspace_bytes(n + 1, code) == 256 + 6144 * ((tiles + 1 + 255) // 256)
