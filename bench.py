@@ -104,14 +104,15 @@ def timeline(bt, wl, torch, dev, sets):
         torch.cuda.synchronize()
         bench_aids.bt_timeline_set(None, 0, 0)
         a = buf.cpu().numpy()
+        slots = tiles
         t = a[:8 * tiles].reshape(tiles, 8)
         stamped = t[:, :4][t[:, :4] != 0]
         t0 = int(stamped.min())
         us = lambda v: (np.asarray(v, dtype=np.int64) - t0) / 100.0
         print("## %s\n" % name)
         print("| tile | asked | counted | prefix | issued |\n|---|---|---|---|---|")
-        for k in sorted(set(list(range(0, tiles, max(1, tiles // 16))) + [1022, 1023, 2046, 2047, tiles - 1])):
-            if k < tiles:
+        for k in sorted(set(list(range(0, slots, max(1, slots // 16))) + [1022, 1023, 2046, 2047, slots - 1])):
+            if k < slots:
                 r = t[k]
                 print("| %d | %.2f | %.2f | %.2f | %.2f |" % (k, us(r[0]), us(r[1]), us(r[2]), us(r[3])))
         print("\nLast of all tiles: asked %.2f, counted %.2f, prefix %.2f, issued %.2f.\n"
@@ -122,6 +123,10 @@ def timeline(bt, wl, torch, dev, sets):
             print("| %.0f | %d | %d | %d | %d |" % (g, ((t[:, 0] != 0) & (us(t[:, 0]) <= g)).sum(), ((t[:, 1] != 0) & (us(t[:, 1]) <= g)).sum(),
                                                  ((t[:, 2] != 0) & (us(t[:, 2]) <= g)).sum(), ((t[:, 3] != 0) & (us(t[:, 3]) <= g)).sum()))
         if name == "bt_compress":
+            ok = (t[:, 4] != 0) & (t[:, 7] != 0)
+            d = lambda a, b: np.median((t[ok, a] - t[ok, b]) / 100.0)
+            print("\nMedian over tiles (first wave of each workgroup), µs: asked → arrived %.2f, arrived → counted %.2f, counted → end of "
+                  "the tile's turn %.2f, counted → prefix seen %.2f." % (d(4, 0), d(1, 4), d(7, 1), d(2, 1)))
             print("\nWaits of the first wave of a workgroup for room in its ring (recorded with the workgroup's last tile): "
                   "%d workgroups, %d waits, at most %d per workgroup." % ((t[:, 6] != 0).sum() + 0, t[:, 6].sum(), t[:, 6].max()))
         p = a[8 * tiles:].reshape(max_passes, 2)

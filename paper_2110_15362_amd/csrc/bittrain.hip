@@ -54,7 +54,7 @@ constexpr int kReluRows = BT_RELU_ROWS;   // 16-byte vectors per lane in the ReL
 #define BT_COMPRESS_OCC 3
 #endif
 #ifndef BT_DECOMPRESS_OCC
-#define BT_DECOMPRESS_OCC 6
+#define BT_DECOMPRESS_OCC 8
 #endif
 constexpr int kCompressOcc = BT_COMPRESS_OCC;
 constexpr int kDecompressOcc = BT_DECOMPRESS_OCC;
@@ -63,23 +63,13 @@ constexpr int kDecompressOcc = BT_DECOMPRESS_OCC;
 #define BT_RING_BYTES 12288
 #endif
 constexpr int kRingBytes = BT_RING_BYTES;
-// Tiles a compressing wave has on their way at a time (1 or 2), and the pace at which the workgroups of a launch
-// ask for their first tile (nanoseconds per workgroup; 0: all at once).
+// Tiles a compressing wave has on their way at a time (1 or 2).
 #ifndef BT_TILES_AHEAD
 #define BT_TILES_AHEAD 2
 #endif
-#ifndef BT_PACE_NS
-#define BT_PACE_NS 0
-#endif
 constexpr int kTilesAhead = BT_TILES_AHEAD;
-constexpr int kPaceNs = BT_PACE_NS;
 constexpr int kRingStride = kRingBytes + kWaveSize * 8;   // + a place per lane that takes the writes of dropped elements
 constexpr int kQueue = 16;                            // parked phases per wave, at most
-// Tiles ahead of the one it restores for which a restoring workgroup has published its counts.
-#ifndef BT_COUNT_AHEAD
-#define BT_COUNT_AHEAD 4
-#endif
-constexpr int kCountAhead = BT_COUNT_AHEAD;
 
 // ---- workspace layout -----------------------------------------------------------------
 // Header (uint32 words), then one 6 KiB block per 256 slots.
@@ -99,6 +89,7 @@ constexpr size_t kHdrSpare = 128;      // bytes [128, 256) of the header take st
 constexpr int kSlotsPerBlock = 256;
 constexpr size_t kBlockBytes = 6144;
 constexpr uint32_t kSpinLimit = 1u << 20; // polls before a wait is given up
+constexpr uint32_t kPatience = 1u << 12;  // polls before a restoring wave counts the bitmap itself instead of waiting on
 #ifndef BT_SCANNER_SLEEP
 #define BT_SCANNER_SLEEP 1
 #endif
@@ -492,17 +483,20 @@ static_assert(sizeof(DecompressMany) <= 3840, "kernel arguments of a batched res
 #ifdef BT_TIMELINE
 __device__ uint64_t *g_timeline = nullptr;
 __device__ uint32_t g_timeline_tiles = 0, g_timeline_passes = 0;
+// read the recording state once per kernel: a stamp must not cost a memory round trip of its own
+#define BT_TL_INIT uint64_t *const tl_buf = g_timeline; const uint32_t tl_tiles = g_timeline_tiles; (void)tl_buf; (void)tl_tiles
 #define BT_TL(slot, k)                                                                            \
     do {                                                                                          \
-        if (threadIdx.x == 0 && g_timeline != nullptr && (slot) < g_timeline_tiles)               \
-            g_timeline[8 * (size_t)(slot) + (k)] = wall_clock64();                                \
+        if (threadIdx.x == 0 && tl_buf != nullptr && (slot) < tl_tiles)                           \
+            tl_buf[8 * (size_t)(slot) + (k)] = wall_clock64();                                    \
     } while (0)
 #define BT_TL_VALUE(slot, k, v)                                                                   \
     do {                                                                                          \
-        if (threadIdx.x == 0 && g_timeline != nullptr && (slot) < g_timeline_tiles)               \
-            g_timeline[8 * (size_t)(slot) + (k)] = (v);                                           \
+        if (threadIdx.x == 0 && tl_buf != nullptr && (slot) < tl_tiles)                           \
+            tl_buf[8 * (size_t)(slot) + (k)] = (v);                                               \
     } while (0)
 #else
+#define BT_TL_INIT do {} while (0)
 #define BT_TL(slot, k) do {} while (0)
 #define BT_TL_VALUE(slot, k, v) do {} while (0)
 #endif
@@ -724,6 +718,14 @@ template <class Job> __device__ __forceinline__ void scan_counts(char *ws, const
                 const uint32_t r = lane >> 4;
                 base[j] = r == 0 ? row_base[0] : r == 1 ? row_base[1] : r == 2 ? row_base[2] : row_base[3];
             }
+            // The window is finished: hand the sums over to the wave that has the next one, at once (what follows in
+            // this pass -- asking again, storing the prefixes -- is none of its business).
+            if (new_frontier == window_end && new_frontier != frontier && lane == 0) {
+                sh.running[wave] = running;
+                sh.item[wave] = item;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");   // LDS only: no wait for global memory
+                __hip_atomic_store(&sh.done[wave], window + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
             if (new_frontier == frontier) {
                 if (spin_expired<kScannerSleep>(hdr, spins, limit)) return;
             }
@@ -753,19 +755,96 @@ template <class Job> __device__ __forceinline__ void scan_counts(char *ws, const
             for (int j = 0; j < kScanGroups; ++j) c[j] = c_next[j];
             frontier = new_frontier;
         }
-        // the window is finished: hand the sums over to the wave that has the next one
-        if (lane == 0) {
-            sh.running[wave] = running;
-            sh.item[wave] = item;
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");   // LDS only: the prefix stores are not waited for
-            __hip_atomic_store(&sh.done[wave], window + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        }
         if (window + 1 == n_windows && lane == 0) {
             // every workgroup of the launch has at least one slot and has published its count by now, hence has
             // read the header: advance it
             __hip_atomic_store(&hdr[kHdrPrevTiles], n_slots, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(&hdr[kHdrSeq], seq + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
+    }
+}
+
+// The scanner of a restoration: one wave.  There the workgroups come and go (one per tile, see
+// decompress_kernel) and a count is published as soon as its workgroup has been started, so the counts
+// arrive in index order at the pace at which tiles finish; one wave that takes kRowScan rows of 64
+// counts starting at the frontier's row in every pass, consumes the leading run of published ones and
+// asks again keeps up with that and has nothing to hand over to anybody.  (All rows are looked at
+// before anything is written: a load waited for after a store would also wait for that store.)
+constexpr int kRowScan = 7;
+template <class Job> __device__ __forceinline__ void scan_counts_rows(char *ws, const Job &job) {
+    const uint32_t lane = threadIdx.x & (kWaveSize - 1);
+    uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
+    const uint32_t seq = hdr[kHdrSeq];
+    const uint32_t cur = seq & 1u;
+    const uint32_t n_items = job.count();
+    const uint32_t n_slots = job.slots();
+    uint32_t frontier = 0;     // slots [0, frontier) are done
+    uint32_t item = 0;         // tensor that slot `frontier` belongs to
+    uint64_t running = 0;      // stored values of tensor `item` in its tiles before `frontier`
+    uint32_t spins = 0;
+    const uint32_t limit = wait_limit(hdr);
+#ifdef BT_TIMELINE
+    uint64_t *const timeline = g_timeline;      // read once: a load in the loop would join the scanner's waits
+    uint32_t timeline_pass = 0;
+#endif
+    while (frontier < n_slots) {
+        const uint32_t w0 = frontier & ~63u;
+        uint32_t c[kRowScan];
+#pragma unroll
+        for (int j = 0; j < kRowScan; ++j) {
+            const uint32_t t = w0 + 64u * j + lane;
+            c[j] = 0;
+            if (t < n_slots)
+                c[j] = __hip_atomic_load(reinterpret_cast<const uint32_t *>(ws_count(ws, t, cur)), __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+        }
+        uint64_t usable_lanes[kRowScan];
+#pragma unroll
+        for (int j = 0; j < kRowScan; ++j) {
+            const uint32_t t = w0 + 64u * j + lane;
+            usable_lanes[j] = __ballot(t < frontier || (t < n_slots && c[j] != 0));   // done before, or published
+        }
+        // rows are consumed in order while every slot of the row is usable
+        bool open = true;
+        uint32_t new_frontier = frontier;
+#pragma unroll
+        for (int j = 0; j < kRowScan; ++j) {
+            const uint32_t row0 = w0 + 64u * j;
+            const uint32_t t = row0 + lane;
+            if (open && row0 < n_slots) {
+                const uint64_t bad = ~usable_lanes[j];                             // lanes that stop the run
+                const uint32_t run = bad == 0 ? 64u : (uint32_t)__ffsll((unsigned long long)bad) - 1u;
+                const uint32_t row_end = row0 + run;                               // slots [row0, row_end) usable
+                if (row_end > new_frontier) {
+                    while (item + 1 < n_items && row0 >= job.start(item + 1)) ++item;
+                    if (row0 == job.start(item) && new_frontier <= row0) running = 0;   // a new tensor begins
+                    const bool fresh = t >= frontier && t < row_end;
+                    const uint32_t mine = fresh ? c[j] - 1u : 0u;
+                    const uint32_t incl = wave_inclusive_sum(mine);
+                    if (fresh) ws_store64(ws_prefix(ws, t, cur), running + (incl - mine) + 1);
+                    running += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+                    new_frontier = row_end;
+                }
+                open = run == 64u;
+            }
+        }
+        if (new_frontier == frontier) {
+            if (spin_expired<kScannerSleep>(hdr, spins, limit)) return;
+            continue;
+        }
+#ifdef BT_TIMELINE
+        if (timeline != nullptr && lane == 0 && timeline_pass < g_timeline_passes) {
+            timeline[8 * (size_t)g_timeline_tiles + 2 * timeline_pass] = wall_clock64();
+            timeline[8 * (size_t)g_timeline_tiles + 2 * timeline_pass + 1] = ((uint64_t)frontier << 32) | new_frontier;
+            ++timeline_pass;
+        }
+#endif
+        frontier = new_frontier;
+    }
+    if (lane == 0) {
+        // every slot's workgroup has published its count by now, hence has read the header: advance it
+        __hip_atomic_store(&hdr[kHdrPrevTiles], n_slots, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&hdr[kHdrSeq], seq + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -791,9 +870,10 @@ __device__ __forceinline__ Epoch read_epoch(const char *ws) {
 
 // Zero what the previous call left in the other copy of the workspace entries: slots
 // [0, prev_slots), shared out over the threads of this call's `workers` workgroups.
-__device__ __forceinline__ void zero_previous(char *ws, const Epoch ep, const uint32_t worker, const uint32_t workers) {
+__device__ __forceinline__ void zero_previous(char *ws, const Epoch ep, const uint32_t worker, const uint32_t workers,
+                                              const uint32_t block = kBlock) {
     const uint32_t other = ep.cur ^ 1u;
-    for (uint64_t i = (uint64_t)worker * kBlock + threadIdx.x; i < ep.prev_slots; i += (uint64_t)workers * kBlock) {
+    for (uint64_t i = (uint64_t)worker * block + threadIdx.x; i < ep.prev_slots; i += (uint64_t)workers * block) {
         ws_store32(ws_count(ws, (uint32_t)i, other), 0);
         ws_store64(ws_prefix(ws, (uint32_t)i, other), 0);
     }
@@ -876,20 +956,12 @@ __device__ __forceinline__ void ring_flush(const unsigned char *data, char *g0_p
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t v = 1u + (uint32_t)lane + (uint32_t)kWaveSize * i;
-#ifdef BT_EXP_FLUSH_B128
-        if (v + 1 < n_vec) t[i] = *reinterpret_cast<const uint4 *>(data + (size_t)v * kVecBytes);
-#else
         if (v + 1 < n_vec) t[i] = lds_read16<S>(src + (size_t)v * kVecBytes, odd_half);
-#endif
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t v = 1u + (uint32_t)lane + (uint32_t)kWaveSize * i;
-#ifdef BT_EXP_NO_FLUSH_STORE
-        if (v + 1 < n_vec && t[i].x == 0x12345678u && t[i].y == 0x9abcdef1u) stream_store<kCompressNtStore>(reinterpret_cast<uint4 *>(gvec + (size_t)v * kVecBytes), t[i]);
-#else
         if (v + 1 < n_vec) stream_store<kCompressNtStore>(reinterpret_cast<uint4 *>(gvec + (size_t)v * kVecBytes), t[i]);
-#endif
     }
     // the first and the last vector, an element a lane: lane j < E element j of the first, lane E + j element j
     // of the last, each only if it lies inside [pad, pad + cnt)
@@ -929,6 +1001,7 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
         if (!workspace_failed(ws)) scan_counts(ws, job, s_scan);
         return;
     }
+    BT_TL_INIT;
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in a scalar register
@@ -961,12 +1034,6 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
 #pragma unroll
         for (int k = 0; k < kRows; ++k) x[k] = stream_load<kCompressNtLoad>(p + k * row_stride);
     };
-    if (kPaceNs != 0) {
-        // the first tiles are asked for in index order, at about the pace at which memory serves them: asked for all at
-        // once they would all arrive together, at the end of the burst, and the scan could not start before that
-        const uint64_t until = wall_clock64() + (uint64_t)worker * kPaceNs / 10;     // the clock ticks every 10 ns
-        while ((uint64_t)wall_clock64() < until) __builtin_amdgcn_s_sleep(1);
-    }
     ask_tile(xa, worker);
 
     if (workspace_failed(ws)) return;
@@ -1070,6 +1137,7 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
         // The tile has arrived and its elements have been looked at: ask for the next one now, into the other
         // buffer (this one is needed until the tile's values are parked), and behind it for the prefix of the oldest
         // parked tile; what the previous turn asked about has come back with this tile's elements.
+        BT_TL(slot, 4);
         const bool answered = polling;
         const uint32_t answered_slot = polled_slot;
         const uint64_t answer = polled;
@@ -1168,7 +1236,6 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
                 // instead of a branch around the write keeps the execution mask alone
                 const int data_rel = (int)(start + kVecBytes) - kRingBytes - lane * S;   // of the entry's first value, from this lane's spare place
                 uint32_t row_start = 0;
-#ifndef BT_EXP_NO_COMPACT
 #pragma unroll
                 for (int k = r0; k < r0 + kPhaseRows; ++k) {
                     int rb = data_rel + (int)(row_start + BT_FIELD(rank2, k)) * S;
@@ -1198,7 +1265,6 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
                     }
                     row_start += BT_FIELD(total2, k);
                 }
-#endif
             }
             wave_lds_sync();             // the values are in the ring before anything reads them
         }
@@ -1230,6 +1296,7 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
                 else store_vec_guarded<S>(dense, e0, n, o);
             }
         }
+        BT_TL(slot, 7);
         // the tile after next takes this buffer: its loads are the last memory operations of the turn
         if (kTilesAhead == 1) ask_tile(x_next, (uint64_t)slot + workers);   // one buffer: the next tile can only be asked for now
         ask_prefix();
@@ -1321,102 +1388,170 @@ __device__ __forceinline__ void strip_commit(unsigned char *strip, const uint32_
     }
 }
 
-// The set bits of a whole tile, counted by one wave: lane l counts LANE_WORDS consecutive
-// words, so the 16 lanes [16 v, 16 v + 16) hold the words of the tile's v-th wave.  Returns
-// the tile's total, and in `before` the set bits of the waves before `wave`.  Words at or
-// beyond n_words count as 0 and so do bits at or beyond n (Algorithm 2 visits n bits).
+// Restoration of one wave's quarter of a tile goes in three steps, so that a wave can have the
+// steps of consecutive tiles overlap:
+//   ahead_load      asks for the bitmap words the wave needs (always the same number of loads,
+//                   from somewhere harmless if there is no such tile);
+//   restore_fetch   turns them into the lane's masks and ranks (Algorithm 2's counter j inside the
+//                   tile) and, given j at the start of the tile, asks for the wave's values;
+//   restore_store   puts the values into the LDS strip, expands them by rank (a value where
+//                   the bit is set, +0 where it is clear) and stores the dense quarter tile.
+// The waves of a workgroup do not talk to each other: each counts what the waves before it hold
+// from the bitmap itself.
+template <int S> struct Ahead {
+    uint32_t rows[kRows];                      // the bitmap word that holds this lane's bits of row k
+    uint32_t mine[Geo<S>::LANE_WORDS];         // this lane's share of the tile's words (lane l: words l * LANE_WORDS ...)
+};
+
+// `bitmap` == nullptr: there is no tile; everything is read from `harmless` (4-byte aligned, readable).
 template <int S>
-__device__ __forceinline__ uint32_t count_tile(const uint32_t *__restrict__ bitmap, const uint64_t n, const uint32_t tile,
-                                               const int lane, const int wave, uint32_t &before) {
+__device__ __forceinline__ void rows_load(const uint32_t *bitmap, const uint64_t n, const uint32_t tile, const int lane,
+                                          const int wave, const uint32_t *harmless, uint32_t (&rows)[kRows]) {
+    using G = Geo<S>;
+    const bool real = bitmap != nullptr;
+    const uint32_t *const base = real ? bitmap : harmless;
+    const uint64_t last = real ? ((n + 31) >> 5) - 1 : 0;         // a real tile has n >= 1
+    const uint64_t row_w0 = (real ? (uint64_t)tile * G::TILE_WORDS : 0) + (uint64_t)wave * (G::TILE_WORDS / kWaves) + (uint32_t)(lane / G::G);
+#pragma unroll
+    for (int k = 0; k < kRows; ++k) {
+        const uint64_t wi = row_w0 + (uint64_t)k * G::WPR;
+        rows[k] = base[wi < last ? wi : last];
+    }
+}
+
+template <int S>
+__device__ __forceinline__ void words_load(const uint32_t *bitmap, const uint64_t n, const uint32_t tile, const int lane,
+                                           const uint32_t *harmless, uint32_t (&words)[Geo<S>::LANE_WORDS]) {
+    using G = Geo<S>;
+    const bool real = bitmap != nullptr;
+    const uint32_t *const base = real ? bitmap : harmless;
+    const uint64_t last = real ? ((n + 31) >> 5) - 1 : 0;
+    const uint64_t w0 = real ? (uint64_t)tile * G::TILE_WORDS + (uint64_t)lane * G::LANE_WORDS : 0;
+#pragma unroll
+    for (int j = 0; j < G::LANE_WORDS; ++j) words[j] = base[w0 + j < last ? w0 + j : last];
+}
+
+template <int S>
+__device__ __forceinline__ void ahead_load(const uint32_t *bitmap, const uint64_t n, const uint32_t tile, const int lane,
+                                           const int wave, const uint32_t *harmless, Ahead<S> &a) {
+    rows_load<S>(bitmap, n, tile, lane, wave, harmless, a.rows);
+    words_load<S>(bitmap, n, tile, lane, harmless, a.mine);
+}
+
+// The set bits of a whole tile from the words words_load has brought, as a running sum over the lanes: lane l
+// holds LANE_WORDS consecutive words, so the 16 lanes [16 v, 16 v + 16) hold the words of the tile's v-th wave,
+// lane 63 ends up with the tile's total and lane 16 v - 1 with the set bits of the waves before v.  Words at or
+// beyond the bitmap's end count as 0 and so do bits at or beyond n (Algorithm 2 visits n bits).
+template <int S>
+__device__ __forceinline__ uint32_t tile_inclusive(const uint32_t (&words)[Geo<S>::LANE_WORDS], const uint64_t n, const uint32_t tile,
+                                                   const int lane) {
     using G = Geo<S>;
     const uint64_t n_words = (n + 31) >> 5;
     const uint64_t w0 = (uint64_t)tile * G::TILE_WORDS + (uint64_t)lane * G::LANE_WORDS;
     const bool full = (uint64_t)(tile + 1) * G::TILE <= n;
     uint32_t mine = 0;
-    if (full) {
 #pragma unroll
-        for (int j = 0; j < G::LANE_WORDS; ++j) mine += (uint32_t)__popc(bitmap[w0 + j]);
-    } else {
-#pragma unroll
-        for (int j = 0; j < G::LANE_WORDS; ++j) {
+    for (int j = 0; j < G::LANE_WORDS; ++j) {
+        uint32_t word = words[j];
+        if (!full) {
             const uint64_t wi = w0 + j;
-            uint32_t word = wi < n_words ? bitmap[wi] : 0u;
+            if (wi >= n_words) word = 0;
             if (wi + 1 == n_words && (n & 31) != 0) word &= (1u << (uint32_t)(n & 31)) - 1u;
-            mine += (uint32_t)__popc(word);
         }
+        mine += (uint32_t)__popc(word);
     }
-    const uint32_t incl = wave_inclusive_sum(mine);
+    return wave_inclusive_sum(mine);
+}
+
+// Returns the tile's total, and in `before` the set bits of the waves before `wave`.
+template <int S>
+__device__ __forceinline__ uint32_t count_words(const uint32_t (&words)[Geo<S>::LANE_WORDS], const uint64_t n, const uint32_t tile,
+                                                const int lane, const int wave, uint32_t &before) {
+    const uint32_t incl = tile_inclusive<S>(words, n, tile, lane);
     before = wave == 0 ? 0u : (uint32_t)__builtin_amdgcn_readlane((int)incl, (int)uniform32(16u * (uint32_t)wave - 1u));
     return (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
 }
 
-// One wave's quarter of one tile, given Algorithm 2's counter j at the start of the tile.
-// The waves of a workgroup do not talk to each other: each counts what the waves before it
-// hold from the bitmap itself (count_tile).
+// The same straight from memory (one wave counts one tile).
 template <int S>
-__device__ __forceinline__ void decompress_wave(const uint32_t *__restrict__ bitmap, const void *__restrict__ values,
-                                                const uint64_t values_cap, const uint64_t n, void *__restrict__ out,
-                                                const uint32_t tile, const uint64_t tile_j, const uint32_t before_wave,
-                                                unsigned char *strip, const int lane, const int wave) {
+__device__ __forceinline__ uint32_t count_tile(const uint32_t *__restrict__ bitmap, const uint64_t n, const uint32_t tile,
+                                               const int lane, const int wave, uint32_t &before) {
+    using G = Geo<S>;
+    const uint64_t last = ((n + 31) >> 5) - 1;
+    uint32_t words[G::LANE_WORDS];
+#pragma unroll
+    for (int j = 0; j < G::LANE_WORDS; ++j) {
+        const uint64_t wi = (uint64_t)tile * G::TILE_WORDS + (uint64_t)lane * G::LANE_WORDS + j;
+        words[j] = bitmap[wi < last ? wi : last];
+    }
+    return count_words<S>(words, n, tile, lane, wave, before);
+}
+
+template <int S> struct Restoring {            // a quarter tile between restore_fetch and restore_store
+    uint32_t mp[Geo<S>::MW], rank2[kRows / 2], total2[kRows / 2];
+    Fetched<S> fetched[kRows / kPhaseRows];
+    uint32_t pads[kRows / kPhaseRows], cnts[kRows / kPhaseRows];
+};
+
+template <int S>
+__device__ __forceinline__ void restore_fetch(const uint32_t (&rows)[kRows], const void *__restrict__ values, const uint64_t values_cap,
+                                              const uint64_t n, const uint32_t tile, const uint64_t tile_j,
+                                              const uint32_t before_wave, const int lane, const int wave, Restoring<S> &r) {
     using G = Geo<S>;
     constexpr int E = G::E;
     const uint64_t n_words = (n + 31) >> 5;
     const uint64_t wave_e0 = (uint64_t)tile * G::TILE + (uint64_t)wave * G::WAVE;
-
-    // (1) this lane's bits of the bitmap, and Algorithm 2's counter j as ranks
-    uint32_t mp[G::MW], rank2[kRows / 2], total2[kRows / 2];
-#pragma unroll
-    for (int i = 0; i < G::MW; ++i) mp[i] = 0;
     const bool full = (uint64_t)(tile + 1) * G::TILE <= n;
-    if (full) {
-        // every word of the tile exists and every bit of it counts: G lanes read the same word and take E bits each
-        const uint32_t *p = bitmap + (wave_e0 >> 5) + (uint32_t)(lane / G::G);
-        const uint32_t shift = (uint32_t)(lane % G::G) * E;
+    // (1) this lane's bits of the bitmap (G lanes read the same word and take E bits each), and Algorithm 2's
+    //     counter j as ranks
 #pragma unroll
-        for (int k = 0; k < kRows; ++k)
-            mp[k / G::RPM] |= ((p[k * G::WPR] >> shift) & ((1u << E) - 1u)) << (E * (k % G::RPM));
-    } else {
+    for (int i = 0; i < G::MW; ++i) r.mp[i] = 0;
 #pragma unroll
-        for (int k = 0; k < kRows; ++k)
-            mp[k / G::RPM] |= bitmap_bits<S>(bitmap, wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E, n, n_words)
-                              << (E * (k % G::RPM));
+    for (int k = 0; k < kRows; ++k) {
+        const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
+        uint32_t m = (rows[k] >> (uint32_t)(e0 & 31)) & ((1u << E) - 1u);
+        if (!full) {                       // words beyond the bitmap read as 0, bits at or beyond n are cleared
+            if ((e0 >> 5) >= n_words) m = 0;
+            if (e0 + E > n) m &= (e0 < n) ? ((1u << (uint32_t)(n - e0)) - 1u) : 0u;
+        }
+        r.mp[k / G::RPM] |= m << (E * (k % G::RPM));
     }
-    rank_rows<S>(mp, rank2, total2);
-
-    // (2) Ask for the values of every phase (kPhaseRows rows each) first, so that all of
-    //     them are in flight together; then, phase by phase, put them into the LDS strip
-    //     and expand from LDS by rank: a value where the bit is set, +0 where it is clear,
-    //     16 bytes per lane per store.  No load is issued after the first store: loads and
-    //     stores share one completion counter, and a load waited for after a store would
-    //     also wait for that store to reach memory.
+    rank_rows<S>(r.mp, r.rank2, r.total2);
+    // (2) ask for the values of every phase (kPhaseRows rows each), so that all of them are in flight together
     uint64_t g0 = tile_j + before_wave;                                   // Algorithm 2's j for this wave
-    constexpr int kPhases = kRows / kPhaseRows;
-    Fetched<S> fetched[kPhases];
-    uint32_t pads[kPhases], cnts[kPhases];
 #pragma unroll
-    for (int ph = 0; ph < kPhases; ++ph) {
-        cnts[ph] = 0;
+    for (int ph = 0; ph < kRows / kPhaseRows; ++ph) {
+        r.cnts[ph] = 0;
 #pragma unroll
-        for (int k = ph * kPhaseRows; k < (ph + 1) * kPhaseRows; ++k) cnts[ph] += BT_FIELD(total2, k);
+        for (int k = ph * kPhaseRows; k < (ph + 1) * kPhaseRows; ++k) r.cnts[ph] += BT_FIELD(r.total2, k);
         const char *gsrc = static_cast<const char *>(values) + g0 * S;
-        pads[ph] = (uint32_t)(reinterpret_cast<uintptr_t>(gsrc) & (kVecBytes - 1)) / S;
-        const uint32_t phase_total = cnts[ph];
+        r.pads[ph] = (uint32_t)(reinterpret_cast<uintptr_t>(gsrc) & (kVecBytes - 1)) / S;
+        const uint32_t phase_total = r.cnts[ph];
         // nothing at or beyond the capacity is read (an index that does not belong to the bitmap, a wait that ran out)
-        if (g0 >= values_cap) cnts[ph] = 0;
-        else if (values_cap - g0 < cnts[ph]) cnts[ph] = (uint32_t)(values_cap - g0);
-        strip_fetch<S>(gsrc, pads[ph], cnts[ph], lane, fetched[ph]);
+        if (g0 >= values_cap) r.cnts[ph] = 0;
+        else if (values_cap - g0 < r.cnts[ph]) r.cnts[ph] = (uint32_t)(values_cap - g0);
+        strip_fetch<S>(gsrc, r.pads[ph], r.cnts[ph], lane, r.fetched[ph]);
         g0 += phase_total;
     }
+}
+
+template <int S>
+__device__ __forceinline__ void restore_store(const Restoring<S> &r, const uint64_t n, void *__restrict__ out, const uint32_t tile,
+                                              unsigned char *strip, const int lane, const int wave) {
+    using G = Geo<S>;
+    constexpr int E = G::E;
+    const uint64_t wave_e0 = (uint64_t)tile * G::TILE + (uint64_t)wave * G::WAVE;
+    const bool full = (uint64_t)(tile + 1) * G::TILE <= n;
 #pragma unroll
-    for (int ph = 0; ph < kPhases; ++ph) {
+    for (int ph = 0; ph < kRows / kPhaseRows; ++ph) {
         if (ph != 0) wave_lds_sync();   // the previous phase's reads are done before the strip is reused
-        strip_commit<S>(strip, pads[ph], cnts[ph], lane, fetched[ph]);
+        strip_commit<S>(strip, r.pads[ph], r.cnts[ph], lane, r.fetched[ph]);
         wave_lds_sync();
-        uint32_t row_start = pads[ph];
+        uint32_t row_start = r.pads[ph];
 #pragma unroll
         for (int k = ph * kPhaseRows; k < (ph + 1) * kPhaseRows; ++k) {
-            uint32_t r = row_start + BT_FIELD(rank2, k);
-            const uint32_t mk = BT_MASK(S, mp, k);
+            uint32_t at = row_start + BT_FIELD(r.rank2, k);
+            const uint32_t mk = BT_MASK(S, r.mp, k);
             uint32_t d[4] = {0, 0, 0, 0};
             // every lane reads at its running rank whether the bit is set or not (the index stays inside the strip)
             // and a select drops what a cleared bit read
@@ -1425,97 +1560,130 @@ __device__ __forceinline__ void decompress_wave(const uint32_t *__restrict__ bit
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     const uint32_t keep = (mk >> j) & 1u;
-                    const uint64_t v = l[r];
+                    const uint64_t v = l[at];
                     d[2 * j] = keep ? (uint32_t)v : 0u;
                     d[2 * j + 1] = keep ? (uint32_t)(v >> 32) : 0u;
-                    r += keep;
+                    at += keep;
                 }
             } else if (S == 4) {
                 const uint32_t *l = reinterpret_cast<const uint32_t *>(strip);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t keep = (mk >> j) & 1u;
-                    const uint32_t v = l[r];
+                    const uint32_t v = l[at];
                     d[j] = keep ? v : 0u;
-                    r += keep;
+                    at += keep;
                 }
             } else {
                 const uint16_t *l = reinterpret_cast<const uint16_t *>(strip);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const uint32_t keep = (mk >> j) & 1u;
-                    const uint32_t v = l[r];
+                    const uint32_t v = l[at];
                     d[j >> 1] |= (keep ? v : 0u) << (16 * (j & 1));
-                    r += keep;
+                    at += keep;
                 }
             }
             const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
             const uint4 o = make_uint4(d[0], d[1], d[2], d[3]);
             if (full) stream_store<kDecompressNtStore>(reinterpret_cast<uint4 *>(static_cast<char *>(out) + e0 * S), o);
             else store_vec_guarded<S>(out, e0, n, o);
-            row_start += BT_FIELD(total2, k);
+            row_start += BT_FIELD(r.total2, k);
         }
     }
     wave_lds_sync();                    // this tile's reads are done before the next tile's values are committed
+    // a ragged tile's stores are element by element, as many as it takes: let them finish here, so that what is
+    // outstanding after a tile does not depend on the tile (see the kernel)
+    if (!full) __builtin_amdgcn_s_waitcnt(0x0f70);                        // vmcnt(0)
 }
 
-// bt_decompress and bt_decompress_batch.  Workgroup 0 is the scanner; workgroup w + 1 restores
-// slots w, w + G, w + 2G, ...  A tile's count depends on the bitmap alone, so a workgroup's first
-// wave publishes the counts of its next kCountAhead tiles before the workgroup restores a tile:
-// the scanner has the time a workgroup spends on kCountAhead tiles to answer, and except at the
-// start of a call a wave finds the prefix of its tile waiting.
+// What a restoring wave does when the scanner's answer for its tile does not come: it counts the set
+// bits of the tensor's bitmap before the tile itself.  Slow (the whole bitmap up to the tile), but it
+// needs nothing from any other workgroup.  Every bit before a tile is a bit of the tensor, so no mask.
+template <int S>
+__device__ __noinline__ uint64_t prefix_from_bitmap(const uint32_t *__restrict__ bitmap, const uint32_t tile, const int lane) {
+    const uint64_t words = (uint64_t)tile * Geo<S>::TILE_WORDS;
+    uint64_t mine = 0;
+    for (uint64_t w = (uint32_t)lane; w < words; w += kWaveSize) mine += (uint32_t)__popc(bitmap[w]);
+#pragma unroll
+    for (int d = 1; d < kWaveSize; d <<= 1) mine += __shfl_xor((unsigned long long)mine, d, kWaveSize);
+    return uniform64(mine);
+}
+
+// bt_decompress and bt_decompress_batch: workgroup 0 is the scanner (one wave of it), workgroup 1 + t
+// restores slot t.  A tile's count depends on the bitmap alone: every wave counts the tile from the
+// bitmap words (so the waves need not talk to each other about it), the workgroup publishes the
+// count, and while the scanner is at work each wave turns its words into masks and ranks; then the
+// first wave waits for the tile's prefix, every wave fetches its values, expands and stores them, and
+// the workgroup ends.
+//
+// Why a workgroup per tile and no loop over tiles as in compression.  A wave that has issued its stores
+// is gone (nothing waits for them to land) and the next workgroup takes its place, whereas a wave that
+// went on to a next tile would, on this hardware, wait for its own stores whenever it waits for that
+// tile's loads (one counter tracks both, in order).  Two thirds of a restoration's traffic are stores;
+// kernels that loop measured 10 to 25 % slower, with or without the next tile's loads in flight.
+//
+// Forward progress does not rest on the order in which workgroups are started.  A workgroup publishes
+// its count before it waits for anything, and one whose prefix has not come after kPatience polls
+// stops waiting and counts the bitmap itself (prefix_from_bitmap): so every workgroup that has been
+// started ends, whatever the others do, and every workgroup is started in the end.
 template <int S, class Job>
 __global__ __launch_bounds__(kBlock, kDecompressOcc) void decompress_kernel(const Job job, char *ws) {
     using G = Geo<S>;
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * G::LDS_WAVE];
-    __shared__ ScanShared s_scan;
+    __shared__ uint64_t s_tile_j;
     if (workspace_failed(ws)) return;
-    const uint32_t n_slots = job.slots();
     if (blockIdx.x == 0) {
-        scan_counts(ws, job, s_scan);
+        if (threadIdx.x < kWaveSize) scan_counts_rows(ws, job);
         return;
     }
+    BT_TL_INIT;
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t worker = blockIdx.x - 1, workers = gridDim.x - 1;
+    const uint32_t slot = blockIdx.x - 1, n_slots = gridDim.x - 1;
     uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
+    const Slot sl = job.at(slot);
+    const uint64_t n = sl.idle ? 0 : job.n(sl.item);
+    const uint32_t *const bitmap = sl.idle ? nullptr : job.bitmap(sl.item);
+    // the bitmap words first: everything else waits for them
+    Ahead<S> ahead;
+    ahead_load<S>(bitmap, n, sl.tile, lane, wave, reinterpret_cast<const uint32_t *>(ws + kHdrSpare), ahead);
+    BT_TL(slot, 0);
     const Epoch ep = read_epoch(ws);
-    const uint32_t cur = ep.cur;
+    const uint32_t cur = uniform32(ep.cur);      // (the wave has the header's words from here on)
+    const uint32_t prev_slots = uniform32(ep.prev_slots);
     const uint32_t limit = wait_limit(hdr);
+    uint32_t before_wave = 0, tile_total = 0;
+    if (!sl.idle) tile_total = count_words<S>(ahead.mine, n, sl.tile, lane, wave, before_wave);
     __syncthreads();                    // every wave has read the header before the first wave publishes anything
-    zero_previous(ws, ep, worker, workers);
-    unsigned char *const strip = s_stage + wave * G::LDS_WAVE;
+    if (tid == 0) ws_store32(ws_count(ws, slot, cur), tile_total + 1);
+    BT_TL(slot, 1);
+    zero_previous(ws, Epoch{cur, prev_slots}, slot, n_slots);
+    if (sl.idle) return;
+    // Algorithm 2's counter j at the start of the tile: the first wave asks (one poller a tile keeps the
+    // traffic on the workspace's few lines low) and passes the answer on through LDS
     uint32_t polls = 0;
-
-    auto publish = [&](const uint64_t slot) {      // first wave only
-        if (slot >= n_slots) return;
-        const Slot sl = job.at((uint32_t)slot);
-        uint32_t count = 0, unused;
-        if (!sl.idle) count = count_tile<S>(job.bitmap(sl.item), job.n(sl.item), sl.tile, lane, 0, unused);
-        if (lane == 0) ws_store32(ws_count(ws, (uint32_t)slot, cur), count + 1);
-        BT_TL((uint32_t)slot, 1);
-    };
     if (wave == 0) {
-#pragma unroll 1
-        for (int a = 0; a < kCountAhead; ++a) publish((uint64_t)worker + (uint64_t)a * workers);
+        const uint32_t patience = limit < kPatience ? limit : kPatience;
+        uint64_t v;
+        for (;;) {
+            v = uniform64(ws_load64(ws_prefix(ws, slot, cur)));
+            ++polls;
+            if (v != 0) { v -= 1; break; }
+            if (polls > patience) { v = prefix_from_bitmap<S>(bitmap, sl.tile, lane); break; }
+            __builtin_amdgcn_s_sleep(kTileSleep);
+        }
+        if (lane == 0) s_tile_j = v;
     }
-    for (uint32_t slot = worker; slot < n_slots; slot += workers) {
-        if (wave == 0) publish((uint64_t)slot + (uint64_t)kCountAhead * workers);
-        const Slot sl = job.at(slot);
-        if (sl.idle) continue;
-        BT_TL(slot, 0);
-        const uint32_t *const bitmap = job.bitmap(sl.item);
-        const uint64_t n = job.n(sl.item);
-        uint32_t before_wave;
-        count_tile<S>(bitmap, n, sl.tile, lane, wave, before_wave);
-        const uint64_t tile_j = wait_prefix(ws, slot, cur, hdr, limit, polls);
-        BT_TL(slot, 2);
-        decompress_wave<S>(bitmap, job.values(sl.item), job.cap(sl.item), n, job.out(sl.item), sl.tile, tile_j, before_wave,
-                           strip, lane, wave);
-        BT_TL(slot, 3);
-        BT_TL_VALUE(slot, 5, polls);
-    }
+    lds_barrier();
+    const uint64_t tile_j = uniform64(s_tile_j);
+    BT_TL(slot, 2);
+    Restoring<S> r;
+    restore_fetch<S>(ahead.rows, job.values(sl.item), job.cap(sl.item), n, sl.tile, tile_j, before_wave, lane, wave, r);
+    restore_store<S>(r, n, job.out(sl.item), sl.tile, s_stage + wave * G::LDS_WAVE, lane, wave);
+    BT_TL(slot, 3);
+    BT_TL_VALUE(slot, 5, polls);
 }
 
 // bt_decompress_indexed and its batched form: one workgroup per slot and nothing else.  Algorithm 2's
@@ -1531,10 +1699,13 @@ __global__ __launch_bounds__(kBlock, 8) void decompress_indexed_kernel(const Job
     const uint64_t tile_j = job.tile_index(sl.item)[sl.tile];             // asked for first, needed last
     const uint32_t *const bitmap = job.bitmap(sl.item);
     const uint64_t n = job.n(sl.item);
+    Ahead<S> ahead;
+    ahead_load<S>(bitmap, n, sl.tile, lane, wave, bitmap, ahead);
     uint32_t before_wave;
-    count_tile<S>(bitmap, n, sl.tile, lane, wave, before_wave);
-    decompress_wave<S>(bitmap, job.values(sl.item), job.cap(sl.item), n, job.out(sl.item), sl.tile, tile_j, before_wave,
-                       s_stage + wave * G::LDS_WAVE, lane, wave);
+    count_words<S>(ahead.mine, n, sl.tile, lane, wave, before_wave);
+    Restoring<S> r;
+    restore_fetch<S>(ahead.rows, job.values(sl.item), job.cap(sl.item), n, sl.tile, tile_j, before_wave, lane, wave, r);
+    restore_store<S>(r, n, job.out(sl.item), sl.tile, s_stage + wave * G::LDS_WAVE, lane, wave);
 }
 
 // ---- ReLU backward from the bitmap -----------------------------------------------------------
@@ -1667,9 +1838,6 @@ template <class Kernel> uint32_t resident_workgroups(Kernel kernel) {
 // worker without a slot.
 template <class Kernel> dim3 persistent_grid(Kernel kernel, uint64_t slots) {
     uint64_t room = resident_workgroups(kernel) - 1;
-#ifdef BT_EXPERIMENT
-    if (const char *e = getenv("BT_WORKERS")) { const uint64_t w = strtoull(e, nullptr, 10); if (w >= 1 && w < room) room = w; }
-#endif
     return dim3((unsigned)((slots < room ? slots : room) + 1));
 }
 
@@ -1770,7 +1938,7 @@ bt_status launch_decompress(const Job &job, uint64_t slots, int s, char *ws, hip
 #define BT_LAUNCH_DECOMPRESS(S_)                                                                \
     do {                                                                                        \
         auto kernel = decompress_kernel<S_, Job>;                                               \
-        kernel<<<persistent_grid(kernel, slots), block, 0, hs>>>(job, ws);                      \
+        kernel<<<dim3((unsigned)(slots + 1)), block, 0, hs>>>(job, ws);                         \
     } while (0)
     if (s == 8) BT_LAUNCH_DECOMPRESS(8);
     else if (s == 4) BT_LAUNCH_DECOMPRESS(4);
