@@ -135,8 +135,8 @@ bt_status bt_workspace_init(void *d_workspace, size_t workspace_bytes, bt_stream
  *               once with bt_workspace_init.  A workspace must not be shared by
  *               two calls that can be in flight at the same time: calls that use
  *               one workspace must be ordered (same stream, or events).
- * Input and outputs must not overlap.  "delete T" of Algorithm 1 is the caller
- * dropping d_in after this call is enqueued.  n == 0 only writes *d_nnz = 0.
+ * Input and outputs must not overlap.  Algorithm 1's last step, giving up the
+ * dense tensor, is the caller dropping d_in after this call is enqueued.  n == 0 only writes *d_nnz = 0.
  * Errors: BT_ERR_NULL, BT_ERR_DTYPE, BT_ERR_ALIGN, BT_ERR_SIZE, BT_ERR_WORKSPACE,
  * BT_ERR_HIP. */
 bt_status bt_compress(const void *d_in, uint64_t n, bt_dtype dtype,

@@ -1816,14 +1816,21 @@ template <class Kernel> uint32_t resident_workgroups(Kernel kernel) {
     uint32_t total = 2;                                  // the scanner and one worker always fit
     // the runtime's figure, and not more than the LDS of a compute unit (160 KiB) holds when a workgroup's share is
     // rounded up generously (the runtime has been seen to count a workgroup's LDS without its allocation granule)
+    // and not more than the registers of a SIMD (512 per lane, handed out in eights; a workgroup has one wave on each
+    // SIMD) hold.  Counting too many here means workgroups that wait for one another without all being resident.
     hipFuncAttributes attr;
-    int lds_limit = 1 << 20;
-    if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(kernel)) == hipSuccess && attr.sharedSizeBytes > 0)
-        lds_limit = (int)(163840 / ((attr.sharedSizeBytes + 4095) / 4096 * 4096));
-    else
+    int own_limit = 1 << 20;
+    if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(kernel)) == hipSuccess) {
+        if (attr.sharedSizeBytes > 0) own_limit = (int)(163840 / ((attr.sharedSizeBytes + 4095) / 4096 * 4096));
+        if (attr.numRegs > 0) {
+            const int by_regs = 512 / ((attr.numRegs + 7) / 8 * 8);
+            if (by_regs < own_limit) own_limit = by_regs;
+        }
+    } else {
         (void)hipGetLastError();
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_unit, kernel, kBlock, 0) == hipSuccess && per_unit > lds_limit)
-        per_unit = lds_limit;
+    }
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_unit, kernel, kBlock, 0) == hipSuccess && per_unit > own_limit)
+        per_unit = own_limit;
     if (per_unit > 0 &&
         hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess &&
         units > 0 && (uint64_t)per_unit * (uint64_t)units >= 2)
