@@ -144,6 +144,24 @@ bt_status bt_compress(const void *d_in, uint64_t n, bt_dtype dtype,
                       uint64_t *d_nnz,
                       void *d_workspace, size_t workspace_bytes, bt_stream stream);
 
+/* bt_compress for callers that cannot allocate device memory and have no workspace to pass: code
+ * whose stream is being recorded into a HIP graph, tight serving loops, harnesses that forbid
+ * allocation.  Same arguments and results as bt_compress, without the workspace: the library
+ * uses a workspace of its own, a device array of 256 + 6144 * BT_STATIC_MAX_TILES / 256 bytes
+ * (393,472) that exists once on every GPU the library is loaded on until the process ends.  The
+ * call allocates and frees nothing; it enqueues a fill kernel that clears that workspace and then
+ * the compression kernel.
+ *   n           at most BT_STATIC_MAX_TILES tiles (bt_tile_elems(dtype) elements each),
+ *               else BT_ERR_SIZE.
+ * All calls on one GPU share the one array: two of them that can be in flight at the same time
+ * (different streams without an event between them) race, and so do the processes' threads that
+ * issue them.  Errors: as bt_compress, without BT_ERR_WORKSPACE; BT_ERR_HIP also if the array's
+ * address cannot be had. */
+#define BT_STATIC_MAX_TILES 16384
+bt_status bt_compress_static(const void *d_in, uint64_t n, bt_dtype dtype,
+                             uint32_t *d_bitmap, void *d_values, uint64_t values_cap,
+                             uint64_t *d_nnz, bt_stream stream);
+
 /* Activation pruning (Section 4.3) fused into Algorithm 1: one pass that stores an
  * element only where its value exceeds `threshold` and treats it as zero elsewhere
  * (the paper's thresholds are 0, 0.01, 0.05 and 0.1).  The comparison is strict and is

@@ -59,6 +59,8 @@ def lib():
         L.bt_workspace_init.restype, L.bt_workspace_init.argtypes = ci, [vp, sz, vp]
         L.bt_compress.restype = ci
         L.bt_compress.argtypes = [vp, u64, ci, vp, vp, u64, vp, vp, sz, vp]
+        L.bt_compress_static.restype = ci
+        L.bt_compress_static.argtypes = [vp, u64, ci, vp, vp, u64, vp, vp]
         L.bt_compress_pruned.restype = ci
         L.bt_compress_pruned.argtypes = [vp, u64, ci, ctypes.c_float, vp, vp, u64, vp, vp, sz, vp]
         L.bt_activation_compress.restype = ci
@@ -172,6 +174,21 @@ def bt_compress(x, bitmap, values, nnz, workspace, stream=None):
     _check("bt_compress", lib().bt_compress(
         _ptr(x), x.numel(), dtype_code(x.dtype), _ptr(bitmap), _ptr(values), values.numel(), _ptr(nnz),
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def bt_compress_static(x, bitmap, values, nnz, stream=None):
+    """bt_compress on the library's own workspace (nothing is allocated by the call); x of at
+    most BT_STATIC_MAX_TILES tiles.  Calls on one GPU share that workspace: keep them ordered."""
+    for t, name in ((x, "x"), (bitmap, "bitmap"), (values, "values"), (nnz, "nnz")):
+        _dev(t, name)
+    if values.dtype != x.dtype:
+        raise TypeError("values must have the dtype of x")
+    if bitmap.element_size() != 4 or bitmap.numel() * 4 < bt_bitmap_bytes(x.numel()):
+        raise ValueError("bitmap must hold ceil(n/32) 32-bit words")
+    if nnz.element_size() != 8 or nnz.numel() < 1:
+        raise ValueError("nnz must be one 64-bit integer")
+    _check("bt_compress_static", lib().bt_compress_static(
+        _ptr(x), x.numel(), dtype_code(x.dtype), _ptr(bitmap), _ptr(values), values.numel(), _ptr(nnz), _stream(stream)))
 
 
 def bt_compress_pruned(x, threshold, bitmap, values, nnz, workspace, stream=None):

@@ -1963,6 +1963,35 @@ bt_status launch_decompress_indexed(const Job &job, uint64_t slots, int s, hipSt
     return launched();
 }
 
+// ---- a workspace that belongs to the library -------------------------------------------------
+//
+// For callers that cannot allocate (see bt_compress_static in the header): a workspace for tensors of
+// up to BT_STATIC_MAX_TILES tiles, one copy on every device the library is used on, held until the
+// process ends.  In host code the array's name only stands for the symbol: what kernels and fills get is
+// the address that the runtime reports for it on the current device, looked up once per device.
+constexpr size_t kStaticBytes = kHeaderBytes + (size_t)(BT_STATIC_MAX_TILES / kSlotsPerBlock) * kBlockBytes;
+static_assert(BT_STATIC_MAX_TILES % kSlotsPerBlock == 0, "whole blocks");
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+bt_status static_workspace(char **ws) {
+    static std::atomic<char *> known[kMaxDevices];
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) {
+        (void)hipGetLastError();
+        return BT_ERR_HIP;
+    }
+    char *ptr = known[device].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        if (hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+            (void)hipGetLastError();
+            return BT_ERR_HIP;
+        }
+        known[device].store(ptr, std::memory_order_release);      // (two threads may both look it up: same answer)
+    }
+    *ws = ptr;
+    return BT_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -2043,6 +2072,25 @@ bt_status bt_compress(const void *d_in, uint64_t n, bt_dtype dtype, uint32_t *d_
                       bt_stream stream) {
     return compress_common(d_in, n, dtype, false, 0.0, d_bitmap, d_values, values_cap, d_nnz, nullptr, nullptr,
                            d_workspace, workspace_bytes, stream);
+}
+
+bt_status bt_compress_static(const void *d_in, uint64_t n, bt_dtype dtype, uint32_t *d_bitmap, void *d_values,
+                             uint64_t values_cap, uint64_t *d_nnz, bt_stream stream) {
+    const int s = elem_size(dtype);
+    if (s == 0) return BT_ERR_DTYPE;
+    if (n > BT_MAX_ELEMENTS || tiles_for(n, s) > BT_STATIC_MAX_TILES) return BT_ERR_SIZE;
+    char *ws = nullptr;
+    const bt_status st = static_workspace(&ws);
+    if (st != BT_OK) return st;
+    // The array keeps what the last call left, possibly a call that gave up a wait: start from a clean workspace
+    // every time (a fill kernel rather than a memset, which callers that record the stream could not replay).
+    const uint64_t words = kStaticBytes / 8;
+    fill_u64_kernel<<<dim3((unsigned)((words + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
+        reinterpret_cast<uint64_t *>(ws), words, 0);
+    const bt_status fs = launched();
+    if (fs != BT_OK) return fs;
+    return compress_common(d_in, n, dtype, false, 0.0, d_bitmap, d_values, values_cap, d_nnz, nullptr, nullptr, ws,
+                           kStaticBytes, stream);
 }
 
 bt_status bt_compress_pruned(const void *d_in, uint64_t n, bt_dtype dtype, float threshold, uint32_t *d_bitmap,
