@@ -164,16 +164,19 @@ bt_status bt_compress_static(const void *d_in, uint64_t n, bt_dtype dtype,
 
 /* Activation pruning (Section 4.3) fused into Algorithm 1: one pass that stores an
  * element only where its value exceeds `threshold` and treats it as zero elsewhere
- * (the paper's thresholds are 0, 0.01, 0.05 and 0.1).  The comparison is strict and is
- * made in single precision after widening fp16 / bf16 exactly (for BT_F64: in double
- * precision, the threshold widened exactly); a NaN exceeds nothing and is dropped.  The result is exactly bt_compress of the pruned tensor (so a +0.0
+ * (the paper's thresholds are 0, 0.01, 0.05 and 0.1).  The comparison is strict and exact:
+ * an element is kept where its value, as a real number, is greater than `threshold`, as a
+ * real number.  (BT_F64 elements are compared in double precision; narrower ones, widened
+ * exactly, in single precision with the largest single at or below `threshold`, which
+ * decides the same.)  A NaN element exceeds nothing and is dropped; a NaN threshold drops
+ * everything.  The result is exactly bt_compress of the pruned tensor (so a +0.0
  * that survives a negative threshold is still not stored).  The bitmap marks the kept
  * elements, d_values holds their original
  * bit patterns in index order, *d_nnz their number.  With threshold 0 on a
  * pre-activation tensor x this is compress(ReLU(x)) without ever writing ReLU(x):
  * bt_decompress then yields ReLU(x) and bt_relu_backward_from_bitmap its backward.
  * All arguments, requirements and errors as for bt_compress. */
-bt_status bt_compress_pruned(const void *d_in, uint64_t n, bt_dtype dtype, float threshold,
+bt_status bt_compress_pruned(const void *d_in, uint64_t n, bt_dtype dtype, double threshold,
                              uint32_t *d_bitmap, void *d_values, uint64_t values_cap,
                              uint64_t *d_nnz,
                              void *d_workspace, size_t workspace_bytes, bt_stream stream);
@@ -186,7 +189,7 @@ bt_status bt_compress_pruned(const void *d_in, uint64_t n, bt_dtype dtype, float
  * x serves both; run separately, ReLU and bt_compress read the activation three times and
  * write it once more.  d_dense_out may be d_in itself (in place) but must not partly
  * overlap it or any other argument.  Everything else as bt_compress_pruned. */
-bt_status bt_activation_compress(const void *d_in, uint64_t n, bt_dtype dtype, float threshold,
+bt_status bt_activation_compress(const void *d_in, uint64_t n, bt_dtype dtype, double threshold,
                                  void *d_dense_out,
                                  uint32_t *d_bitmap, void *d_values, uint64_t values_cap,
                                  uint64_t *d_nnz,
@@ -269,7 +272,8 @@ bt_status bt_mask_apply(const uint32_t *d_bitmap, const void *d_in, uint64_t n, 
  * to all of them; Table 1 lists a network's layers).  Compressing them one call
  * each pays one launch and one pipeline fill-and-drain per tensor, which dominates
  * for the small layers; the batched calls run Algorithm 1 / Algorithm 2 on all the
- * tensors of a list in one launch per BT_MAX_BATCH tensors.  The result for each
+ * tensors of a list in one launch per BT_MAX_BATCH tensors (restoration) or 52 tensors
+ * (compression, whose items are larger).  The result for each
  * tensor is exactly what the single-tensor call gives.  The item arrays are HOST
  * memory and are read before the call returns; the pointers inside them are device
  * pointers with the meaning, alignment and overlap rules of the single-tensor calls.
@@ -282,6 +286,11 @@ typedef struct {
     void *d_values;      /* room for values_cap elements */
     uint64_t values_cap;
     uint64_t *d_nnz;     /* one uint64 per tensor, 8-byte aligned, required also when n == 0 */
+    uint64_t *d_index;   /* NULL, or bt_index_bytes(n, dtype) bytes, 8-byte aligned: the tensor's tile index,
+                            as bt_compress_indexed writes it */
+    void *d_dense_out;   /* bt_compress_batch_pruned only, else NULL: the dense pruned tensor, as
+                            bt_activation_compress writes it (n elements, 16-byte aligned, may be d_in);
+                            given for every tensor of the call that has elements, or for none */
 } bt_compress_item;
 
 typedef struct {
@@ -289,6 +298,8 @@ typedef struct {
     const void *d_values;
     uint64_t n;
     void *d_out;         /* n elements, 16-byte aligned */
+    uint64_t values_cap; /* bt_decompress_batch_indexed only: elements d_values holds, as for bt_decompress_indexed */
+    const uint64_t *d_index; /* bt_decompress_batch_indexed only: the tensor's tile index */
 } bt_decompress_item;
 
 /* Workspace bytes a batched call on tensors of n[0..count) elements needs (host
@@ -300,14 +311,38 @@ size_t bt_batch_workspace_bytes(const uint64_t *n, size_t count, bt_dtype dtype)
  * anything is launched.  d_workspace: bt_batch_workspace_bytes(...) bytes, 128-byte
  * aligned, initialised once with bt_workspace_init; the same workspace may serve
  * single-tensor and batched calls alike, in stream order.  count == 0 does nothing.
- * Errors: as bt_compress (the first offending item decides). */
+ * d_index of an item, if
+ * given, receives that tensor's tile index.  Errors: as bt_compress (the first offending item
+ * decides); BT_ERR_NULL also if an item has d_dense_out. */
 bt_status bt_compress_batch(const bt_compress_item *items, size_t count, bt_dtype dtype,
                             void *d_workspace, size_t workspace_bytes, bt_stream stream);
 
+/* bt_compress_pruned on every tensor of items[0..count), one threshold for all; where the
+ * items give d_dense_out, bt_activation_compress (the activations of a whole list of layers
+ * pruned, handed on and stashed in one launch).  Otherwise as bt_compress_batch.
+ * Errors: also BT_ERR_NULL if some tensors with elements have d_dense_out and others do not. */
+bt_status bt_compress_batch_pruned(const bt_compress_item *items, size_t count, bt_dtype dtype,
+                                   double threshold,
+                                   void *d_workspace, size_t workspace_bytes, bt_stream stream);
+
 /* Algorithm 2 on every tensor of items[0..count); otherwise as bt_compress_batch and
- * bt_decompress. */
+ * bt_decompress.  values_cap and d_index of the items are not looked at. */
 bt_status bt_decompress_batch(const bt_decompress_item *items, size_t count, bt_dtype dtype,
                               void *d_workspace, size_t workspace_bytes, bt_stream stream);
+
+/* bt_decompress_indexed on every tensor of items[0..count), each from the tile index that
+ * bt_compress_indexed or a batched compression with d_index left for it: no scan, no
+ * workspace, no dependency between tiles or tensors.  Errors: as bt_decompress_indexed. */
+bt_status bt_decompress_batch_indexed(const bt_decompress_item *items, size_t count, bt_dtype dtype,
+                                      bt_stream stream);
+
+/* What became of the calls on a workspace, without knowing its layout: enqueues a kernel
+ * that writes d_status[0] = 1 if a kernel gave up a wait on this workspace (the outputs of
+ * that call and of every later one are not valid, and the workspace refuses work until
+ * bt_workspace_init has been run on it again), else 0, and d_status[1] = the number of calls
+ * completed on it since it was initialised.  d_status: two uint32 of device memory, valid
+ * once `stream` has reached this call.  Errors: BT_ERR_NULL, BT_ERR_ALIGN, BT_ERR_HIP. */
+bt_status bt_workspace_status(const void *d_workspace, uint32_t *d_status, bt_stream stream);
 
 #ifdef __cplusplus
 }

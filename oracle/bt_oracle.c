@@ -24,8 +24,8 @@
  *     bf16 are the same codec.
  *
  * Activation pruning (Section 4.3) is bt_oracle_prune: an element is kept where its
- * value exceeds the threshold (strictly; the comparison is made in single precision
- * after widening half / bfloat16 exactly, in double precision for doubles; a NaN exceeds nothing) and becomes +0
+ * value exceeds the threshold (strictly, and as real numbers: every element format widens
+ * exactly to double, where it is compared with the threshold, a double; a NaN exceeds nothing) and becomes +0
  * elsewhere.  With threshold 0 on a pre-activation tensor this is ReLU.  Pruning
  * followed by Algorithm 1 is what the fused GPU call is checked against.
  *
@@ -179,10 +179,9 @@ static float widen_to_f32(uint64_t bits, int dtype)
 }
 
 /* out[i] = T[i] where value(T[i]) > threshold, +0 (all-zero bits) elsewhere.
- * Double-precision elements (dtype 3) are compared as doubles with the threshold
- * widened to double, which is exact as well.
+ * The element is widened to double (exact for all four formats) and compared there.
  * Returns the number of kept elements, or UINT64_MAX for an unknown dtype. */
-uint64_t bt_oracle_prune(const void *T, uint64_t n, int dtype, float threshold, void *out)
+uint64_t bt_oracle_prune(const void *T, uint64_t n, int dtype, double threshold, void *out)
 {
     if (dtype < 0 || dtype > 3) return UINT64_MAX;
     const int width = dtype == 3 ? 8 : (dtype == 0 ? 4 : 2);
@@ -195,9 +194,9 @@ uint64_t bt_oracle_prune(const void *T, uint64_t n, int dtype, float threshold, 
         if (dtype == 3) {
             double d;
             memcpy(&d, &bits, sizeof d);
-            keep = d > (double)threshold;
+            keep = d > threshold;
         } else {
-            keep = widen_to_f32(bits, dtype) > threshold;
+            keep = (double)widen_to_f32(bits, dtype) > threshold;
         }
         if (keep) {
             store_bits(o, i, width, bits);

@@ -42,7 +42,7 @@ def _load():
         lib.bt_oracle_relu_backward.restype = ci
         lib.bt_oracle_relu_backward.argtypes = [vp, vp, u64, ci, vp]
         lib.bt_oracle_prune.restype = u64
-        lib.bt_oracle_prune.argtypes = [vp, u64, ci, ctypes.c_float, vp]
+        lib.bt_oracle_prune.argtypes = [vp, u64, ci, ctypes.c_double, vp]
         lib.bt_oracle_coo_size.restype = u64
         lib.bt_oracle_coo_size.argtypes = [u64, ci, ci, ci]
         lib.bt_oracle_mask_apply.restype = ci
@@ -120,7 +120,7 @@ def prune(T, dtype, threshold):
     assert T.dtype.itemsize == {0: 4, 1: 2, 2: 2, 3: 8}[code]
     out = np.empty_like(T)
     out.view(np.uint8)[:] = 0xA5
-    kept = int(_load().bt_oracle_prune(_ptr(T), T.size, code, float(np.float32(threshold)), _ptr(out)))
+    kept = int(_load().bt_oracle_prune(_ptr(T), T.size, code, float(threshold), _ptr(out)))
     assert kept <= T.size
     return out
 

@@ -14,6 +14,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbittrain.so")
 
 BT_F32, BT_F16, BT_BF16, BT_F64 = 0, 1, 2, 3
+# 32-bit words of a workspace that a caller may look at (BT_WS_* of the C header)
+BT_WS_ERROR_WORD, BT_WS_WAIT_LIMIT_WORD = 2, 3
+BT_STATIC_MAX_TILES = 16384
 BT_OK = 0
 STATUS_NAMES = {0: "BT_OK", 1: "BT_ERR_NULL", 2: "BT_ERR_DTYPE", 3: "BT_ERR_ALIGN", 4: "BT_ERR_WORKSPACE",
                 5: "BT_ERR_HIP", 6: "BT_ERR_SIZE", 7: "BT_ERR_UNSUPPORTED"}
@@ -33,13 +36,14 @@ class BitTrainError(RuntimeError):
 class CompressItem(ctypes.Structure):
     """bt_compress_item of the C header."""
     _fields_ = [("d_in", ctypes.c_void_p), ("n", ctypes.c_uint64), ("d_bitmap", ctypes.c_void_p),
-                ("d_values", ctypes.c_void_p), ("values_cap", ctypes.c_uint64), ("d_nnz", ctypes.c_void_p)]
+                ("d_values", ctypes.c_void_p), ("values_cap", ctypes.c_uint64), ("d_nnz", ctypes.c_void_p),
+                ("d_index", ctypes.c_void_p), ("d_dense_out", ctypes.c_void_p)]
 
 
 class DecompressItem(ctypes.Structure):
     """bt_decompress_item of the C header."""
     _fields_ = [("d_bitmap", ctypes.c_void_p), ("d_values", ctypes.c_void_p), ("n", ctypes.c_uint64),
-                ("d_out", ctypes.c_void_p)]
+                ("d_out", ctypes.c_void_p), ("values_cap", ctypes.c_uint64), ("d_index", ctypes.c_void_p)]
 
 
 def lib():
@@ -62,9 +66,9 @@ def lib():
         L.bt_compress_static.restype = ci
         L.bt_compress_static.argtypes = [vp, u64, ci, vp, vp, u64, vp, vp]
         L.bt_compress_pruned.restype = ci
-        L.bt_compress_pruned.argtypes = [vp, u64, ci, ctypes.c_float, vp, vp, u64, vp, vp, sz, vp]
+        L.bt_compress_pruned.argtypes = [vp, u64, ci, ctypes.c_double, vp, vp, u64, vp, vp, sz, vp]
         L.bt_activation_compress.restype = ci
-        L.bt_activation_compress.argtypes = [vp, u64, ci, ctypes.c_float, vp, vp, vp, u64, vp, vp, sz, vp]
+        L.bt_activation_compress.argtypes = [vp, u64, ci, ctypes.c_double, vp, vp, vp, u64, vp, vp, sz, vp]
         L.bt_decompress.restype = ci
         L.bt_decompress.argtypes = [vp, vp, u64, ci, vp, vp, sz, vp]
         L.bt_relu_backward_from_bitmap.restype = ci
@@ -85,6 +89,12 @@ def lib():
         L.bt_compress_batch.argtypes = [ctypes.POINTER(CompressItem), sz, ci, vp, sz, vp]
         L.bt_decompress_batch.restype = ci
         L.bt_decompress_batch.argtypes = [ctypes.POINTER(DecompressItem), sz, ci, vp, sz, vp]
+        L.bt_compress_batch_pruned.restype = ci
+        L.bt_compress_batch_pruned.argtypes = [ctypes.POINTER(CompressItem), sz, ci, ctypes.c_double, vp, sz, vp]
+        L.bt_decompress_batch_indexed.restype = ci
+        L.bt_decompress_batch_indexed.argtypes = [ctypes.POINTER(DecompressItem), sz, ci, vp]
+        L.bt_workspace_status.restype = ci
+        L.bt_workspace_status.argtypes = [vp, vp, vp]
         _lib = L
     return _lib
 
@@ -203,7 +213,7 @@ def bt_compress_pruned(x, threshold, bitmap, values, nnz, workspace, stream=None
     if nnz.element_size() != 8 or nnz.numel() < 1:
         raise ValueError("nnz must be one 64-bit integer")
     _check("bt_compress_pruned", lib().bt_compress_pruned(
-        _ptr(x), x.numel(), dtype_code(x.dtype), ctypes.c_float(threshold), _ptr(bitmap), _ptr(values), values.numel(),
+        _ptr(x), x.numel(), dtype_code(x.dtype), ctypes.c_double(threshold), _ptr(bitmap), _ptr(values), values.numel(),
         _ptr(nnz), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
@@ -249,11 +259,17 @@ def _bytes(t):
     return t.numel() * t.element_size()
 
 
-def compress_items(xs, bitmaps, values, nnz):
-    """The host item array of bt_compress_batch for lists of device tensors; nnz is one
-    int64 tensor with an entry per tensor.  Build it once and reuse it while the buffers live."""
+def compress_items(xs, bitmaps, values, nnz, indexes=None, dense_outs=None):
+    """The host item array of the batched compressions for lists of device tensors; nnz is one
+    int64 tensor with an entry per tensor; indexes (optional): an int64 tensor of
+    bt_index_bytes(n) / 8 entries per tensor, to receive its tile index; dense_outs (optional,
+    bt_compress_batch_pruned): a tensor like x per tensor (may be x itself) for the dense pruned
+    result.  Build it once and reuse it while the buffers live."""
     if not (len(xs) == len(bitmaps) == len(values)) or nnz.numel() < len(xs) or nnz.element_size() != 8:
         raise ValueError("one bitmap, one value buffer and one 64-bit nnz entry per tensor")
+    for extra, name in ((indexes, "indexes"), (dense_outs, "dense_outs")):
+        if extra is not None and len(extra) != len(xs):
+            raise ValueError("%s: one per tensor" % name)
     _dev(nnz, "nnz")
     items = (CompressItem * max(len(xs), 1))()
     for i, (x, b, v) in enumerate(zip(xs, bitmaps, values)):
@@ -263,15 +279,27 @@ def compress_items(xs, bitmaps, values, nnz):
             raise TypeError("all tensors and value buffers of a batch share one dtype")
         if b.element_size() != 4 or _bytes(b) < bt_bitmap_bytes(x.numel()):
             raise ValueError("bitmap %d must hold ceil(n/32) 32-bit words" % i)
+        index = dense = None
+        if indexes is not None and x.numel() != 0:
+            _dev(indexes[i], "index")
+            if indexes[i].element_size() != 8 or _bytes(indexes[i]) < bt_index_bytes(x.numel(), x.dtype):
+                raise ValueError("index %d must hold bt_index_bytes(n, dtype) bytes of 64-bit entries" % i)
+            index = indexes[i].data_ptr()
+        if dense_outs is not None and x.numel() != 0:
+            _dev(dense_outs[i], "dense_out")
+            if dense_outs[i].dtype != x.dtype or dense_outs[i].numel() != x.numel():
+                raise TypeError("dense_out %d must match x" % i)
+            dense = dense_outs[i].data_ptr()
         items[i] = CompressItem(x.data_ptr(), x.numel(), b.data_ptr(), v.data_ptr(), v.numel(),
-                                nnz.data_ptr() + 8 * i)
+                                nnz.data_ptr() + 8 * i, index, dense)
     return items
 
 
-def decompress_items(bitmaps, values, outs):
-    """The host item array of bt_decompress_batch for lists of device tensors."""
-    if not (len(outs) == len(bitmaps) == len(values)):
-        raise ValueError("one bitmap and one value buffer per tensor")
+def decompress_items(bitmaps, values, outs, indexes=None):
+    """The host item array of the batched restorations for lists of device tensors; indexes: the
+    tile indexes, for bt_decompress_batch_indexed."""
+    if not (len(outs) == len(bitmaps) == len(values)) or (indexes is not None and len(indexes) != len(outs)):
+        raise ValueError("one bitmap and one value buffer (and one index) per tensor")
     items = (DecompressItem * max(len(outs), 1))()
     for i, (b, v, o) in enumerate(zip(bitmaps, values, outs)):
         for t, name in ((b, "bitmap"), (v, "values"), (o, "out")):
@@ -280,7 +308,13 @@ def decompress_items(bitmaps, values, outs):
             raise TypeError("all tensors and value buffers of a batch share one dtype")
         if b.element_size() != 4 or _bytes(b) < bt_bitmap_bytes(o.numel()):
             raise ValueError("bitmap %d must hold ceil(n/32) 32-bit words" % i)
-        items[i] = DecompressItem(b.data_ptr(), v.data_ptr(), o.numel(), o.data_ptr())
+        index = None
+        if indexes is not None and o.numel() != 0:
+            _dev(indexes[i], "index")
+            if indexes[i].element_size() != 8 or _bytes(indexes[i]) < bt_index_bytes(o.numel(), o.dtype):
+                raise ValueError("index %d must hold bt_index_bytes(n, dtype) bytes of 64-bit entries" % i)
+            index = indexes[i].data_ptr()
+        items[i] = DecompressItem(b.data_ptr(), v.data_ptr(), o.numel(), o.data_ptr(), v.numel(), index)
     return items
 
 
@@ -290,6 +324,30 @@ def bt_compress_batch(items, count, dtype, workspace, stream=None):
     _check("bt_compress_batch", lib().bt_compress_batch(
         items, count, dtype if isinstance(dtype, int) else dtype_code(dtype), _ptr(workspace), _bytes(workspace),
         _stream(stream)))
+
+
+def bt_compress_batch_pruned(items, count, dtype, threshold, workspace, stream=None):
+    """bt_compress_pruned (bt_activation_compress where the items carry dense outputs) on every
+    tensor of `items`, one threshold for all."""
+    _dev(workspace, "workspace")
+    _check("bt_compress_batch_pruned", lib().bt_compress_batch_pruned(
+        items, count, dtype if isinstance(dtype, int) else dtype_code(dtype), ctypes.c_double(threshold), _ptr(workspace),
+        _bytes(workspace), _stream(stream)))
+
+
+def bt_decompress_batch_indexed(items, count, dtype, stream=None):
+    """bt_decompress_indexed on every tensor of `items` (from decompress_items with indexes)."""
+    _check("bt_decompress_batch_indexed", lib().bt_decompress_batch_indexed(
+        items, count, dtype if isinstance(dtype, int) else dtype_code(dtype), _stream(stream)))
+
+
+def bt_workspace_status(workspace, status, stream=None):
+    """status (int32[2] on the device): [0] = 1 if a call gave up a wait on this workspace, [1] = calls completed."""
+    _dev(workspace, "workspace")
+    _dev(status, "status")
+    if status.element_size() != 4 or status.numel() < 2:
+        raise ValueError("status must be two 32-bit integers")
+    _check("bt_workspace_status", lib().bt_workspace_status(_ptr(workspace), _ptr(status), _stream(stream)))
 
 
 def bt_decompress_batch(items, count, dtype, workspace, stream=None):
@@ -366,5 +424,5 @@ def bt_activation_compress(x, threshold, dense_out, bitmap, values, nnz, workspa
     if nnz.element_size() != 8 or nnz.numel() < 1:
         raise ValueError("nnz must be one 64-bit integer")
     _check("bt_activation_compress", lib().bt_activation_compress(
-        _ptr(x), x.numel(), dtype_code(x.dtype), ctypes.c_float(threshold), _ptr(dense_out), _ptr(bitmap), _ptr(values),
+        _ptr(x), x.numel(), dtype_code(x.dtype), ctypes.c_double(threshold), _ptr(dense_out), _ptr(bitmap), _ptr(values),
         values.numel(), _ptr(nnz), _ptr(workspace), _bytes(workspace), _stream(stream)))

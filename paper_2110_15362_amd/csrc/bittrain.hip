@@ -30,6 +30,7 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <atomic>
+#include <cmath>
 #include <type_traits>
 
 #include "bittrain.h"
@@ -990,7 +991,7 @@ __device__ __forceinline__ void ring_flush(const unsigned char *data, char *g0_p
 // counted.  Only when the ring cannot take another phase does a wave stop and wait for a
 // prefix.  What is left in the rings at the end is waited for and written out.
 template <int S, int KEEP, bool DENSE, class Job>
-__global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Job job, char *ws, const double threshold) {
+__global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Job job, char *ws, const double threshold, const float threshold_f) {
     using G = Geo<S>;
     constexpr int E = G::E;
     __shared__ __attribute__((aligned(16))) unsigned char s_ring[kWaves * kRingStride];
@@ -1042,7 +1043,6 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
     const uint32_t cur = ep.cur;
     const uint32_t limit = wait_limit(hdr);
     zero_previous(ws, ep, worker, workers);
-    const float threshold_f = (float)threshold;
 
     // This wave's ring: phases of compacted values, first in first out.  An entry occupies
     // [start, start + 32 + its values rounded up to 16 bytes): 16 bytes of slack, the values,
@@ -1770,6 +1770,14 @@ __global__ void fill_u64_kernel(uint64_t *p, uint64_t count, uint64_t value) {
     if (i < count) p[i] = value;
 }
 
+// bt_workspace_status: d_status[0] = 1 if a wait was given up on the workspace (else 0), d_status[1] = calls completed.
+__global__ void copy_status_kernel(const uint32_t *ws, uint32_t *d_status) {
+    if (threadIdx.x == 0) {
+        d_status[0] = ws[kHdrError] != 0 ? 1u : 0u;
+        d_status[1] = ws[kHdrSeq];
+    }
+}
+
 // ---- host side ---------------------------------------------------------------------------------
 
 int elem_size(bt_dtype dt) {
@@ -1914,10 +1922,15 @@ template <class Job>
 bt_status launch_compress(const Job &job, uint64_t slots, bt_dtype dtype, bool prune, bool dense, double threshold,
                           char *ws, hipStream_t hs) {
     const dim3 block(kBlock);
+    // Elements narrower than a double are compared in single precision.  For a single x, x > threshold exactly when
+    // x > the largest single at or below the threshold, so that is what the kernel gets (a NaN stays one: nothing
+    // exceeds it).
+    float threshold_f = (float)threshold;
+    if ((double)threshold_f > threshold) threshold_f = std::nextafterf(threshold_f, -INFINITY);
 #define BT_LAUNCH_COMPRESS(S_, KEEP_, DENSE_)                                                   \
     do {                                                                                        \
         auto kernel = compress_kernel<S_, KEEP_, DENSE_, Job>;                                  \
-        kernel<<<persistent_grid(kernel, slots), block, 0, hs>>>(job, ws, threshold);           \
+        kernel<<<persistent_grid(kernel, slots), block, 0, hs>>>(job, ws, threshold, threshold_f); \
     } while (0)
     const int s = elem_size(dtype);
     if (!prune) {
@@ -2093,21 +2106,21 @@ bt_status bt_compress_static(const void *d_in, uint64_t n, bt_dtype dtype, uint3
                            kStaticBytes, stream);
 }
 
-bt_status bt_compress_pruned(const void *d_in, uint64_t n, bt_dtype dtype, float threshold, uint32_t *d_bitmap,
+bt_status bt_compress_pruned(const void *d_in, uint64_t n, bt_dtype dtype, double threshold, uint32_t *d_bitmap,
                              void *d_values, uint64_t values_cap, uint64_t *d_nnz, void *d_workspace,
                              size_t workspace_bytes, bt_stream stream) {
-    return compress_common(d_in, n, dtype, true, (double)threshold, d_bitmap, d_values, values_cap, d_nnz, nullptr, nullptr,
+    return compress_common(d_in, n, dtype, true, threshold, d_bitmap, d_values, values_cap, d_nnz, nullptr, nullptr,
                            d_workspace, workspace_bytes, stream);
 }
 
-bt_status bt_activation_compress(const void *d_in, uint64_t n, bt_dtype dtype, float threshold, void *d_dense_out,
+bt_status bt_activation_compress(const void *d_in, uint64_t n, bt_dtype dtype, double threshold, void *d_dense_out,
                                  uint32_t *d_bitmap, void *d_values, uint64_t values_cap, uint64_t *d_nnz,
                                  void *d_workspace, size_t workspace_bytes, bt_stream stream) {
     if (elem_size(dtype) != 0 && n != 0 && n <= BT_MAX_ELEMENTS) {
         if (d_dense_out == nullptr) return BT_ERR_NULL;
         if (misaligned(d_dense_out, 16)) return BT_ERR_ALIGN;
     }
-    return compress_common(d_in, n, dtype, true, (double)threshold, d_bitmap, d_values, values_cap, d_nnz, nullptr, d_dense_out,
+    return compress_common(d_in, n, dtype, true, threshold, d_bitmap, d_values, values_cap, d_nnz, nullptr, d_dense_out,
                            d_workspace, workspace_bytes, stream);
 }
 
@@ -2193,22 +2206,28 @@ size_t bt_batch_workspace_bytes(const uint64_t *n, size_t count, bt_dtype dtype)
     return a > b ? a : b;
 }
 
-bt_status bt_compress_batch(const bt_compress_item *items, size_t count, bt_dtype dtype, void *d_workspace,
-                            size_t workspace_bytes, bt_stream stream) {
+static bt_status compress_batch_common(const bt_compress_item *items, size_t count, bt_dtype dtype, bool prune,
+                                       double threshold, void *d_workspace, size_t workspace_bytes, bt_stream stream) {
     const bt_status st = check_batch_common(items, count, dtype, d_workspace);
     if (st != BT_OK || count == 0) return st;
     const int s = elem_size(dtype);
+    size_t with_dense = 0, not_empty = 0;
     for (size_t i = 0; i < count; ++i) {
         const bt_compress_item &it = items[i];
         if (it.n > BT_MAX_ELEMENTS) return BT_ERR_SIZE;
         if (it.d_nnz == nullptr) return BT_ERR_NULL;
         if (misaligned(it.d_nnz, 8)) return BT_ERR_ALIGN;
         if (it.n == 0) continue;
+        ++not_empty;
         if (it.d_in == nullptr || it.d_bitmap == nullptr) return BT_ERR_NULL;
         if (it.d_values == nullptr && it.values_cap != 0) return BT_ERR_NULL;
-        if (misaligned(it.d_in, 16) || misaligned(it.d_bitmap, 4) || misaligned(it.d_values, (size_t)s))
+        if (misaligned(it.d_in, 16) || misaligned(it.d_bitmap, 4) || misaligned(it.d_values, (size_t)s) ||
+            misaligned(it.d_index, 8) || misaligned(it.d_dense_out, 16))
             return BT_ERR_ALIGN;
+        if (it.d_dense_out != nullptr) ++with_dense;
     }
+    // the dense output is a property of the launch: for every tensor that has elements, or for none
+    if (with_dense != 0 && (!prune || with_dense != not_empty)) return BT_ERR_NULL;
     const auto n_of = [items](size_t i) { return items[i].n; };
     if (workspace_bytes < batch_workspace_bytes(count, (size_t)kMaxBatchCompress, s, n_of)) return BT_ERR_WORKSPACE;
 
@@ -2219,20 +2238,31 @@ bt_status bt_compress_batch(const bt_compress_item *items, size_t count, bt_dtyp
         CompressMany b;
         lay_out(b.lay, first, c, s, n_of);
         for (size_t i = 0; i < (size_t)kMaxBatchCompress; ++i) {
-            const bt_compress_item it = i < c ? items[first + i] : bt_compress_item{nullptr, 0, nullptr, nullptr, 0, nullptr};
+            const bt_compress_item it =
+                i < c ? items[first + i] : bt_compress_item{nullptr, 0, nullptr, nullptr, 0, nullptr, nullptr, nullptr};
             b.in_[i] = it.d_in;
             b.n_[i] = it.n;
             b.bitmap_[i] = it.d_bitmap;
             b.values_[i] = it.d_values;
             b.cap_[i] = it.values_cap;
             b.nnz_[i] = it.d_nnz;
-            b.index_[i] = nullptr;
-            b.dense_[i] = nullptr;
+            b.index_[i] = it.n != 0 ? it.d_index : nullptr;
+            b.dense_[i] = it.n != 0 ? it.d_dense_out : nullptr;
         }
-        const bt_status ls = launch_compress(b, b.lay.start[c], dtype, false, false, 0.0, ws, hs);
+        const bt_status ls = launch_compress(b, b.lay.start[c], dtype, prune, with_dense != 0, threshold, ws, hs);
         if (ls != BT_OK) return ls;
     }
     return BT_OK;
+}
+
+bt_status bt_compress_batch(const bt_compress_item *items, size_t count, bt_dtype dtype, void *d_workspace,
+                            size_t workspace_bytes, bt_stream stream) {
+    return compress_batch_common(items, count, dtype, false, 0.0, d_workspace, workspace_bytes, stream);
+}
+
+bt_status bt_compress_batch_pruned(const bt_compress_item *items, size_t count, bt_dtype dtype, double threshold,
+                                   void *d_workspace, size_t workspace_bytes, bt_stream stream) {
+    return compress_batch_common(items, count, dtype, true, threshold, d_workspace, workspace_bytes, stream);
 }
 
 bt_status bt_decompress_batch(const bt_decompress_item *items, size_t count, bt_dtype dtype, void *d_workspace,
@@ -2258,7 +2288,7 @@ bt_status bt_decompress_batch(const bt_decompress_item *items, size_t count, bt_
         DecompressMany b;
         lay_out(b.lay, first, c, s, n_of);
         for (size_t i = 0; i < (size_t)kMaxBatchDecompress; ++i) {
-            const bt_decompress_item it = i < c ? items[first + i] : bt_decompress_item{nullptr, nullptr, 0, nullptr};
+            const bt_decompress_item it = i < c ? items[first + i] : bt_decompress_item{nullptr, nullptr, 0, nullptr, 0, nullptr};
             b.bitmap_[i] = it.d_bitmap;
             b.values_[i] = it.d_values;
             b.cap_[i] = ~(uint64_t)0;
@@ -2270,6 +2300,50 @@ bt_status bt_decompress_batch(const bt_decompress_item *items, size_t count, bt_
         if (ls != BT_OK) return ls;
     }
     return BT_OK;
+}
+
+bt_status bt_decompress_batch_indexed(const bt_decompress_item *items, size_t count, bt_dtype dtype, bt_stream stream) {
+    const int s = elem_size(dtype);
+    if (s == 0) return BT_ERR_DTYPE;
+    if (count == 0) return BT_OK;
+    if (items == nullptr) return BT_ERR_NULL;
+    for (size_t i = 0; i < count; ++i) {
+        const bt_decompress_item &it = items[i];
+        if (it.n > BT_MAX_ELEMENTS) return BT_ERR_SIZE;
+        if (it.n == 0) continue;
+        if (it.d_bitmap == nullptr || it.d_out == nullptr || it.d_index == nullptr) return BT_ERR_NULL;
+        if (it.d_values == nullptr && it.values_cap != 0) return BT_ERR_NULL;
+        if (misaligned(it.d_out, 16) || misaligned(it.d_bitmap, 4) || misaligned(it.d_values, (size_t)s) || misaligned(it.d_index, 8))
+            return BT_ERR_ALIGN;
+    }
+    const auto n_of = [items](size_t i) { return items[i].n; };
+    hipStream_t hs = (hipStream_t)stream;
+    for (size_t first = 0; first < count; first += kMaxBatchDecompress) {
+        const size_t c = count - first < (size_t)kMaxBatchDecompress ? count - first : (size_t)kMaxBatchDecompress;
+        DecompressMany b;
+        lay_out(b.lay, first, c, s, n_of);
+        for (size_t i = 0; i < (size_t)kMaxBatchDecompress; ++i) {
+            const bt_decompress_item it = i < c ? items[first + i] : bt_decompress_item{nullptr, nullptr, 0, nullptr, 0, nullptr};
+            b.bitmap_[i] = it.d_bitmap;
+            b.values_[i] = it.d_values;
+            b.cap_[i] = it.values_cap;
+            b.index_[i] = it.d_index;
+            b.n_[i] = it.n;
+            b.out_[i] = it.d_out;
+        }
+        const bt_status ls = launch_decompress_indexed(b, b.lay.start[c], s, hs);
+        if (ls != BT_OK) return ls;
+    }
+    return BT_OK;
+}
+
+// What the kernels leave in a workspace's header when they had to give up, as words a caller can copy back and look
+// at without knowing the layout.
+bt_status bt_workspace_status(const void *d_workspace, uint32_t *d_status, bt_stream stream) {
+    if (d_workspace == nullptr || d_status == nullptr) return BT_ERR_NULL;
+    if (misaligned(d_workspace, 128) || misaligned(d_status, 4)) return BT_ERR_ALIGN;
+    copy_status_kernel<<<dim3(1), dim3(64), 0, (hipStream_t)stream>>>(static_cast<const uint32_t *>(d_workspace), d_status);
+    return launched();
 }
 
 }  // extern "C"

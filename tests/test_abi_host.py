@@ -39,6 +39,12 @@ def test_every_declared_symbol_is_exported(bt):
     assert not hasattr(raw, "bt_stream_probe") and not hasattr(raw, "bt_timeline_set")
 
 
+def test_binding_constants_are_the_headers(bt):
+    text = open(os.path.join(os.path.dirname(__file__), "..", "include", "bittrain.h")).read()
+    for name in ("BT_WS_ERROR_WORD", "BT_WS_WAIT_LIMIT_WORD", "BT_STATIC_MAX_TILES"):
+        assert int(re.search(r"#define\s+%s\s+(\d+)" % name, text).group(1)) == getattr(bt, name)
+
+
 def test_header_compiles_as_plain_c(tmp_path):
     import subprocess
     src = tmp_path / "t.c"
@@ -189,6 +195,42 @@ def test_batch_workspace_bytes_and_host_errors(bt):
     assert decompress(wsb=wsb - 1) == 4
     assert L.bt_decompress_batch(None, 0, f32, None, 0, None) == 0
 
+    # the pruning batch: one dense output for every tensor that has elements, or for none; never without pruning
+    def c_dense(dense, index=None, n=1000):
+        good = bt.CompressItem(A, 1000, A, A, 1000, A, None, A)
+        return (bt.CompressItem * 3)(good, bt.CompressItem(A, n, A, A, 1000, A, index, dense), good)
+
+    pruned = lambda items, thr=0.0: L.bt_compress_batch_pruned(items, 3, f32, ctypes.c_double(thr), A, wsb, None)
+    assert pruned(c_dense(None)) == 1                      # two tensors have one, the third has not
+    assert pruned(c_dense(A + 8)) == 3
+    assert pruned(c_dense(A, index=A + 4)) == 3
+    assert L.bt_compress_batch(c_dense(A), 3, f32, A, wsb, None) == 1      # a dense output without pruning
+    assert L.bt_compress_batch_pruned(None, 3, f32, ctypes.c_double(0.0), A, wsb, None) == 1
+    assert L.bt_compress_batch_pruned(None, 0, f32, ctypes.c_double(0.0), None, 0, None) == 0
+    assert compress(items=c_items(), wsb=wsb - 1) == 4
+
+    # restoration from tile indexes: no workspace, the index required
+    def di_items(bm=A, val=A, n=1000, out=A, cap=1000, index=A):
+        good = bt.DecompressItem(A, A, 1000, A, 1000, A)
+        return (bt.DecompressItem * 3)(good, good, bt.DecompressItem(bm, val, n, out, cap, index))
+
+    indexed = lambda dt=f32, count=3, **kw: L.bt_decompress_batch_indexed(di_items(**kw), count, dt, None)
+    assert indexed(dt=7) == 2
+    assert indexed(index=None) == 1 and indexed(bm=None) == 1 and indexed(out=None) == 1 and indexed(val=None) == 1
+    assert indexed(index=A + 4) == 3 and indexed(out=A + 8) == 3
+    assert indexed(n=(1 << 37) + 1) == 6
+    assert L.bt_decompress_batch_indexed(None, 3, f32, None) == 1
+    assert L.bt_decompress_batch_indexed(None, 0, f32, None) == 0
+
+    # the workspace's state
+    assert L.bt_workspace_status(None, A, None) == 1 and L.bt_workspace_status(A, None, None) == 1
+    assert L.bt_workspace_status(A + 64, A, None) == 3 and L.bt_workspace_status(A, A + 2, None) == 3
+
+    # the entry point without a workspace refuses what its own workspace cannot hold, before anything else
+    assert L.bt_compress_static(None, 16385 * 8192, f32, None, None, 0, None, None) == 6
+    assert L.bt_compress_static(None, 16384 * 16384 + 1, f16, None, None, 0, None, None) == 6
+    assert L.bt_compress_static(None, 10, 9, None, None, 0, None, None) == 2
+
 
 def test_dense_and_coo_sizes_match_the_oracle(bt, oracle):
     for code, width in ((bt.BT_F32, 4), (bt.BT_F16, 2), (bt.BT_BF16, 2), (bt.BT_F64, 8)):
@@ -267,7 +309,7 @@ def test_activation_compress_host_errors(bt):
     wsb = bt.bt_workspace_bytes(1000, bt.BT_F32)
 
     def call(d_in=A, n=1000, dt=bt.BT_F32, thr=0.0, dense=A + 0x10000, bm=A, val=A, cap=1000, nnz=A, ws=A, wsb=wsb):
-        return L.bt_activation_compress(d_in, n, dt, ctypes.c_float(thr), dense, bm, val, cap, nnz, ws, wsb, None)
+        return L.bt_activation_compress(d_in, n, dt, ctypes.c_double(thr), dense, bm, val, cap, nnz, ws, wsb, None)
 
     assert call(dense=None) == 1 and call(dense=A + 8) == 3
     assert call(dt=9) == 2 and call(d_in=None) == 1 and call(nnz=None) == 1 and call(bm=None) == 1

@@ -213,3 +213,135 @@ def test_batch_config4_resnet50_set_full_size(bt, oracle):
         assert np.array_equal(b.cpu().numpy().view(np.uint32), o_bitmap), k
         assert np.array_equal(wl.bits(v.cpu()), o_values), k
         assert np.array_equal(wl.bits(o.cpu()), xb), k
+
+
+# ---- the pruning batch, the dense outputs, the tile indexes --------------------------------------
+
+_ORACLE_DT = {torch.float32: "f32", torch.float16: "f16", torch.bfloat16: "bf16", torch.float64: "f64"}
+
+
+def _pruned_batch_against_oracle(bt, oracle, xs, thr, dense, in_place=False):
+    """bt_compress_batch_pruned (with dense outputs and tile indexes) on CPU tensors xs, every output against
+    the oracle's pruning followed by Algorithm 1, then bt_decompress_batch_indexed of the result."""
+    dt = xs[0].dtype
+    ns = [x.numel() for x in xs]
+    ws = bt.new_batch_workspace(ns, dt)
+    xd = [x.clone().cuda() for x in xs]
+    bms = [torch.empty((n + 31) // 32, dtype=torch.int32, device="cuda") for n in ns]
+    vals = [_sentinel(n + 8, dt) for n in ns]
+    idx = [torch.full((max(bt.bt_index_bytes(n, dt) // 8, 1) + 1,), -3, dtype=torch.int64, device="cuda") for n in ns]
+    dense_outs = None
+    if dense:
+        dense_outs = xd if in_place else [_sentinel(n + 16 // x.element_size(), dt) for n, x in zip(ns, xs)]
+    nnz = torch.full((len(xs),), -7, dtype=torch.int64, device="cuda")
+    items = bt.compress_items(xd, bms, [v[:n] for v, n in zip(vals, ns)], nnz, indexes=[i[:-1] for i in idx],
+                              dense_outs=None if not dense else [d[:n] for d, n in zip(dense_outs, ns)])
+    bt.bt_compress_batch_pruned(items, len(xs), dt, thr, ws)
+    torch.cuda.synchronize()
+    tile = bt.bt_tile_elems(dt)
+    pruned = []
+    for k, x in enumerate(xs):
+        want = oracle.prune(wl.bits(x), _ORACLE_DT[dt], thr)
+        o_bitmap, o_values, o_nnz = oracle.compress(want)
+        pruned.append(want)
+        assert int(nnz[k].item()) == o_nnz, k
+        assert np.array_equal(bms[k].cpu().numpy().view(np.uint32), o_bitmap), k
+        vb = wl.bits(vals[k].cpu())
+        assert np.array_equal(vb[:o_nnz], o_values), k
+        assert (vb[o_nnz:] == _sent_of(vb)).all(), k
+        tiles = bt.bt_index_bytes(ns[k], dt) // 8
+        got_index = idx[k].cpu().numpy()
+        assert np.array_equal(got_index[:tiles].view(np.uint64), oracle.tile_index(o_bitmap, ns[k], tile)), k
+        assert (got_index[tiles:] == -3).all(), k
+        if dense:
+            db = wl.bits(dense_outs[k].cpu())
+            assert np.array_equal(db[:ns[k]], want), k
+            if not in_place:
+                assert (db[ns[k]:] == _sent_of(db)).all(), k
+    outs = [_sentinel(n + 16 // xs[0].element_size(), dt) for n in ns]
+    ditems = bt.decompress_items(bms, [v[:max(int(k), 0)] for v, k in zip(vals, nnz.cpu().tolist())], [o[:n] for o, n in zip(outs, ns)],
+                                 indexes=[i[:-1] for i in idx])
+    bt.bt_decompress_batch_indexed(ditems, len(xs), dt)
+    torch.cuda.synchronize()
+    for k, n in enumerate(ns):
+        ob = wl.bits(outs[k].cpu())
+        assert np.array_equal(ob[:n], pruned[k]), k
+        assert (ob[n:] == _sent_of(ob)).all(), k
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dt,thr", [(torch.float32, 0.0), (torch.float32, 0.1), (torch.float16, 0.1), (torch.bfloat16, 0.01),
+                                    (torch.float64, 0.1), (torch.float32, -1.0)])
+def test_pruned_batch_with_dense_outputs_and_tile_indexes(bt, oracle, dt, thr):
+    width = torch.empty(0, dtype=dt).element_size()
+    xs = []
+    for k, n in enumerate(_mixed_sizes(width)):
+        g = torch.Generator().manual_seed(100 + k)
+        x = torch.randn(n, generator=g, dtype=torch.float64) * 0.3
+        x[torch.rand(n, generator=g) < 0.3] = 0
+        xs.append(x.to(dt))
+    # values on both sides of the threshold's nearest narrower numbers
+    edge = torch.tensor([thr, np.nextafter(thr, 1.0), np.nextafter(thr, -1.0), float(np.float32(thr)), float(np.float16(thr)), 0.0, -0.0],
+                        dtype=torch.float64).repeat(300).to(dt)
+    xs.append(edge)
+    _pruned_batch_against_oracle(bt, oracle, xs, thr, dense=True)
+    _pruned_batch_against_oracle(bt, oracle, xs[:5], thr, dense=True, in_place=True)
+    _pruned_batch_against_oracle(bt, oracle, xs, thr, dense=False)
+
+
+@pytest.mark.gpu
+def test_pruned_single_calls_take_a_double_threshold(bt, oracle):
+    """bt_compress_pruned / bt_activation_compress on doubles and singles around a threshold that is no single."""
+    thr = 0.1
+    for dt in (torch.float64, torch.float32):
+        base = torch.tensor([thr, np.nextafter(thr, 1.0), np.nextafter(thr, -1.0), float(np.float32(thr)),
+                             float(np.nextafter(np.float32(thr), np.float32(0))), 0.25, -0.25, 0.0], dtype=torch.float64)
+        x = base.repeat(5000).to(dt)
+        n = x.numel()
+        ws = bt.new_workspace(n, dt)
+        bm = torch.empty((n + 31) // 32, dtype=torch.int32, device="cuda")
+        vals, dense = torch.empty(n, dtype=dt, device="cuda"), torch.empty(n, dtype=dt, device="cuda")
+        nnz = torch.zeros(1, dtype=torch.int64, device="cuda")
+        want = oracle.prune(wl.bits(x), _ORACLE_DT[dt], thr)
+        o_bitmap, o_values, o_nnz = oracle.compress(want)
+        for call in ("pruned", "activation"):
+            nnz.fill_(-1)
+            if call == "pruned":
+                bt.bt_compress_pruned(x.cuda(), thr, bm, vals, nnz, ws)
+            else:
+                bt.bt_activation_compress(x.cuda(), thr, dense, bm, vals, nnz, ws)
+            torch.cuda.synchronize()
+            assert int(nnz.item()) == o_nnz
+            assert np.array_equal(bm.cpu().numpy().view(np.uint32), o_bitmap)
+            assert np.array_equal(wl.bits(vals.cpu())[:o_nnz], o_values)
+        assert np.array_equal(wl.bits(dense.cpu()), want)
+
+
+@pytest.mark.gpu
+def test_config4_full_size_pruned_activation_batch_and_indexed_restore(bt, oracle):
+    """The 49 activations of the ResNet-50 set at full size: one pruning launch that also writes the dense pruned
+    tensors (in place) and the tile indexes, one restoration launch from the indexes; all against the oracle."""
+    xs = [cfg["x"].reshape(-1) for cfg in wl.config4_tensors()]
+    _pruned_batch_against_oracle(bt, oracle, xs, 0.05, dense=True, in_place=True)
+
+
+@pytest.mark.gpu
+def test_workspace_status_reports_a_given_up_wait(bt):
+    n = 50 * TILE[4] + 17
+    x = wl.random_sparse(n, torch.float32, 0.5, 9).cuda()
+    ws = bt.new_workspace(n, torch.float32)
+    status = torch.full((2,), -1, dtype=torch.int32, device="cuda")
+    bm = torch.empty((n + 31) // 32, dtype=torch.int32, device="cuda")
+    vals, nnz = torch.empty(n, dtype=torch.float32, device="cuda"), torch.zeros(1, dtype=torch.int64, device="cuda")
+    bt.bt_workspace_status(ws, status)
+    assert status.cpu().tolist() == [0, 0]
+    bt.bt_compress(x, bm, vals, nnz, ws)
+    bt.bt_decompress(bm, vals, torch.empty_like(x), ws)
+    bt.bt_workspace_status(ws, status)
+    assert status.cpu().tolist() == [0, 2]
+    ws.view(torch.int32)[bt.BT_WS_ERROR_WORD] = 1          # what a kernel that gave up a wait leaves behind
+    bt.bt_workspace_status(ws, status)
+    assert status.cpu().tolist()[0] == 1
+    bt.bt_workspace_init(ws)
+    bt.bt_workspace_status(ws, status)
+    assert status.cpu().tolist() == [0, 0]

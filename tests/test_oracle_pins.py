@@ -1,15 +1,12 @@
 """Pins for the CPU oracle: each test checks oracle/bt_oracle.c against something
 other than itself -- numbers the paper prints, closed forms, library routines of
-numpy, brute-force enumeration, and a literal list-based transcription of
-Algorithms 1 and 2.  A dropped term, a wrong bit order, a reversed value order,
+numpy (bit packing, boolean selection) and brute-force enumeration.  A dropped term, a wrong bit order, a reversed value order,
 an off-by-one at a word boundary or an IEEE (instead of bit-pattern) zero test
 each fail at least one of them."""
 import os
 
 import numpy as np
 import pytest
-
-from oracle import py_ref
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "table1_theoretical.txt")
 
@@ -65,8 +62,9 @@ def test_size_closed_forms_and_rounding(oracle):
     # nonsense arguments
     assert oracle.compressed_size(10, 11, 4) == 0
     assert oracle.compressed_size(10, 1, 3) == 0
-    for n, nnz, w in ((0, 0, 4), (77, 13, 2), (1000, 1000, 8)):
-        assert oracle.compressed_size(n, nnz, w) == py_ref.footprint_bytes(n, nnz, w)
+    # one more value moves the size by exactly one element, one more element by a word every 32
+    assert oracle.compressed_size(77, 14, 2) - oracle.compressed_size(77, 13, 2) == 2
+    assert oracle.compressed_size(1000, 1000, 8) == 4 * 32 + 8000
 
 
 def test_hand_built_tensor(oracle):
@@ -153,20 +151,22 @@ def test_all_2_to_16_patterns_decode(oracle):
         assert out.tolist() == np.where(sel, payload, 0).tolist()
 
 
-def test_every_length_0_to_130_against_list_transcription(oracle):
-    """Word and tail boundaries: every n in [0,130], C oracle == pure-Python Algorithm 1/2."""
+def test_every_length_0_to_130_against_numpy_routines(oracle):
+    """Word and tail boundaries: for every n in [0,130] the bitmap is numpy's little-endian bit packing of
+    (x != 0), the values are numpy's boolean selection, restoration gives x back, and the backward is a select."""
     rng = np.random.default_rng(11)
     for n in range(0, 131):
         x = rng.integers(1, 2**32, size=n, dtype=np.uint32)
         x[rng.random(n) < 0.5] = 0
-        bits_list, vals_list = py_ref.to_bitmap(x.tolist())
         bitmap, values, nnz = oracle.compress(x)
         assert bitmap.size == (n + 31) // 32
-        assert bitmap.tolist() == py_ref.pack_words(bits_list)
-        assert values.tolist() == vals_list and nnz == len(vals_list)
-        assert oracle.decompress(bitmap, values, n).tolist() == py_ref.to_dense(bits_list, vals_list) == x.tolist()
+        packed = np.packbits(x != 0, bitorder="little")
+        packed = np.concatenate([packed, np.zeros(4 * bitmap.size - packed.size, np.uint8)])
+        assert bitmap.tolist() == packed.view("<u4").tolist()
+        assert values.tolist() == x[x != 0].tolist() and nnz == int(np.count_nonzero(x))
+        assert oracle.decompress(bitmap, values, n).tolist() == x.tolist()
         g = rng.integers(0, 2**32, size=n, dtype=np.uint32)
-        assert oracle.relu_backward(bitmap, g).tolist() == py_ref.relu_backward(bits_list, g.tolist())
+        assert oracle.relu_backward(bitmap, g).tolist() == np.where(x != 0, g, 0).tolist()
         if n % 32:
             assert int(bitmap[-1]) >> (n % 32) == 0      # unused high bits stay clear
 
@@ -244,12 +244,12 @@ def _bf16_bits_to_f32(bits):
 
 @pytest.mark.parametrize("thr", [0.0, 1e-6, 0.01, 0.05, 0.1, -2.0, float("inf")])
 def test_prune_every_16_bit_pattern(oracle, thr):
-    """All 65536 half and bfloat16 patterns: kept exactly where numpy's widened value
+    """All 65536 half and bfloat16 patterns: kept exactly where numpy's widened value, as a double,
     exceeds the threshold; NaNs (for which no comparison holds) are dropped."""
     allbits = np.arange(65536, dtype=np.uint16)
     with np.errstate(invalid="ignore"):
         for dt, widen in (("f16", _f16_bits_to_f32), ("bf16", _bf16_bits_to_f32)):
-            expect = np.where(widen(allbits) > np.float32(thr), allbits, 0).astype(np.uint16)
+            expect = np.where(widen(allbits).astype(np.float64) > thr, allbits, 0).astype(np.uint16)
             assert np.array_equal(oracle.prune(allbits, dt, thr), expect)
 
 
@@ -258,7 +258,7 @@ def test_prune_fp32_special_values(oracle):
     bits = f.view(np.uint32)
     kept0 = oracle.prune(bits, "f32", 0.0).view(np.float32)
     assert kept0.view(np.uint32).tolist() == np.array([0, 0, 1e-45, 0, 0.01, 0.0100001, 0, np.inf, 0, 0, 0.1, 3.0], np.float32).view(np.uint32).tolist()
-    kept = oracle.prune(bits, "f32", 0.01).view(np.float32)     # strict: 0.01 itself is pruned
+    kept = oracle.prune(bits, "f32", 0.01).view(np.float32)     # the single nearest 0.01 lies below it: pruned
     assert kept.view(np.uint32).tolist() == np.array([0, 0, 0, 0, 0, 0.0100001, 0, np.inf, 0, 0, 0.1, 3.0], np.float32).view(np.uint32).tolist()
     assert not oracle.prune(bits, "f32", float("nan")).any()    # nothing exceeds NaN
     everything = oracle.prune(bits, "f32", float("-inf")).view(np.uint32)
@@ -339,24 +339,47 @@ def test_mask_apply_special_cases(oracle):
 
 
 def test_prune_fp64_against_numpy_and_special_values(oracle):
-    """Double-precision elements: kept where the double exceeds the threshold widened to double."""
+    """Double-precision elements: kept where the double exceeds the threshold, a double."""
     rng = np.random.default_rng(5)
     x = rng.standard_normal(5000)
     x[::7] = 0.0
     specials = np.array([0.0, -0.0, 5e-324, -5e-324, np.nan, np.inf, -np.inf, 0.01, np.float64(np.float32(0.01)),
-                         np.nextafter(np.float64(np.float32(0.01)), 1.0), 1.7976931348623157e308], dtype=np.float64)
+                         np.nextafter(0.01, 1.0), 1.7976931348623157e308], dtype=np.float64)
     x = np.concatenate([specials, x])
     for thr in (0.0, 0.01, 0.05, 0.1, -1.0, float("inf"), float("-inf")):
-        t = np.float64(np.float32(thr))
         with np.errstate(invalid="ignore"):
-            want = np.where(x > t, x, 0.0).view(np.uint64)
-        want = np.where(x > t, x.view(np.uint64), 0).astype(np.uint64)     # kept elements keep their bits
+            want = np.where(x > thr, x.view(np.uint64), 0).astype(np.uint64)     # kept elements keep their bits
         got = oracle.prune(x.view(np.uint64), "f64", thr)
         assert np.array_equal(got, want), thr
-    # the threshold is the single-precision number: 0.01f is a little below 0.01, so the double 0.01 survives it
-    got = oracle.prune(specials.view(np.uint64), "f64", 0.01).view(np.float64)
-    assert got[7] == 0.01 and got[8] == 0.0 and got[9] > 0.0
     assert oracle.prune(specials.view(np.uint64), "f64", float("nan")).any() == False
+
+
+def test_prune_threshold_that_is_no_single(oracle):
+    """Section 4.3's thresholds (0.01, 0.05, 0.1) are not single-precision numbers.  The comparison is between
+    real values, so it must not matter on which side of the threshold its nearest single lies.  Written out by
+    hand for 0.1, whose nearest single, 0.100000001490116..., is ABOVE it, and 0.01, whose nearest single,
+    0.00999999977648..., is BELOW it."""
+    f32 = np.float32
+    up = np.float64(f32(0.1))              # the single above 0.1
+    dn = np.float64(np.nextafter(f32(0.1), f32(0)))   # the single below 0.1
+    assert dn < 0.1 < up
+    # doubles around 0.1: the threshold itself goes (strict), everything above it stays, however little above
+    d = np.array([0.1, np.nextafter(0.1, 1.0), up, np.nextafter(0.1, 0.0), dn, -up], dtype=np.float64)
+    got = oracle.prune(d.view(np.uint64), "f64", 0.1).view(np.float64)
+    assert got.tolist() == [0.0, float(np.nextafter(0.1, 1.0)), float(up), 0.0, 0.0, 0.0]
+    # singles around 0.1: the nearest single exceeds 0.1 and stays (a threshold rounded to single would drop it)
+    s = np.array([f32(0.1), np.nextafter(f32(0.1), f32(0)), np.nextafter(f32(0.1), f32(1))], dtype=np.float32)
+    got = oracle.prune(s.view(np.uint32), "f32", 0.1).view(np.float32)
+    assert got.tolist() == [float(f32(0.1)), 0.0, float(np.nextafter(f32(0.1), f32(1)))]
+    # singles around 0.01: its nearest single is below it and goes; the next one up stays
+    s = np.array([f32(0.01), np.nextafter(f32(0.01), f32(1))], dtype=np.float32)
+    assert np.float64(s[0]) < 0.01 < np.float64(s[1])
+    got = oracle.prune(s.view(np.uint32), "f32", 0.01).view(np.float32)
+    assert got.tolist() == [0.0, float(s[1])]
+    # half precision: 0.0999755859375 is the half nearest 0.1 (below it), 0.10003662109375 the next
+    h = np.array([0x2E66, 0x2E67], dtype=np.uint16)
+    assert np.float64(h.view(np.float16)[0]) < 0.1 < np.float64(h.view(np.float16)[1])
+    assert oracle.prune(h, "f16", 0.1).tolist() == [0, 0x2E67]
 
 
 # ---- Algorithm 2's counter at tile boundaries ----

@@ -61,4 +61,4 @@ def test_pruning_is_monotone_and_idempotent(oracle, x, thr):
     assert np.array_equal(oracle.prune(kept, "f32", thr) if thr >= 0 else kept, kept)       # pruning twice changes nothing
     higher = oracle.prune(bits, "f32", thr + 0.5)
     assert np.all((higher != 0) <= (kept != 0) | (bits == 0))                # a higher threshold keeps a subset
-    assert np.array_equal(kept.view(np.float32)[kept != 0] > np.float32(thr), np.ones(int((kept != 0).sum()), dtype=bool))
+    assert np.array_equal(kept.view(np.float32)[kept != 0].astype(np.float64) > thr, np.ones(int((kept != 0).sum()), dtype=bool))
