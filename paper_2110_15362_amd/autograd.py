@@ -5,8 +5,8 @@ kept in the bitmap format between the forward and the backward pass.
 Two pieces, both thin: every byte of codec work is done by libbittrain's kernels.
 
 * ``BitmapStash`` -- a ``torch.autograd.graph.saved_tensors_hooks`` context.  Packing a
-  saved activation runs ``bt_compress`` into a reusable worst-case scratch buffer, reads
-  nnz (one host synchronisation per tensor: that is the price of right-sizing) and keeps
+  saved activation runs ``bt_compress_indexed`` into a reusable worst-case scratch buffer, reads
+  nnz and the workspace's status (one host synchronisation per tensor: the price of right-sizing) and keeps
   only ``values[:nnz]`` and the bitmap; if that is not smaller than the dense tensor the
   tensor is kept as it is.  Packing also keeps the tile index (8 bytes per 32 KiB of
   dense data) that compression produces on the way, so unpacking runs
@@ -16,6 +16,8 @@ Two pieces, both thin: every byte of codec work is done by libbittrain's kernels
   ``bt_relu_backward_from_bitmap`` and which saves nothing but the bitmap of its output
   (1/32 of an fp32 activation): compression with a value capacity of 0.
 """
+import warnings
+
 import torch
 
 from . import bittrain as bt
@@ -23,15 +25,18 @@ from . import bittrain as bt
 _SUPPORTED = (torch.float32, torch.float16, torch.bfloat16, torch.float64)
 
 
-class _DeviceState:
-    """Per-device reusable buffers: workspace, worst-case value scratch, nnz scalar."""
+class _StreamState:
+    """Reusable buffers of one (device, stream): workspace, worst-case value scratch, and the words
+    read back after a compression (nnz, then the workspace's status).  Work on different streams must
+    not share them: a workspace serves one call at a time."""
 
     def __init__(self, device):
         self.device = device
         self.ws = None
-        self.ws_elems = {}
         self.scratch = {}
-        self.nnz = torch.zeros(1, dtype=torch.int64, device=device)
+        self.result = torch.zeros(2, dtype=torch.int64, device=device)      # [0]: nnz; [1]: two status words
+        self.nnz = self.result[:1]
+        self.status = self.result[1:].view(torch.int32)
 
     def workspace(self, n, dtype):
         need = bt.bt_workspace_bytes(n, dtype)
@@ -52,9 +57,10 @@ _states = {}
 
 
 def _state(device):
-    st = _states.get(device)
+    key = (device, torch.cuda.current_stream(device).cuda_stream)
+    st = _states.get(key)
     if st is None:
-        st = _states[device] = _DeviceState(device)
+        st = _states[key] = _StreamState(device)
     return st
 
 
@@ -75,22 +81,32 @@ class BitmapStash(torch.autograd.graph.saved_tensors_hooks):
 
     def __init__(self, min_numel=4096):
         self.min_numel = min_numel
-        self.stats = {"tensors": 0, "compressed": 0, "dense_bytes": 0, "stored_bytes": 0}
+        self.stats = {"tensors": 0, "compressed": 0, "failed": 0, "dense_bytes": 0, "stored_bytes": 0}
         super().__init__(self._pack, self._unpack)
 
     def _pack(self, t):
         if (not t.is_cuda or t.dtype not in _SUPPORTED or t.numel() < self.min_numel or not t.is_contiguous()
-                or isinstance(t, torch.nn.Parameter)):
-            return t
+                or isinstance(t, torch.nn.Parameter) or t.data_ptr() % 16 != 0):
+            return t                      # (a view that starts off a 16-byte boundary is not what the library takes)
         st = _state(t.device)
         n = t.numel()
         self.stats["tensors"] += 1
         self.stats["dense_bytes"] += n * t.element_size()
-        bitmap = torch.empty((n + 31) // 32, dtype=torch.int32, device=t.device)
+        bitmap = torch.empty(bt.bt_bitmap_bytes(n) // 4, dtype=torch.int32, device=t.device)
         index = torch.empty(bt.bt_index_bytes(n, t.dtype) // 8, dtype=torch.int64, device=t.device)
         scratch = st.value_scratch(n, t.dtype)
-        bt.bt_compress_indexed(t.detach(), bitmap, scratch, st.nnz, index, st.workspace(n, t.dtype))
-        nnz = int(st.nnz.item())                                   # host sync: needed to right-size
+        ws = st.workspace(n, t.dtype)
+        bt.bt_compress_indexed(t.detach(), bitmap, scratch, st.nnz, index, ws)
+        bt.bt_workspace_status(ws, st.status)
+        result = st.result.cpu()                                   # host sync: nnz is needed to right-size
+        nnz, gave_up = int(result[0]), int(result[1:].view(torch.int32)[0])
+        if gave_up:
+            # a kernel gave up a wait: what it wrote is not valid.  Keep the tensor as it is, make the workspace usable again
+            self.stats["failed"] += 1
+            bt.bt_workspace_init(ws)
+            warnings.warn("BitmapStash: a compression gave up a wait; the tensor is kept dense")
+            self.stats["stored_bytes"] += n * t.element_size()
+            return t
         stored = bt.bt_compressed_size(n, nnz, t.dtype) + 8 * index.numel()    # M_b plus the tile index
         if stored >= n * t.element_size():
             self.stats["stored_bytes"] += n * t.element_size()
@@ -114,7 +130,7 @@ class _BitmapReLU(torch.autograd.Function):
             raise TypeError("bitmap_relu needs a contiguous float64/float32/float16/bfloat16 device tensor")
         st = _state(x.device)
         n = x.numel()
-        bitmap = torch.empty((n + 31) // 32, dtype=torch.int32, device=x.device)
+        bitmap = torch.empty(bt.bt_bitmap_bytes(n) // 4, dtype=torch.int32, device=x.device)
         empty = torch.empty(0, dtype=x.dtype, device=x.device)
         # capacity 0: only the bitmap (and nnz) are produced, no value is written
         if fused:

@@ -36,5 +36,9 @@ def sweep(shape, fractions=(0.0, 0.25, 0.5, 0.75, 1.0), dtype=torch.float32):
 def break_even_nonzero_fraction(ndim, index_bytes, dtype=torch.float32):
     """Largest non-zero fraction at which COO is no larger than dense, and the one at which
     the bitmap format is no larger than dense (31/32 for fp32)."""
-    s = bt.bt_dense_size(1, dtype)
-    return {"coo_vs_dense": s / (s + index_bytes * ndim), "bitmap_vs_dense": 1.0 - 1.0 / (8 * s)}
+    # per element: dense bytes, bytes of a COO entry, bitmap bytes and bytes of a stored value, all from the library
+    dense32 = bt.bt_dense_size(32, dtype)
+    coo_entry = bt.bt_coo_size(1, ndim, index_bytes, dtype)
+    bitmap32 = bt.bt_compressed_size(32, 0, dtype)
+    value = bt.bt_compressed_size(32, 1, dtype) - bitmap32
+    return {"coo_vs_dense": (dense32 / 32) / coo_entry, "bitmap_vs_dense": (dense32 - bitmap32) / (32 * value)}
