@@ -55,8 +55,10 @@ def parse():
                     help="skip the same-buffer (warm) timings, so that a profiler's per-kernel average is the cold one")
     ap.add_argument("--no-step", action="store_true",
                     help="skip the combined-step loop (in it decompress reads what compress just wrote, i.e. warm data)")
-    ap.add_argument("--all-configs", action="store_true",
-                    help="also time configurations 1, 3, 4 and 5 (adds about a minute; reported under `other_configs`)")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip configurations 1, 3, 4 and 5 and the added rows (they take about a minute; reported under "
+                         "`other_configs`)")
+    ap.add_argument("--all-configs", action="store_true", help="accepted for compatibility: the other configurations are on by default")
     ap.add_argument("--timeline", action="store_true",
                     help="instead of timing: one cold bt_compress and bt_decompress of configuration 2 (50 %% zeros) with the "
                          "instrumented build of the library, per-tile time stamps printed as a markdown table")
@@ -296,6 +298,66 @@ def other_configs(bt, wl, torch, dev, timed, args):
                  "batched_compress_roofline_frac": round(alg / tfb / 1e3 / HBM_PEAK_GBPS, 4),
                  "batched_decompress_roofline_frac": round(alg / tbb / 1e3 / HBM_PEAK_GBPS, 4),
                  "note": "5 GB working set: every tensor is cold when its turn comes"})
+    # the same set through the tile indexes: batched compression that also writes them, batched restoration from them
+    indexes = [torch.empty(bt.bt_index_bytes(n, torch.float32) // 8, dtype=torch.int64, device=dev) for n in ns]
+    ci_items = bt.compress_items(xs, [b for b, _, _ in stash], [v for _, v, _ in stash], nnz_all, indexes=indexes)
+    di_items = bt.decompress_items([b for b, _, _ in stash], [v for _, v, _ in stash], outs, indexes=indexes)
+    tci = timed(lambda i: bt.bt_compress_batch(ci_items, len(xs), torch.float32, wsb), 5, 1)
+    tdi = timed(lambda i: bt.bt_decompress_batch_indexed(di_items, len(xs), torch.float32), 5, 1)
+    assert all(torch.equal(o.view(torch.int32), xd.view(torch.int32)) for o, xd in zip(outs, xs)), "round trip mismatch (indexed batch)"
+    # and the activation batch: prune at 0.05, dense pruned tensors written in place, compressed form beside them
+    act_items = bt.compress_items(xs, [b for b, _, _ in stash], [v for _, v, _ in stash], nnz_all, dense_outs=xs)
+    tact = timed(lambda i: bt.bt_compress_batch_pruned(act_items, len(xs), torch.float32, 0.05, wsb), 5, 1)
+    torch.cuda.synchronize()
+    kept = int(nnz_all.sum().item())
+    alg_act = 2 * dense_bytes + dense_bytes // 32 + 4 * kept
+    rows.append({"config": "4 again: tile indexes (batched), and the pruning batch with dense outputs (threshold 0.05, in place)",
+                 "batched_compress_with_index_us": round(tci, 1), "batched_decompress_indexed_us": round(tdi, 1),
+                 "batched_compress_with_index_roofline_frac": round(alg / tci / 1e3 / HBM_PEAK_GBPS, 4),
+                 "batched_decompress_indexed_roofline_frac": round(alg / tdi / 1e3 / HBM_PEAK_GBPS, 4),
+                 "activation_batch_us": round(tact, 1), "activation_batch_zero_fraction": round(1 - kept / (dense_bytes // 4), 4),
+                 "activation_batch_roofline_frac": round(alg_act / tact / 1e3 / HBM_PEAK_GBPS, 4)})
+    del xs, stash, outs, indexes
+
+    # the codec inside a training step: 16 ReLU layers whose saved activations are 32 MiB each, with and without the stash
+    import contextlib
+    from paper_2110_15362_amd import autograd as ag
+    layers, batch, hidden = 16, 8192, 1024
+    g = torch.Generator(device=dev).manual_seed(0)
+    weights = [(torch.randn(hidden, hidden, device=dev, generator=g) / hidden ** 0.5).requires_grad_() for _ in range(layers)]
+    x0 = torch.randn(batch, hidden, device=dev, generator=g)
+
+    def mlp_step(stash_on):
+        ctx = ag.BitmapStash(deferred=stash_on == "deferred") if stash_on else contextlib.nullcontext()
+        with ctx:
+            y = x0
+            for w in weights:
+                y = ag.bitmap_relu(y @ w) if stash_on else torch.relu(y @ w)
+            loss = y.sum()
+        loss.backward()
+        return ctx
+
+    res = {}
+    for stash_on in (False, True, "deferred"):
+        for _ in range(3):
+            ctx = mlp_step(stash_on)
+        torch.cuda.synchronize()
+        torch.cuda.reset_peak_memory_stats()
+        before = torch.cuda.memory_allocated()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            ctx = mlp_step(stash_on)
+        torch.cuda.synchronize()
+        res[stash_on] = ((time.perf_counter() - t0) / 10 * 1e3, (torch.cuda.max_memory_allocated() - before) / 2**20,
+                         ctx.stats if stash_on else None)
+    rows.append({"config": "autograd stash: 16 x (matmul 8192x1024x1024 fp32 + ReLU), forward + backward, host clock",
+                 "step_ms_without_stash": round(res[False][0], 2), "step_ms_with_stash": round(res[True][0], 2),
+                 "step_ms_with_deferred_stash": round(res["deferred"][0], 2),
+                 "peak_MiB_without_stash": round(res[False][1]), "peak_MiB_with_stash": round(res[True][1]),
+                 "peak_MiB_with_deferred_stash": round(res["deferred"][1]),
+                 "saved_dense_MiB": round(res[True][2]["dense_bytes"] / 2**20), "saved_stored_MiB": round(res[True][2]["stored_bytes"] / 2**20),
+                 "note": "packing reads nnz and the workspace status back to right-size the value buffer: one host synchronisation per saved "
+                         "tensor; the deferred stash lets them arrive behind an event and cuts the buffer to size later"})
     return rows
 
 
@@ -454,7 +516,7 @@ def main():
         del xs, gs, bitmaps, values, outs, gins, indexes
 
     other = None
-    if args.all_configs:
+    if not args.no_other_configs:
         other = other_configs(bt, wl, torch, dev, timed, args)
 
     n, s, row = headline["n"], headline["s"], headline["row"]
@@ -464,6 +526,14 @@ def main():
     achieved = row[dom]["algorithmic_bytes"] / row[dom]["us_cold"] / 1e3
     roofline = {"bound": "hbm", "kernel": {"compress": "compress_kernel<4, 0, false>", "decompress": "decompress_kernel<4>"}[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(dom),
+                "traffic_source": (None if measured_traffic(dom) is None else
+                                   "profiles/hbm_traffic_config2_z50.txt: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE of this "
+                                   "kernel on this workload, each scaled by the same counter's reading for a plain copy of "
+                                   "known size (a committed summary, not measured by this run)"),
+                "north_star": {"target_frac": 0.70, "what": "bt_compress and bt_decompress on configuration 2 at 50 % zeros, cold",
+                               "compress_frac": row["compress"]["roofline_frac_cold"],
+                               "decompress_frac": row["decompress"]["roofline_frac_cold"],
+                               "met": bool(min(row["compress"]["roofline_frac_cold"], row["decompress"]["roofline_frac_cold"]) >= 0.70)},
                 "algorithmic_bytes_per_launch": row[dom]["algorithmic_bytes"],
                 "avg_launch_us": row[dom]["us_cold"], "cache": "cold (8 rotating buffer sets)",
                 "frac_warm": row[dom]["roofline_frac_warm"], "stream_ceiling": headline["stream_ceiling"]}
@@ -482,7 +552,15 @@ def main():
             t.append(time.perf_counter() - t0)
         assert o_nnz == headline["nnz"]
         med = sorted(t)[len(t) // 2]
-        cpu = {"value": round(3 * n * s / med / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        cpu_model = None
+        try:
+            for line in open("/proc/cpuinfo"):
+                if line.lower().startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+        except OSError:
+            pass
+        cpu = {"value": round(3 * n * s / med / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle", "cpu_model": cpu_model,
                "host_cores_available": os.cpu_count(), "seconds_per_step": round(med, 3),
                "sample": "the full config-2 tensor at 50 %% sparsity (%d elements), %d repetitions (%.0f s of CPU work), median"
                          % (n, len(t), sum(t))}

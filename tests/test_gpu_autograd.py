@@ -63,7 +63,7 @@ def test_bitmap_relu_backward_matches_torch(ag, dtype, fused):
         assert torch.equal(r, t.grad)
 
 
-def _relu_mlp_step(ag, stash, layers, batch, hidden, seed=0):
+def _relu_mlp_step(ag, stash, layers, batch, hidden, seed=0, deferred=False):
     """Forward and backward of y = relu(... relu(x W_0) ... W_{L-1}), sum as loss.  Returns the gradients, the
     peak of allocated device memory above what was allocated before the step, and the stash's counters."""
     import contextlib
@@ -73,7 +73,7 @@ def _relu_mlp_step(ag, stash, layers, batch, hidden, seed=0):
     torch.cuda.synchronize()
     torch.cuda.reset_peak_memory_stats()
     before = torch.cuda.memory_allocated()
-    ctx = ag.BitmapStash() if stash else contextlib.nullcontext()
+    ctx = ag.BitmapStash(deferred=deferred) if stash else contextlib.nullcontext()
     with ctx:
         y = x
         for w in ws:
@@ -98,3 +98,13 @@ def test_stash_lowers_peak_memory_of_a_step(ag):
         assert torch.equal(a.view(torch.int32), b.view(torch.int32))
     print("peak MiB without / with the stash: %.0f / %.0f; stored %.0f of %.0f MiB" % (
         peak_off / 2**20, peak_on / 2**20, stats["stored_bytes"] / 2**20, stats["dense_bytes"] / 2**20))
+
+
+def test_deferred_stash_gives_the_same_gradients_without_waiting_for_the_device(ag):
+    layers, batch, hidden = 8, 4096, 1024
+    grads_off, peak_off, _ = _relu_mlp_step(ag, False, layers, batch, hidden, seed=3)
+    grads_on, peak_on, stats = _relu_mlp_step(ag, True, layers, batch, hidden, seed=3, deferred=True)
+    assert stats["tensors"] >= layers and stats["compressed"] >= layers - 1 and stats["failed"] == 0
+    assert stats["stored_bytes"] < 0.75 * stats["dense_bytes"]        # (the dense input and the weights pass through too)
+    for a, b in zip(grads_on, grads_off):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32))
