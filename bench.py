@@ -524,7 +524,7 @@ def main():
     # dominant kernel of the step: the slower of the two codec kernels (the ReLU kernel is a plain stream)
     dom = max(("compress", "decompress"), key=lambda k: row[k]["us_cold"])
     achieved = row[dom]["algorithmic_bytes"] / row[dom]["us_cold"] / 1e3
-    roofline = {"bound": "hbm", "kernel": {"compress": "compress_kernel<4, 0, false>", "decompress": "decompress_kernel<4>"}[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+    roofline = {"bound": "hbm", "kernel": {"compress": "compress_kernel<4, 0, false, CompressOne>", "decompress": "decompress_kernel<4, DecompressOne>"}[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(dom),
                 "traffic_source": (None if measured_traffic(dom) is None else
                                    "profiles/hbm_traffic_config2_z50.txt: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE of this "

@@ -100,16 +100,23 @@ const char *bt_status_str(bt_status status);
  *   BT_WS_ERROR_WORD        0 in normal operation.  Every wait inside the kernels (a tile
  *                           waiting for the grid scan, the scan waiting for a tile) is
  *                           bounded; a kernel whose wait ran out sets this word to 1 and
- *                           ends normally, staying inside all buffers.  The outputs of that
+ *                           ends normally, staying inside all buffers (read it with
+ *                           bt_workspace_status).  The outputs of that
  *                           call are undefined, and later calls on the workspace write
  *                           nothing at all, until bt_workspace_init has been run on it again.
  *   BT_WS_WAIT_LIMIT_WORD   polls after which a wait is given up; 0 (the initial state)
  *                           means the built-in limit of 2^20 polls, far beyond what any
  *                           tensor needs.  Written by the caller only (a device-side store
  *                           or copy ordered before the call); meant for tests of the
- *                           failure path. */
+ *                           failure path.
+ *   BT_WS_PATIENCE_WORD     bt_decompress and bt_decompress_batch only: polls after which a
+ *                           workgroup stops waiting for the grid scan and counts the set bits
+ *                           before its tile itself (correct, only slower); 0 means the
+ *                           built-in 4096.  Written by the caller only, like the wait limit;
+ *                           meant for tests of that path. */
 #define BT_WS_ERROR_WORD 2
 #define BT_WS_WAIT_LIMIT_WORD 3
+#define BT_WS_PATIENCE_WORD 4
 
 /* Put a workspace into its initial state (all zero bytes) by enqueueing a fill
  * kernel on `stream`.  Required once after allocating a workspace, before its

@@ -78,6 +78,7 @@ constexpr int kHdrSeq = 0;       // calls completed on this workspace; its low b
 constexpr int kHdrPrevTiles = 1; // slots of the previous call (what it left behind in the other copy)
 constexpr int kHdrError = BT_WS_ERROR_WORD;           // set if a wait was given up
 constexpr int kHdrSpinLimit = BT_WS_WAIT_LIMIT_WORD;  // polls before a wait is given up; 0: kSpinLimit
+constexpr int kHdrPatience = BT_WS_PATIENCE_WORD;     // polls before a restoring workgroup counts for itself; 0: kPatience
 constexpr size_t kHeaderBytes = 256;
 constexpr size_t kHdrSpare = 128;      // bytes [128, 256) of the header take stores that mean nothing (see the scanner)
 // Block of 256 slots, two copies c = 0, 1 of everything:
@@ -1235,6 +1236,7 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
                 // every element is written, a dropped one to a place nobody reads: a select on the address
                 // instead of a branch around the write keeps the execution mask alone
                 const int data_rel = (int)(start + kVecBytes) - kRingBytes - lane * S;   // of the entry's first value, from this lane's spare place
+#define BT_SCATTER(T, v) (*reinterpret_cast<T *>(dump + __mul24(keep, rb)) = (v))
                 uint32_t row_start = 0;
 #pragma unroll
                 for (int k = r0; k < r0 + kPhaseRows; ++k) {
@@ -1245,21 +1247,21 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
 #pragma unroll
                         for (int j = 0; j < 2; ++j) {
                             const int keep = (int)((mk >> j) & 1u);
-                            *reinterpret_cast<uint64_t *>(dump + __mul24(keep, rb)) = ((uint64_t)d[2 * j + 1] << 32) | d[2 * j];
+                            BT_SCATTER(uint64_t, ((uint64_t)d[2 * j + 1] << 32) | d[2 * j]);
                             rb += keep * S;
                         }
                     } else if (S == 4) {
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
                             const int keep = (int)((mk >> j) & 1u);
-                            *reinterpret_cast<uint32_t *>(dump + __mul24(keep, rb)) = d[j];
+                            BT_SCATTER(uint32_t, d[j]);
                             rb += keep * S;
                         }
                     } else {
 #pragma unroll
                         for (int j = 0; j < 8; ++j) {
                             const int keep = (int)((mk >> j) & 1u);
-                            *reinterpret_cast<uint16_t *>(dump + __mul24(keep, rb)) = (uint16_t)(d[j >> 1] >> (16 * (j & 1)));
+                            BT_SCATTER(uint16_t, (uint16_t)(d[j >> 1] >> (16 * (j & 1))));
                             rb += keep * S;
                         }
                     }
@@ -1493,17 +1495,16 @@ template <int S> struct Restoring {            // a quarter tile between restore
     uint32_t pads[kRows / kPhaseRows], cnts[kRows / kPhaseRows];
 };
 
+// (1) this lane's bits of the bitmap (G lanes read the same word and take E bits each), and Algorithm 2's
+//     counter j as ranks.  Returns the set bits of this wave's quarter of the tile.
 template <int S>
-__device__ __forceinline__ void restore_fetch(const uint32_t (&rows)[kRows], const void *__restrict__ values, const uint64_t values_cap,
-                                              const uint64_t n, const uint32_t tile, const uint64_t tile_j,
-                                              const uint32_t before_wave, const int lane, const int wave, Restoring<S> &r) {
+__device__ __forceinline__ uint32_t restore_ranks(const uint32_t (&rows)[kRows], const uint64_t n, const uint32_t tile, const int lane,
+                                                  const int wave, Restoring<S> &r) {
     using G = Geo<S>;
     constexpr int E = G::E;
     const uint64_t n_words = (n + 31) >> 5;
     const uint64_t wave_e0 = (uint64_t)tile * G::TILE + (uint64_t)wave * G::WAVE;
     const bool full = (uint64_t)(tile + 1) * G::TILE <= n;
-    // (1) this lane's bits of the bitmap (G lanes read the same word and take E bits each), and Algorithm 2's
-    //     counter j as ranks
 #pragma unroll
     for (int i = 0; i < G::MW; ++i) r.mp[i] = 0;
 #pragma unroll
@@ -1517,7 +1518,16 @@ __device__ __forceinline__ void restore_fetch(const uint32_t (&rows)[kRows], con
         r.mp[k / G::RPM] |= m << (E * (k % G::RPM));
     }
     rank_rows<S>(r.mp, r.rank2, r.total2);
-    // (2) ask for the values of every phase (kPhaseRows rows each), so that all of them are in flight together
+    uint32_t wave_total = 0;
+#pragma unroll
+    for (int k = 0; k < kRows; ++k) wave_total += BT_FIELD(r.total2, k);
+    return wave_total;
+}
+
+// (2) ask for the values of every phase (kPhaseRows rows each), so that all of them are in flight together
+template <int S>
+__device__ __forceinline__ void restore_fetch(const void *__restrict__ values, const uint64_t values_cap, const uint64_t tile_j,
+                                              const uint32_t before_wave, const int lane, Restoring<S> &r) {
     uint64_t g0 = tile_j + before_wave;                                   // Algorithm 2's j for this wave
 #pragma unroll
     for (int ph = 0; ph < kRows / kPhaseRows; ++ph) {
@@ -1611,11 +1621,10 @@ __device__ __noinline__ uint64_t prefix_from_bitmap(const uint32_t *__restrict__
 }
 
 // bt_decompress and bt_decompress_batch: workgroup 0 is the scanner (one wave of it), workgroup 1 + t
-// restores slot t.  A tile's count depends on the bitmap alone: every wave counts the tile from the
-// bitmap words (so the waves need not talk to each other about it), the workgroup publishes the
-// count, and while the scanner is at work each wave turns its words into masks and ranks; then the
-// first wave waits for the tile's prefix, every wave fetches its values, expands and stores them, and
-// the workgroup ends.
+// restores slot t.  A tile's count depends on the bitmap alone: every wave turns its bitmap words into
+// masks and ranks, whose totals are the wave's share of the count; the workgroup adds the shares up
+// and publishes the count; then the first wave waits for the tile's prefix, every wave fetches its
+// values, expands and stores them, and the workgroup ends.
 //
 // Why a workgroup per tile and no loop over tiles as in compression.  A wave that has issued its stores
 // is gone (nothing waits for them to land) and the next workgroup takes its place, whereas a wave that
@@ -1632,6 +1641,7 @@ __global__ __launch_bounds__(kBlock, kDecompressOcc) void decompress_kernel(cons
     using G = Geo<S>;
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * G::LDS_WAVE];
     __shared__ uint64_t s_tile_j;
+    __shared__ uint32_t s_wave_total[kWaves];
     if (workspace_failed(ws)) return;
     if (blockIdx.x == 0) {
         if (threadIdx.x < kWaveSize) scan_counts_rows(ws, job);
@@ -1644,19 +1654,29 @@ __global__ __launch_bounds__(kBlock, kDecompressOcc) void decompress_kernel(cons
     const uint32_t slot = blockIdx.x - 1, n_slots = gridDim.x - 1;
     uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
     const Slot sl = job.at(slot);
-    const uint64_t n = sl.idle ? 0 : job.n(sl.item);
-    const uint32_t *const bitmap = sl.idle ? nullptr : job.bitmap(sl.item);
     // the bitmap words first: everything else waits for them
-    Ahead<S> ahead;
-    ahead_load<S>(bitmap, n, sl.tile, lane, wave, reinterpret_cast<const uint32_t *>(ws + kHdrSpare), ahead);
+    const uint32_t *const bitmap = sl.idle ? nullptr : job.bitmap(sl.item);
+    const uint64_t n = sl.idle ? 0 : job.n(sl.item);
+    uint32_t rows[kRows];
+    rows_load<S>(bitmap, n, sl.tile, lane, wave, reinterpret_cast<const uint32_t *>(ws + kHdrSpare), rows);
     BT_TL(slot, 0);
     const Epoch ep = read_epoch(ws);
     const uint32_t cur = uniform32(ep.cur);      // (the wave has the header's words from here on)
     const uint32_t prev_slots = uniform32(ep.prev_slots);
-    const uint32_t limit = wait_limit(hdr);
+    const uint32_t asked_patience = hdr[kHdrPatience];          // never written by a kernel
+    const uint32_t patience = asked_patience != 0 ? asked_patience : kPatience;
+    // masks and ranks; what they add up to is this wave's share of the tile's count
+    Restoring<S> r;
+    const uint32_t wave_total = sl.idle ? 0u : restore_ranks<S>(rows, n, sl.tile, lane, wave, r);
+    if (lane == 0) s_wave_total[wave] = wave_total;
+    lds_barrier();                      // also: every wave has read the header before the first wave publishes anything
     uint32_t before_wave = 0, tile_total = 0;
-    if (!sl.idle) tile_total = count_words<S>(ahead.mine, n, sl.tile, lane, wave, before_wave);
-    __syncthreads();                    // every wave has read the header before the first wave publishes anything
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t c = s_wave_total[w];
+        if (w < wave) before_wave += c;
+        tile_total += c;
+    }
     if (tid == 0) ws_store32(ws_count(ws, slot, cur), tile_total + 1);
     BT_TL(slot, 1);
     zero_previous(ws, Epoch{cur, prev_slots}, slot, n_slots);
@@ -1665,7 +1685,6 @@ __global__ __launch_bounds__(kBlock, kDecompressOcc) void decompress_kernel(cons
     // traffic on the workspace's few lines low) and passes the answer on through LDS
     uint32_t polls = 0;
     if (wave == 0) {
-        const uint32_t patience = limit < kPatience ? limit : kPatience;
         uint64_t v;
         for (;;) {
             v = uniform64(ws_load64(ws_prefix(ws, slot, cur)));
@@ -1679,8 +1698,7 @@ __global__ __launch_bounds__(kBlock, kDecompressOcc) void decompress_kernel(cons
     lds_barrier();
     const uint64_t tile_j = uniform64(s_tile_j);
     BT_TL(slot, 2);
-    Restoring<S> r;
-    restore_fetch<S>(ahead.rows, job.values(sl.item), job.cap(sl.item), n, sl.tile, tile_j, before_wave, lane, wave, r);
+    restore_fetch<S>(job.values(sl.item), job.cap(sl.item), tile_j, before_wave, lane, r);
     restore_store<S>(r, n, job.out(sl.item), sl.tile, s_stage + wave * G::LDS_WAVE, lane, wave);
     BT_TL(slot, 3);
     BT_TL_VALUE(slot, 5, polls);
@@ -1704,7 +1722,8 @@ __global__ __launch_bounds__(kBlock, 8) void decompress_indexed_kernel(const Job
     uint32_t before_wave;
     count_words<S>(ahead.mine, n, sl.tile, lane, wave, before_wave);
     Restoring<S> r;
-    restore_fetch<S>(ahead.rows, job.values(sl.item), job.cap(sl.item), n, sl.tile, tile_j, before_wave, lane, wave, r);
+    restore_ranks<S>(ahead.rows, n, sl.tile, lane, wave, r);
+    restore_fetch<S>(job.values(sl.item), job.cap(sl.item), tile_j, before_wave, lane, r);
     restore_store<S>(r, n, job.out(sl.item), sl.tile, s_stage + wave * G::LDS_WAVE, lane, wave);
 }
 

@@ -362,20 +362,51 @@ def test_a_wait_that_runs_out_ends_the_kernel_and_raises_the_flag(gpu, oracle):
     x = wl.random_sparse(n, "f32", 0.5, seed=31337)
     ws = bt.new_workspace(n, torch.float32)
     words = ws.view(torch.int32)
-    words[3] = 1                                   # BT_WS_WAIT_LIMIT_WORD: one poll
+    words[bt.BT_WS_WAIT_LIMIT_WORD] = 1            # one poll
     bitmap, values, nnz, tail_ok = gpu.gpu_compress(x, ws=ws)          # synchronises; returns at all
     assert tail_ok, "wrote outside bitmap[0,W) or values[0,min(nnz,cap))"
-    assert int(words[2].item()) == 1               # BT_WS_ERROR_WORD
+    assert int(words[bt.BT_WS_ERROR_WORD].item()) == 1
+    status = torch.zeros(2, dtype=torch.int32, device="cuda")
+    bt.bt_workspace_status(ws, status)
+    assert int(status[0].item()) == 1
     o_bitmap, o_values, o_nnz = oracle.compress(wl.bits(x))
     # a later call on the failed workspace writes nothing: the output keeps the test's fill pattern
     out, guard_ok = gpu.gpu_decompress(o_bitmap, o_values, n, torch.float32, ws=ws)
-    assert guard_ok and int(words[2].item()) == 1
+    assert guard_ok and int(words[bt.BT_WS_ERROR_WORD].item()) == 1
     assert (out == 0x5A5A5A5A).all()
+    # whatever a failing call reports as nnz, nothing at or beyond the capacity is written
     bt.bt_workspace_init(ws)
-    assert int(words[2].item()) == 0 and int(words[3].item()) == 0
+    words[bt.BT_WS_WAIT_LIMIT_WORD] = 1
+    cap, guard = n // 8, 4096
+    xd = x.cuda()
+    vbuf = torch.full((cap + guard,), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+    bm = torch.empty((n + 31) // 32, dtype=torch.int32, device="cuda")
+    nnz_d = torch.zeros(1, dtype=torch.int64, device="cuda")
+    bt.bt_compress(xd, bm, vbuf[:cap].view(torch.float32), nnz_d, ws)
+    torch.cuda.synchronize()
+    assert bool((vbuf[cap:] == 0x5A5A5A5A).all()), "wrote at or beyond the capacity"
+    bt.bt_workspace_init(ws)
+    assert int(words[bt.BT_WS_ERROR_WORD].item()) == 0 and int(words[bt.BT_WS_WAIT_LIMIT_WORD].item()) == 0
     _check_compress(gpu, oracle, x, ws=ws)
     _check_decompress(gpu, oracle, o_bitmap, o_values, n, x.dtype, wl.bits(x), ws=ws)
-    assert int(words[2].item()) == 0
+    assert int(words[bt.BT_WS_ERROR_WORD].item()) == 0
+
+
+@pytest.mark.parametrize("dt", DTYPES)
+def test_restoration_that_stops_waiting_counts_the_bitmap_itself(gpu, oracle, dt):
+    """Forced from the host: with the patience word at one poll a restoring workgroup does not wait for the scanner
+    but counts the set bits before its tile itself.  The output must be right all the same, and nothing has failed."""
+    import paper_2110_15362_amd.bittrain as bt
+    n = 150 * bt.bt_tile_elems(wl.DTYPES[dt]) + 4321
+    x = wl.random_sparse(n, dt, 0.6, seed=99)
+    o_bitmap, o_values, o_nnz = oracle.compress(wl.bits(x))
+    ws = bt.new_workspace(n, x.dtype)
+    ws.view(torch.int32)[bt.BT_WS_PATIENCE_WORD] = 1
+    for _ in range(2):
+        out, guard_ok = gpu.gpu_decompress(o_bitmap, o_values, n, x.dtype, ws=ws)
+        assert guard_ok
+        assert np.array_equal(out, wl.bits(x))
+    assert int(ws.view(torch.int32)[bt.BT_WS_ERROR_WORD].item()) == 0
 
 
 def test_stream_probe_stays_inside_its_buffers(gpu):
