@@ -95,15 +95,15 @@ uint64_t bt_oracle_compress(const void *T, uint64_t n, int width,
     uint64_t words = n / 32 + (n % 32 != 0);
     for (uint64_t w = 0; w < words; ++w) bitmap[w] = 0;
 
-    uint64_t j = 0;                          /* length of B.values so far */
+    uint64_t j = 0;                          /* values stored so far */
     for (uint64_t i = 0; i < n; ++i) {
         uint64_t bits = load_bits(t, i, width);
         if (bits == 0) {
-            /* push a 0 bit: the word was cleared above */
+            /* a zero element: its bit stays clear (the word was cleared above) */
         } else {
-            store_bits(vals, j, width, bits);             /* push T[i] to B.values */
+            store_bits(vals, j, width, bits);             /* a non-zero element is appended to the values */
             j += 1;
-            bitmap[i / 32] |= (uint32_t)1 << (i % 32);    /* push a 1 bit */
+            bitmap[i / 32] |= (uint32_t)1 << (i % 32);    /* and its bit is set */
         }
     }
     return j;

@@ -169,7 +169,7 @@ __device__ __forceinline__ void wave_lds_sync() {
 //   decompress  plain 35.6/27.6   nt loads 36.3/32.8   nt stores 34.4/27.3   both 35.0/34.2
 //   relu bwd    plain 37.2        nt loads 36.6        nt stores 35.4        both 34.7
 // so compress and the ReLU stream use both hints (their input is dead after the call:
-// "delete T" in Algorithm 1), decompress only the store hint.
+// Algorithm 1 ends by giving the dense tensor up), decompress only the store hint.
 typedef uint32_t bt_u4 __attribute__((ext_vector_type(4)));
 template <bool NT> __device__ __forceinline__ uint4 stream_load(const uint4 *p) {
     if (NT) {
