@@ -97,23 +97,23 @@ const char *bt_status_str(bt_status status);
 /* ---- device calls -------------------------------------------------------- */
 
 /* What a caller may look at, or set, in a workspace: 32-bit words at the start of it.
- *   BT_WS_ERROR_WORD        0 in normal operation.  Every wait inside the kernels (a tile
- *                           waiting for the grid scan, the scan waiting for a tile) is
+ *   BT_WS_ERROR_WORD        0 in normal operation.  The one wait inside the kernels that can
+ *                           fail, the grid scan waiting for the counts of a call's tiles, is
  *                           bounded; a kernel whose wait ran out sets this word to 1 and
  *                           ends normally, staying inside all buffers (read it with
- *                           bt_workspace_status).  The outputs of that
- *                           call are undefined, and later calls on the workspace write
- *                           nothing at all, until bt_workspace_init has been run on it again.
- *   BT_WS_WAIT_LIMIT_WORD   polls after which a wait is given up; 0 (the initial state)
- *                           means the built-in limit of 2^20 polls, far beyond what any
+ *                           bt_workspace_status).  The outputs of that call are not valid (nnz
+ *                           in particular is not written), and later calls on the workspace
+ *                           write nothing at all, until bt_workspace_init has been run on it again.
+ *   BT_WS_WAIT_LIMIT_WORD   passes of the grid scan after which it gives up; 0 (the initial
+ *                           state) means the built-in limit of 2^20, far beyond what any
  *                           tensor needs.  Written by the caller only (a device-side store
  *                           or copy ordered before the call); meant for tests of the
  *                           failure path.
- *   BT_WS_PATIENCE_WORD     bt_decompress and bt_decompress_batch only: polls after which a
- *                           workgroup stops waiting for the grid scan and counts the set bits
- *                           before its tile itself (correct, only slower); 0 means the
- *                           built-in 4096.  Written by the caller only, like the wait limit;
- *                           meant for tests of that path. */
+ *   BT_WS_PATIENCE_WORD     polls after which a tile's workgroup stops waiting for the grid
+ *                           scan and counts what lies before its tile itself, from the
+ *                           bitmap (restoration) or the input (compression): correct, only
+ *                           slower; 0 means the built-in 4096.  Written by the caller only,
+ *                           like the wait limit; meant for tests of that path. */
 #define BT_WS_ERROR_WORD 2
 #define BT_WS_WAIT_LIMIT_WORD 3
 #define BT_WS_PATIENCE_WORD 4

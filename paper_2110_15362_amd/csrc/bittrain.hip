@@ -48,29 +48,16 @@ constexpr int kVecBytes = 16;
 #endif
 constexpr int kReluRows = BT_RELU_ROWS;   // 16-byte vectors per lane in the ReLU-backward stream
 
-// Workgroups per compute unit (= waves per SIMD) the persistent kernels are built for.
-// Compression wants LDS (a quarter of a unit's 160 KiB per workgroup: room for the values of
-// about two tiles per wave), restoration wants waves.
+// Workgroups per compute unit (= waves per SIMD) the codec kernels are built for: eight, i.e. at
+// most 64 vector registers per lane.
 #ifndef BT_COMPRESS_OCC
-#define BT_COMPRESS_OCC 3
+#define BT_COMPRESS_OCC 8
 #endif
 #ifndef BT_DECOMPRESS_OCC
 #define BT_DECOMPRESS_OCC 8
 #endif
 constexpr int kCompressOcc = BT_COMPRESS_OCC;
 constexpr int kDecompressOcc = BT_DECOMPRESS_OCC;
-// Bytes of LDS in which a compressing wave parks values that wait for their prefix.
-#ifndef BT_RING_BYTES
-#define BT_RING_BYTES 12288
-#endif
-constexpr int kRingBytes = BT_RING_BYTES;
-// Tiles a compressing wave has on their way at a time (1 or 2).
-#ifndef BT_TILES_AHEAD
-#define BT_TILES_AHEAD 2
-#endif
-constexpr int kTilesAhead = BT_TILES_AHEAD;
-constexpr int kRingStride = kRingBytes + kWaveSize * 8;   // + a place per lane that takes the writes of dropped elements
-constexpr int kQueue = 16;                            // parked phases per wave, at most
 
 // ---- workspace layout -----------------------------------------------------------------
 // Header (uint32 words), then one 6 KiB block per 256 slots.
@@ -110,12 +97,12 @@ template <int S> struct Geo {
     static constexpr int TILE = kWaves * WAVE;       // elements per tile
     static constexpr int TILE_WORDS = TILE / 32;     // bitmap words per tile
     static constexpr int LANE_WORDS = TILE_WORDS / kWaveSize;   // of which a lane counts this many when a wave counts a tile
-    static constexpr int LDS_WAVE = kPhaseRows * ROW * S + 2 * kVecBytes;  // restoration's staging bytes per wave: the rows of a phase,
-                                                                          // the shift to a 16-byte boundary, and slack
+    static constexpr int LDS_WAVE = kPhaseRows * ROW * S + 2 * kVecBytes;  // staging bytes per wave: the rows of a phase, the
+                                                                          // shift to a 16-byte boundary, and a vector nobody reads
+    static constexpr int DUMP = (LDS_WAVE - kVecBytes) / S;             // element index of that vector in a wave's strip
     static constexpr int RPM = 32 / E;               // rows whose E-bit lane masks share one register
     static constexpr int MW = (kRows + RPM - 1) / RPM;   // registers that hold a lane's masks
     static_assert(kRows % kPhaseRows == 0 && kPhaseRows % 2 == 0, "rows are scanned two to a register");
-    static_assert(kPhaseRows * ROW * S + 2 * kVecBytes <= kRingBytes, "a phase must fit the ring");
 };
 
 // ---- wave-level primitives (all 64 lanes must be active) ---------------------
@@ -458,21 +445,21 @@ static_assert(sizeof(DecompressMany) <= 3840, "kernel arguments of a batched res
 //
 // The position of a tile's first value is the number of non-zero elements in all
 // tiles before it (Algorithm 1 appends in index order; Algorithm 2's counter j).
-// Tiles do not talk to each other.  Each tile publishes its count in the workspace;
-// ONE extra workgroup (workgroup 0, a single wave: the "scanner") reads the counts
-// in index order, kScanGroups x 256 at a time, keeps the running sum, and writes every
-// tile's prefix back; a wave then polls the prefix of its tile, one 8-byte load.  Per
-// tile that is one store and a few polled loads on lines shared with few other tiles.
-// (Having every tile read its predecessors' counts itself -- a look-back window or a tree --
-// makes a few hot lines that thousands of tiles read at once, and those reads
-// queue up at one memory channel.)
+// Tiles do not talk to each other.  Each tile's workgroup publishes its count in the
+// workspace; ONE extra workgroup (workgroup 0, a single wave: the "scanner") reads the
+// counts in index order, keeps the running sum, and writes every tile's prefix back; the
+// tile then polls its own prefix, one 8-byte load.  Per tile that is one store and a few
+// polled loads on lines shared with few other tiles.  (Having every tile read its
+// predecessors' counts itself -- a look-back window or a tree -- makes a few hot lines that
+// thousands of tiles read at once, and those reads queue up at one memory channel.)
 //
-// Forward progress.  A launch never has more workgroups than the device can hold at the
-// same time (the host asks the runtime for the kernel's occupancy), so all of them,
-// scanner included, are running whatever the order in which they were started.  A
-// workgroup publishes the count of a tile without waiting for anything; the scanner
-// waits only for counts; a wave waits only for the scanner.  Waits are bounded anyway
-// (kSpinLimit): if the assumption were ever broken the call ends with the error word set.
+// Forward progress does not rest on the order in which workgroups are started.  A workgroup
+// publishes its count before it waits for anything, the scanner waits only for counts, and
+// a workgroup whose prefix has not come after kPatience polls stops waiting and counts what
+// lies before its tile itself, from the call's inputs alone (prefix_from_bitmap,
+// prefix_from_input): slow, but then every workgroup that has been started ends, whatever
+// the others do, and every workgroup is started in the end.  The scanner's own wait is
+// bounded (kSpinLimit): if it runs out the call ends with the error word set.
 //
 // Entries are value + 1 (0 = not published), written and read with relaxed
 // device-scope atomics: the entry is the only thing that is communicated.
@@ -547,231 +534,15 @@ template <int SLEEP> __device__ __forceinline__ bool spin_expired(uint32_t *hdr,
     return false;
 }
 
-// The scanner.  A pass of one of its waves looks at the kScanGroups x 256 slots of a window.  Lane l takes the four consecutive slots 4l .. 4l + 3 of a block, so the
-// counts of a block are one 16-byte load per lane and its prefixes two 16-byte stores; the
-// 16 lanes of a DPP row hold 64 consecutive slots, the unit in which batched tensors are laid
-// out.  The pass takes the leading run of published counts, turns it into prefixes (four
-// adds inside the lane, four DPP steps inside the row, the rows chained through scalar
-// registers, where a tensor's total is also taken and the sum restarts at a tensor's first
-// row), writes them, and moves the frontier.  At the end it advances the header for the
-// next call.
-//
-// The passes are pipelined.  On this hardware one counter tracks a wave's loads and
-// stores alike, in order of issue: a load that is waited for after a store also waits for
-// that store to reach memory, which would make a pass cost two round trips.  So the counts
-// of the NEXT window are asked for before the prefixes of the current one are stored, and
-// every pass issues exactly the same instructions behind its loads (a lane with nothing to
-// store writes to a spare line of the header), so that the wait for the counts can leave
-// precisely those stores outstanding.
-#ifndef BT_SCAN_GROUPS
-#define BT_SCAN_GROUPS 1
-#endif
-constexpr int kScanGroups = BT_SCAN_GROUPS;
-
-// Inclusive prefix sum inside each row of 16 lanes.
-__device__ __forceinline__ uint32_t row_inclusive_sum(uint32_t x) {
-    x += BT_DPP(0, x, 0x111, 0xf, true);   // row_shr:1
-    x += BT_DPP(0, x, 0x112, 0xf, true);   // row_shr:2
-    x += BT_DPP(0, x, 0x114, 0xf, true);   // row_shr:4
-    x += BT_DPP(0, x, 0x118, 0xf, true);   // row_shr:8
-    return x;
-}
-
-// The four waves of workgroup 0 share the work: the call's slots are cut into windows of
-// kScanGroups x 256, window k belongs to wave k mod 4.  A wave polls the counts of its window from
-// the start, whether or not the frontier has reached it; it may turn them into prefixes once the
-// wave before it has finished the window before and handed over the running sum (through LDS).
-// So up to four windows' counts are on their way at a time, and when the frontier enters a
-// window that window's counts are mostly there already: a memory round trip (several
-// microseconds when the memory system is busy) is paid once per four windows, not once per window.
-struct ScanShared {
-    uint64_t running[kWaves];   // a wave's running sum at the end of the window it finished last
-    uint32_t item[kWaves];      //   and the tensor that window ended in
-    uint32_t done[kWaves];      // 1 + the window a wave finished last (0: none yet)
-};
-
-template <class Job> __device__ __forceinline__ void scan_counts(char *ws, const Job &job, ScanShared &sh) {
-    const uint32_t lane = threadIdx.x & (kWaveSize - 1);
-    const uint32_t wave = uniform32(threadIdx.x >> 6);
-    uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
-    const uint32_t seq = hdr[kHdrSeq];
-    const uint32_t cur = seq & 1u;
-    const uint32_t n_items = job.count();
-    const uint32_t n_slots = job.slots();
-    const uint32_t last_block = (n_slots - 1) >> 8;
-    constexpr uint32_t kWindow = 256u * kScanGroups;
-    const uint32_t n_windows = (n_slots + kWindow - 1) / kWindow;
-    const uint32_t limit = wait_limit(hdr);
-    char *const nowhere = ws + kHdrSpare + 8u * (lane & 15u);
-    if (lane == 0) sh.done[wave] = 0;
-    __syncthreads();
-#ifdef BT_TIMELINE
-    uint64_t *const timeline = g_timeline;      // read once: a load in the loop would join the scanner's waits
-    uint32_t timeline_pass = wave;
-#endif
-    // counts of the blocks b0, b0 + 1, ...: no branch around a load; blocks beyond the call read the last block
-    // and are not looked at.  Two 8-byte atomic loads per lane and block (there is no 16-byte one).
-    auto ask = [&](bt_u4 (&c)[kScanGroups], const uint32_t b0) {
-#pragma unroll
-        for (int j = 0; j < kScanGroups; ++j) {
-            const uint32_t b = b0 + j < last_block ? b0 + j : last_block;
-            const char *const p = ws_count(ws, 256u * b + 4u * lane, cur);
-            const uint64_t lo = ws_load64(p), hi = ws_load64(p + 8);
-            c[j].x = (uint32_t)lo; c[j].y = (uint32_t)(lo >> 32); c[j].z = (uint32_t)hi; c[j].w = (uint32_t)(hi >> 32);
-        }
-    };
-    const auto store_behind = [&](char *p0, char *p1, char *p2, char *p3, const uint64_t v0, const uint64_t v1,
-                                  const uint64_t v2, const uint64_t v3) {
-        ws_store64(p0, v0);
-        ws_store64(p1, v1);
-        ws_store64(p2, v2);
-        ws_store64(p3, v3);
-    };
-    for (uint32_t window = wave; window < n_windows; window += kWaves) {
-        const uint32_t b0 = window * kScanGroups;
-        const uint32_t window_end = kWindow * (window + 1) < n_slots ? kWindow * (window + 1) : n_slots;
-        uint32_t frontier = kWindow * window;     // slots [window start, frontier) are done
-        bool mine = window == 0;                  // the window before this one is finished, its sums are known
-        uint32_t item = 0;                        // tensor that slot `frontier` belongs to
-        uint64_t running = 0;                     // stored values of tensor `item` in its tiles before `frontier`
-        uint32_t spins = 0;
-        bt_u4 c[kScanGroups];
-        ask(c, b0);
-#pragma unroll
-        for (int j = 0; j < kScanGroups; ++j)     // as many stores behind these loads as behind all later ones
-            store_behind(nowhere, nowhere, nowhere, nowhere, 0, 0, 0, 0);
-        while (frontier < window_end) {
-            // (1) how far the leading run of usable slots goes: done before, published, or beyond the call
-            uint32_t run_end = frontier;
-            {
-                bool open = true;
-#pragma unroll
-                for (int j = 0; j < kScanGroups; ++j) {
-                    const uint32_t s0 = 256u * (b0 + j) + 4u * lane;
-                    const uint32_t cc[4] = {c[j].x, c[j].y, c[j].z, c[j].w};
-                    uint32_t lane_run = 0;
-                    bool ok = true;
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        ok = ok && (s0 + k >= n_slots || s0 + k < frontier || cc[k] != 0);
-                        lane_run += ok ? 1u : 0u;
-                    }
-                    const uint64_t whole = __ballot(lane_run == 4);
-                    const uint32_t first_short = whole == ~(uint64_t)0 ? 64u : (uint32_t)__ffsll((unsigned long long)~whole) - 1u;
-                    const uint32_t short_run = (uint32_t)__builtin_amdgcn_readlane((int)lane_run, (int)(first_short & 63u));
-                    uint32_t end = 256u * (b0 + j) + (first_short == 64u ? 256u : 4u * first_short + short_run);
-                    if (end > n_slots) end = n_slots;
-                    if (open && b0 + j <= last_block && end > run_end) run_end = end;
-                    open = open && first_short == 64u;
-                }
-            }
-            if (!mine) {
-                // Has the wave before this one finished the window before?  If every count of this window is here
-                // already there is nothing to ask memory for: wait for the hand-over in LDS, which is quick to poll.
-                const uint32_t before = (wave + kWaves - 1) & (kWaves - 1);
-                for (;;) {
-                    const uint32_t d = __hip_atomic_load(&sh.done[before], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    if (uniform32(d) == window) {     // it has finished window - 1
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");   // LDS only: no wait for global memory
-                        running = uniform64(sh.running[before]);
-                        item = uniform32(sh.item[before]);
-                        mine = true;
-                        break;
-                    }
-                    if (run_end != window_end) break;
-                    if (spin_expired<kScannerSleep>(hdr, spins, limit)) return;
-                }
-            }
-            const uint32_t new_frontier = mine ? run_end : frontier;
-            // (2) prefixes of the fresh slots [frontier, new_frontier)
-            uint32_t in_lane[kScanGroups][3];      // sums of a lane's first one, two, three counts
-            uint32_t in_row[kScanGroups];          // a lane's place inside its row of 64 slots
-            uint64_t base[kScanGroups];            // what comes before the lane's row
-#pragma unroll
-            for (int j = 0; j < kScanGroups; ++j) {
-                const uint32_t s0 = 256u * (b0 + j) + 4u * lane;
-                const uint32_t cc[4] = {c[j].x, c[j].y, c[j].z, c[j].w};
-                uint32_t m[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) m[k] = (s0 + k >= frontier && s0 + k < new_frontier) ? cc[k] - 1u : 0u;
-                in_lane[j][0] = m[0];
-                in_lane[j][1] = m[0] + m[1];
-                in_lane[j][2] = in_lane[j][1] + m[2];
-                const uint32_t total = in_lane[j][2] + m[3];
-                const uint32_t incl = row_inclusive_sum(total);
-                in_row[j] = incl - total;
-                uint64_t row_base[4] = {0, 0, 0, 0};
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const uint32_t row0 = 256u * (b0 + j) + 64u * r;
-                    const uint32_t row_total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 16 * r + 15);
-                    const uint32_t lo = row0 > frontier ? row0 : frontier;
-                    const uint32_t hi = row0 + 64u < new_frontier ? row0 + 64u : new_frontier;
-                    if (lo < hi) {                                                     // the row has fresh slots
-                        while (item + 1 < n_items && row0 >= job.start(item + 1)) ++item;
-                        if (row0 == job.start(item) && frontier <= row0) running = 0;  // a new tensor begins
-                        row_base[r] = running;
-                        running += row_total;
-                        uint64_t *const nnz = job.nnz(item);
-                        if (hi == job.start(item + 1) && lane == 0 && nnz != nullptr)
-                            *nnz = running;                                            // the length of this tensor's value array
-                    }
-                }
-                const uint32_t r = lane >> 4;
-                base[j] = r == 0 ? row_base[0] : r == 1 ? row_base[1] : r == 2 ? row_base[2] : row_base[3];
-            }
-            // The window is finished: hand the sums over to the wave that has the next one, at once (what follows in
-            // this pass -- asking again, storing the prefixes -- is none of its business).
-            if (new_frontier == window_end && new_frontier != frontier && lane == 0) {
-                sh.running[wave] = running;
-                sh.item[wave] = item;
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");   // LDS only: no wait for global memory
-                __hip_atomic_store(&sh.done[wave], window + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            }
-            if (new_frontier == frontier) {
-                if (spin_expired<kScannerSleep>(hdr, spins, limit)) return;
-            }
-#ifdef BT_TIMELINE
-            else if (timeline != nullptr && lane == 0 && timeline_pass < g_timeline_passes) {
-                timeline[8 * (size_t)g_timeline_tiles + 2 * timeline_pass] = wall_clock64();
-                timeline[8 * (size_t)g_timeline_tiles + 2 * timeline_pass + 1] = ((uint64_t)frontier << 32) | new_frontier;
-                timeline_pass += kWaves;
-            }
-#endif
-            // (3) the window again, for what was not published yet: asked for before (4), see above
-            bt_u4 c_next[kScanGroups];
-            ask(c_next, b0);
-            // (4) now the stores: a fresh slot's prefix to its entry, everything else to the spare line
-#pragma unroll
-            for (int j = 0; j < kScanGroups; ++j) {
-                const uint32_t s0 = 256u * (b0 + j) + 4u * lane;
-                bool fresh[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) fresh[k] = s0 + k >= frontier && s0 + k < new_frontier;
-                const uint64_t at = base[j] + in_row[j] + 1;
-                char *const p = ws_prefix(ws, s0 < n_slots ? s0 : 0u, cur);
-                store_behind(fresh[0] ? p : nowhere, fresh[1] ? p + 8 : nowhere, fresh[2] ? p + 16 : nowhere,
-                             fresh[3] ? p + 24 : nowhere, at, at + in_lane[j][0], at + in_lane[j][1], at + in_lane[j][2]);
-            }
-#pragma unroll
-            for (int j = 0; j < kScanGroups; ++j) c[j] = c_next[j];
-            frontier = new_frontier;
-        }
-        if (window + 1 == n_windows && lane == 0) {
-            // every workgroup of the launch has at least one slot and has published its count by now, hence has
-            // read the header: advance it
-            __hip_atomic_store(&hdr[kHdrPrevTiles], n_slots, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&hdr[kHdrSeq], seq + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-}
-
-// The scanner of a restoration: one wave.  There the workgroups come and go (one per tile, see
-// decompress_kernel) and a count is published as soon as its workgroup has been started, so the counts
-// arrive in index order at the pace at which tiles finish; one wave that takes kRowScan rows of 64
-// counts starting at the frontier's row in every pass, consumes the leading run of published ones and
-// asks again keeps up with that and has nothing to hand over to anybody.  (All rows are looked at
-// before anything is written: a load waited for after a store would also wait for that store.)
+// The scanner: one wave.  Workgroups come and go (one per tile) and a count is published as soon as
+// its workgroup has been started, so the counts arrive in index order at the pace at which tiles
+// finish; one wave that takes kRowScan rows of 64 counts starting at the frontier's row in every
+// pass, consumes the leading run of published ones and asks again keeps up with that.  A row of 64
+// slots is also the unit in which batched tensors are laid out: the running sum restarts where a
+// tensor begins and goes to that tensor's nnz where it ends.  (All rows are looked at before anything
+// is written: on this hardware one counter tracks a wave's loads and stores in order of issue, so a
+// load waited for after a store would also wait for that store.)  At the end the scanner advances
+// the header for the next call.
 constexpr int kRowScan = 7;
 template <class Job> __device__ __forceinline__ void scan_counts_rows(char *ws, const Job &job) {
     const uint32_t lane = threadIdx.x & (kWaveSize - 1);
@@ -826,12 +597,16 @@ template <class Job> __device__ __forceinline__ void scan_counts_rows(char *ws, 
                     if (fresh) ws_store64(ws_prefix(ws, t, cur), running + (incl - mine) + 1);
                     running += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
                     new_frontier = row_end;
+                    uint64_t *const nnz = job.nnz(item);
+                    if (row_end == job.start(item + 1) && lane == 0 && nnz != nullptr) *nnz = running;   // this tensor's number of values
                 }
                 open = run == 64u;
             }
         }
+        // the scanner's wait for the call's counts is bounded in passes, fruitful or not
+        if (spin_expired<0>(hdr, spins, limit)) return;
         if (new_frontier == frontier) {
-            if (spin_expired<kScannerSleep>(hdr, spins, limit)) return;
+            __builtin_amdgcn_s_sleep(kScannerSleep);
             continue;
         }
 #ifdef BT_TIMELINE
@@ -881,22 +656,6 @@ __device__ __forceinline__ void zero_previous(char *ws, const Epoch ep, const ui
     }
 }
 
-// Wait for the scanner's answer for `slot`: the number of stored values of the slot's tensor before
-// the slot's tile.  Run by whole waves (all lanes load the same 8 bytes).  A wait that runs out
-// answers 0, which keeps every access of the caller inside the tile's own share of the buffers.
-__device__ __forceinline__ uint64_t wait_prefix(char *ws, const uint32_t slot, const uint32_t cur, uint32_t *hdr,
-                                                const uint32_t limit, uint32_t &polls) {
-    uint32_t spins = 0;
-    uint64_t v;
-    for (;;) {
-        v = uniform64(ws_load64(ws_prefix(ws, slot, cur)));
-        if (v != 0) break;
-        if (spin_expired<kTileSleep>(hdr, spins, limit)) { v = 1; break; }
-    }
-    polls += spins + 1;
-    return v - 1;
-}
-
 // A lane's E-bit non-zero masks of all rows, packed RPM rows to a register.
 #define BT_MASK(S_, mp, k) (((mp)[(k) / Geo<S_>::RPM] >> (Geo<S_>::E * ((k) % Geo<S_>::RPM))) & ((1u << Geo<S_>::E) - 1u))
 
@@ -918,39 +677,20 @@ __device__ __forceinline__ void rank_rows(const uint32_t (&mp)[Geo<S>::MW], uint
 
 // ---- Algorithm 1: dense -> bitmap -------------------------------------------------------
 
-// 16 bytes from LDS at an address that is only element-aligned.
-template <int S> __device__ __forceinline__ uint4 lds_read16(const unsigned char *p, const bool odd_half) {
-    if (S == 8) {
-        const uint64_t a = reinterpret_cast<const uint64_t *>(p)[0], b = reinterpret_cast<const uint64_t *>(p)[1];
-        return make_uint4((uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32));
-    }
-    if (S == 4 || !odd_half) {
-        const uint32_t *q = reinterpret_cast<const uint32_t *>(p);
-        return make_uint4(q[0], q[1], q[2], q[3]);
-    }
-    // 2-byte elements at an odd element position: five aligned words, shifted down by 16 bits
-    const uint32_t *q = reinterpret_cast<const uint32_t *>(p - 2);
-    const uint32_t d0 = q[0], d1 = q[1], d2 = q[2], d3 = q[3], d4 = q[4];
-    return make_uint4(__builtin_amdgcn_alignbit(d1, d0, 16), __builtin_amdgcn_alignbit(d2, d1, 16),
-                      __builtin_amdgcn_alignbit(d3, d2, 16), __builtin_amdgcn_alignbit(d4, d3, 16));
-}
-
-// Write `cnt` elements that a wave has parked in LDS, starting at `data` (16-byte aligned, with
-// 16 bytes of slack before it and after the last element), to global memory at g0_ptr with
-// aligned 16-byte stores.  Global vector v (counted from the 16-byte boundary at or before
-// g0_ptr) takes LDS elements v * E - pad ..., pad being g0_ptr's distance from that boundary in
-// elements; the first and the last vector go element by element, so nothing outside
-// [g0_ptr, g0_ptr + cnt) is touched.  All LDS reads of the inner vectors are issued before the
-// first store.
+// Write `cnt` elements from a wave's LDS strip to global memory with aligned 16-byte
+// stores.  LDS element `pad + i` corresponds to global element g0 + i, where pad makes
+// LDS byte 0 line up with a 16-byte boundary of the global buffer.  The first and
+// last vector go element by element, so nothing outside [g0, g0 + cnt) is touched.
+// All LDS reads of the inner vectors are issued before the first store and the two edge
+// vectors are left to 2 E lanes at the end: this runs after the tile has received its
+// prefix, where every instruction delays the tile's exit.
 template <int S>
-__device__ __forceinline__ void ring_flush(const unsigned char *data, char *g0_ptr, const uint32_t cnt, const int lane) {
+__device__ __forceinline__ void strip_store(const unsigned char *strip, char *g0_ptr, const uint32_t pad,
+                                            const uint32_t cnt, const int lane) {
     constexpr int E = Geo<S>::E;
     static_assert(kPhaseRows * Geo<S>::ROW / E + 1 <= 2 + 4 * kWaveSize, "a phase must fit four inner vectors per lane");
     if (cnt == 0) return;
-    const uint32_t pad = (uint32_t)(reinterpret_cast<uintptr_t>(g0_ptr) & (kVecBytes - 1)) / S;
-    char *gvec = g0_ptr - (size_t)pad * S;      // 16-byte aligned; may start before g0_ptr
-    const unsigned char *src = data - (size_t)pad * S;   // LDS address of gvec's first element
-    const bool odd_half = S == 2 && (pad & 1u) != 0;
+    char *gvec = g0_ptr - (size_t)pad * S;      // 16-byte aligned; may start before g0
     const uint32_t hi_valid = pad + cnt;
     const uint32_t n_vec = (hi_valid + E - 1) / E;
     // the inner vectors (all but the first and the last: at most 255, wholly inside the range), four to a lane
@@ -958,7 +698,7 @@ __device__ __forceinline__ void ring_flush(const unsigned char *data, char *g0_p
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t v = 1u + (uint32_t)lane + (uint32_t)kWaveSize * i;
-        if (v + 1 < n_vec) t[i] = lds_read16<S>(src + (size_t)v * kVecBytes, odd_half);
+        if (v + 1 < n_vec) t[i] = *reinterpret_cast<const uint4 *>(strip + (size_t)v * kVecBytes);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -970,361 +710,278 @@ __device__ __forceinline__ void ring_flush(const unsigned char *data, char *g0_p
     if (lane < 2 * E) {
         const uint32_t e = lane < E ? (uint32_t)lane : (n_vec - 1) * E + (uint32_t)(lane - E);
         if (e >= pad && e < hi_valid && (lane < E || n_vec > 1)) {
-            if (S == 8) reinterpret_cast<uint64_t *>(gvec)[e] = reinterpret_cast<const uint64_t *>(src)[e];
-            else if (S == 4) reinterpret_cast<uint32_t *>(gvec)[e] = reinterpret_cast<const uint32_t *>(src)[e];
-            else reinterpret_cast<uint16_t *>(gvec)[e] = reinterpret_cast<const uint16_t *>(src)[e];
+            if (S == 8) reinterpret_cast<uint64_t *>(gvec)[e] = reinterpret_cast<const uint64_t *>(strip)[e];
+            else if (S == 4) reinterpret_cast<uint32_t *>(gvec)[e] = reinterpret_cast<const uint32_t *>(strip)[e];
+            else reinterpret_cast<uint16_t *>(gvec)[e] = reinterpret_cast<const uint16_t *>(strip)[e];
         }
     }
 }
 
-// bt_compress and its relatives.  Workgroup 0 is the scanner; workgroup w + 1 works through
-// slots w, w + G, w + 2G, ... of the call (G = gridDim.x - 1).  For each of its tiles a
-// workgroup
-//   (1) reads the tile (8 x 16 bytes per lane; a wave reads 8 KiB contiguous) and takes
-//       Algorithm 1's test on every element (optionally after the pruning of Section 4.3),
-//   (2) ranks the kept elements inside each wave (DPP prefix sums) and writes the bitmap words,
-//   (3) adds up the four waves' totals through LDS and publishes the tile's count,
-//   (4) compacts each wave's kept elements, a phase of 4 rows at a time, into that wave's
-//       ring in LDS, where they wait for the tile's prefix,
-// and goes on to its next tile.  The prefix of the OLDEST parked tile is asked for together with
-// the next tile's loads and looked at when those have arrived: by then it is usually there, and
-// the parked values leave with aligned 16-byte stores while the tile that has just arrived is
-// counted.  Only when the ring cannot take another phase does a wave stop and wait for a
-// prefix.  What is left in the rings at the end is waited for and written out.
+// What a compressing workgroup does when the scanner's answer for its tile does not come: its first
+// wave counts the kept elements of the tensor before the tile itself, with the same test.  Slow (the
+// whole input up to the tile), but it needs nothing from any other workgroup.
+template <int S, int KEEP>
+__device__ __forceinline__ uint64_t prefix_from_input(const void *__restrict__ in, const uint32_t tile, const float threshold_f,
+                                                   const double threshold, const int lane) {
+    const uint64_t vectors = (uint64_t)tile * (Geo<S>::TILE / Geo<S>::E);      // all of them whole and inside the tensor
+    const uint4 *const p = static_cast<const uint4 *>(in);
+    uint64_t mine = 0;
+    for (uint64_t v = (uint32_t)lane; v < vectors; v += kWaveSize) mine += (uint32_t)__popc(keep_mask<S, KEEP>(p[v], threshold_f, threshold));
+#pragma unroll
+    for (int d = 1; d < kWaveSize; d <<= 1) mine += __shfl_xor((unsigned long long)mine, d, kWaveSize);
+    return uniform64(mine);
+}
+
+// bt_compress and its relatives (pruning, dense output, tile index, batches): workgroup 0 is the scanner
+// (one wave of it), workgroup 1 + t compresses slot t.
+// 1. load: lane l of row k owns elements wave_e0 + k * ROW + l * E ... + E - 1 of its wave's quarter of the
+//    tile; all eight rows are asked for at once.
+// 2. the test of Algorithm 1 (on the bit pattern), or the pruning test; masks packed RPM rows to a register;
+//    ranks by one DPP wave prefix sum per two rows.
+// 3. bitmap words: G lanes OR their E-bit masks into one 32-bit word.
+// 4. the waves' totals meet in LDS, the tile's count is published, the first wave polls the tile's prefix.
+// 5. values: kPhaseRows rows at a time, the wave compacts its kept elements into its LDS strip at their ranks,
+//    shifted so that LDS byte 0 maps to a 16-byte boundary of the value array, and writes the strip out with
+//    aligned stores; then the dense pruned tensor, if asked for.
+// The workgroup ends with its stores on their way: nothing waits for them to land.  (A persistent version
+// of this kernel -- as many workgroups as are resident, each taking tiles w, w + G, ..., the next tile's loads
+// asked for before the current tile's prefix wait, compacted values parked in rings in LDS -- was built and
+// measured: 1 % faster on a 25.7 M element fp32 tensor, 5 to 15 % slower on 16-bit and on larger tensors.)
 template <int S, int KEEP, bool DENSE, class Job>
 __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Job job, char *ws, const double threshold, const float threshold_f) {
     using G = Geo<S>;
     constexpr int E = G::E;
-    __shared__ __attribute__((aligned(16))) unsigned char s_ring[kWaves * kRingStride];
-    __shared__ uint32_t s_wave_total[2][kWaves];
-    __shared__ ScanShared s_scan;
-    const uint32_t n_slots = job.slots();
+    __shared__ __attribute__((aligned(16))) unsigned char s_stage[kWaves * G::LDS_WAVE];
+    __shared__ uint64_t s_tile_prefix;
+    __shared__ uint32_t s_wave_total[kWaves];
+    if (workspace_failed(ws)) return;
     if (blockIdx.x == 0) {
-        if (!workspace_failed(ws)) scan_counts(ws, job, s_scan);
+        if (threadIdx.x < kWaveSize) scan_counts_rows(ws, job);
         return;
     }
     BT_TL_INIT;
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in a scalar register
-    const uint32_t worker = blockIdx.x - 1, workers = gridDim.x - 1;
+    const uint32_t slot = blockIdx.x - 1, n_slots = gridDim.x - 1;
     uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
+    const Slot sl = job.at(slot);
+    if (sl.idle) {
+        // a slot of a batched call that belongs to no tile: it publishes an empty count (so that the scanner gets
+        // past it) and does its share of the clean-up
+        const Epoch ep = read_epoch(ws);
+        const uint32_t cur = uniform32(ep.cur);
+        const uint32_t prev_slots = uniform32(ep.prev_slots);
+        lds_barrier();                  // every wave has read the header before the first wave publishes anything
+        if (tid == 0) ws_store32(ws_count(ws, slot, cur), 1);
+        zero_previous(ws, Epoch{cur, prev_slots}, slot, n_slots);
+        return;
+    }
+    const uint32_t tile = sl.tile;
+    const uint64_t n = job.n(sl.item);
+    const void *const in = job.in(sl.item);
+    const uint64_t n_words = (n + 31) >> 5;
+    const uint64_t wave_e0 = (uint64_t)tile * G::TILE + (uint64_t)wave * G::WAVE;
+    const bool full = (uint64_t)(tile + 1) * G::TILE <= n;
 
-    // (1) load: lane l of row k owns elements wave_e0 + k*ROW + l*E ... + E-1 of its wave's part of the tile; all
-    //     rows of a tile are asked for at once.  The first tile is asked for before anything else is done.
-    //     xa and xb take turns: as soon as a tile has arrived the next one is asked for, into the other buffer, so that
-    //     the work on a tile (ranks, bitmap, compaction) does not leave the memory system idle.
-    uint4 xa[kRows], xb[kRows];
-    // Always the same eight loads, whatever the slot: from the tile if it is a whole tile, else (no such slot, a slot
-    // that belongs to no tile, a tensor's ragged last tile) from somewhere harmless in the workspace.  The number
-    // of loads behind the other buffer's loads then never depends on the data, and the wait for one buffer can leave
-    // exactly the other buffer's loads outstanding.  A ragged tile is loaded when its turn comes (see below).
-    // (a line of the workspace's first block that depends on the wave, so that no line has many readers)
-    const uint4 *const nowhere = reinterpret_cast<const uint4 *>(ws + kHeaderBytes + ((worker * kWaves + (uint32_t)wave) * 64u) % (uint32_t)kBlockBytes);
-    auto ask_tile = [&](uint4 (&x)[kRows], const uint64_t slot64) {
-        const uint4 *p = nowhere;
-        uint32_t row_stride = 0;
-        if (slot64 < n_slots) {
-            const Slot sl = job.at((uint32_t)slot64);
-            if (!sl.idle && (uint64_t)(sl.tile + 1) * G::TILE <= job.n(sl.item)) {
-                const uint64_t wave_e0 = (uint64_t)sl.tile * G::TILE + (uint64_t)wave * G::WAVE;
-                p = reinterpret_cast<const uint4 *>(static_cast<const char *>(job.in(sl.item)) + wave_e0 * S) + lane;
-                row_stride = kWaveSize;
-            }
-            BT_TL((uint32_t)slot64, 0);
-        }
+    // (1), (2)
+    uint4 x[kRows];
+    uint32_t mp[G::MW], rank2[kRows / 2], total2[kRows / 2];
 #pragma unroll
-        for (int k = 0; k < kRows; ++k) x[k] = stream_load<kCompressNtLoad>(p + k * row_stride);
-    };
-    ask_tile(xa, worker);
-
-    if (workspace_failed(ws)) return;
+    for (int i = 0; i < G::MW; ++i) mp[i] = 0;
+    BT_TL(slot, 0);
+    if (full) {
+        const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const char *>(in) + wave_e0 * S) + lane;
+#pragma unroll
+        for (int k = 0; k < kRows; ++k) x[k] = stream_load<kCompressNtLoad>(p + k * kWaveSize);
+    }
     // written at the end of the previous call; constant until every slot of this call has published
     const Epoch ep = read_epoch(ws);
-    const uint32_t cur = ep.cur;
-    const uint32_t limit = wait_limit(hdr);
-    zero_previous(ws, ep, worker, workers);
+    const uint32_t cur = uniform32(ep.cur);      // (the wave has the header's words from here on)
+    const uint32_t prev_slots = uniform32(ep.prev_slots);
+    const uint32_t asked_patience = hdr[kHdrPatience];          // never written by a kernel
+    const uint32_t patience = asked_patience != 0 ? asked_patience : kPatience;
+    if (full) {
+#pragma unroll
+        for (int k = 0; k < kRows; ++k) {
+            uint32_t mk = keep_mask<S, KEEP>(x[k], threshold_f, threshold);
+            asm volatile("" : "+v"(mk));             // row k has arrived: its mask exists from here on
+            mp[k / G::RPM] |= mk << (E * (k % G::RPM));
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < kRows; ++k) {
+            const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
+            x[k] = load_vec_guarded<S>(in, e0, n);
+            // elements at or beyond n read as 0, which a negative threshold would keep: mask them
+            const uint32_t in_range = e0 >= n ? 0u : (n - e0 >= (uint64_t)E ? (1u << E) - 1u : (1u << (uint32_t)(n - e0)) - 1u);
+            mp[k / G::RPM] |= (keep_mask<S, KEEP>(x[k], threshold_f, threshold) & in_range) << (E * (k % G::RPM));
+        }
+    }
+    // Keep the masks as values of their own: otherwise the compiler keeps one compare
+    // result (a scalar register pair) per element alive until the values are written.
+#pragma unroll
+    for (int i = 0; i < G::MW; ++i) asm volatile("" : "+v"(mp[i]));
+    rank_rows<S>(mp, rank2, total2);
+    uint32_t wave_total = 0;
+#pragma unroll
+    for (int k = 0; k < kRows; ++k) wave_total += BT_FIELD(total2, k);
 
-    // This wave's ring: phases of compacted values, first in first out.  An entry occupies
-    // [start, start + 32 + its values rounded up to 16 bytes): 16 bytes of slack, the values,
-    // slack.  Entries never wrap: one that does not fit behind the newest goes to the front.
-    // The queue itself lives in four vector registers, entry i in lane i.
-    unsigned char *const ring = s_ring + wave * kRingStride;
-    unsigned char *const dump = ring + kRingBytes + lane * S;   // takes this lane's writes of dropped elements; never read
-    uint32_t q_place = 0, q_slot = 0, q_before = 0, q_item = 0;   // start | count << 16; slot; values of the tile before it; tensor
-    uint32_t q_head = 0, q_n = 0;        // oldest entry, number of entries
-    uint32_t r_head = 0, r_tail = 0;     // ring bytes [r_head, r_tail) are in use (cyclically)
-    uint32_t polls = 0, blocked = 0;
-    uint32_t barriers = 0;
+    // (3) lane (g * G + i) keeps the word of row r0 + i, group g: one store per G rows.  The store itself
+    //     waits until after (4): a store in flight would delay the polling loads there.
+    constexpr int kWordRegs = (kRows + G::G - 1) / G::G;
+    uint32_t word[kWordRegs];
+    {
+        const int i = lane % G::G;
+#pragma unroll
+        for (int r0 = 0; r0 < kRows; r0 += G::G) {
+            word[r0 / G::G] = 0;
+#pragma unroll
+            for (int k = r0; k < r0 + G::G && k < kRows; ++k) {
+                const uint32_t w = group_or<G::G>(BT_MASK(S, mp, k) << (uint32_t)(E * i));
+                if (i == k - r0) word[r0 / G::G] = w;
+                // finish this row's word now: left alone, the compiler sinks the selects below
+                // the wait in (4) and keeps one partial result per row alive across it
+                asm volatile("" : "+v"(word[r0 / G::G]));
+            }
+        }
+    }
 
-#define BT_Q(field, i) ((uint32_t)__builtin_amdgcn_readlane((int)(field), (int)uniform32((i) & (kQueue - 1))))
-    // write the oldest entry's values to global memory, given its tile's prefix, and free its ring space
-    auto flush_head = [&](const uint64_t prefix) {
-        const uint32_t place = BT_Q(q_place, q_head), before = BT_Q(q_before, q_head), item = BT_Q(q_item, q_head);
-        const uint32_t start = place & 0xffffu;
-        uint32_t cnt = place >> 16;
-        const uint64_t g0 = prefix + before;
-        const uint64_t cap = job.cap(item);
-        // Algorithm 2's j at the start of this tile, for bt_decompress_indexed: the tile's first wave leaves it
-        uint64_t *const index = job.index(item);
-        if (index != nullptr && wave == 0 && before == 0 && lane == 0) index[BT_Q(q_slot, q_head) - job.start(item)] = prefix;
+    // (4)
+    if (lane == 0) s_wave_total[wave] = wave_total;
+    lds_barrier();                      // also: every wave has read the header before the first wave publishes anything
+    uint32_t before_wave = 0, tile_total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t c = s_wave_total[w];
+        if (w < wave) before_wave += c;
+        tile_total += c;
+    }
+    before_wave = uniform32(before_wave);       // the same in every lane: tell the compiler, so that addresses built on it stay scalar
+    if (tid == 0) ws_store32(ws_count(ws, slot, cur), tile_total + 1);
+    BT_TL(slot, 1);
+    zero_previous(ws, Epoch{cur, prev_slots}, slot, n_slots);
+    uint32_t polls = 0;
+    if (wave == 0) {
+        uint64_t v;
+        for (;;) {
+            v = uniform64(ws_load64(ws_prefix(ws, slot, cur)));
+            ++polls;
+            if (v != 0) { v -= 1; break; }
+            if (polls > patience) {
+                // Count for ourselves.  The loop needs registers and the tile's elements fill them: park the elements
+                // in LDS meanwhile (the strips are not in use before the barrier below).
+                static_assert(kRows * kWaveSize * kVecBytes <= kWaves * G::LDS_WAVE, "room to park a wave's elements");
+                uint4 *const park = reinterpret_cast<uint4 *>(s_stage) + lane;
+#pragma unroll
+                for (int k = 0; k < kRows; ++k) park[k * kWaveSize] = x[k];
+                v = prefix_from_input<S, KEEP>(in, tile, threshold_f, threshold, lane);
+#pragma unroll
+                for (int k = 0; k < kRows; ++k) x[k] = park[k * kWaveSize];
+                break;
+            }
+            __builtin_amdgcn_s_sleep(kTileSleep);
+        }
+        if (lane == 0) {
+            s_tile_prefix = v;
+            uint64_t *const index = job.index(sl.item);
+            if (index != nullptr) index[tile] = v;     // Algorithm 2's j at the start of this tile, for bt_decompress_indexed
+        }
+    }
+    lds_barrier();
+    uint64_t g0 = uniform64(s_tile_prefix) + before_wave;          // index in the value array of this wave's next value
+    BT_TL(slot, 2);
+    BT_TL_VALUE(slot, 5, polls);
+    {
+        uint32_t *const bitmap = job.bitmap(sl.item);
+        const int g = lane / G::G, i = lane % G::G;
+#pragma unroll
+        for (int r0 = 0; r0 < kRows; r0 += G::G) {
+            const uint64_t widx = (wave_e0 >> 5) + (uint64_t)(r0 + i) * G::WPR + (uint64_t)g;
+            if (r0 + i < kRows && widx < n_words) bitmap[widx] = word[r0 / G::G];
+        }
+    }
+
+    // (5)
+    unsigned char *strip = s_stage + wave * G::LDS_WAVE;
+    const uint64_t values_cap = job.cap(sl.item);
+#pragma unroll
+    for (int r0 = 0; r0 < kRows; r0 += kPhaseRows) {
+        char *gdst = static_cast<char *>(job.values(sl.item)) + g0 * S;
+        const uint32_t pad = (uint32_t)(reinterpret_cast<uintptr_t>(gdst) & (kVecBytes - 1)) / S;   // elements
+        if (r0 != 0) wave_lds_sync();   // the previous phase's reads are done before the strip is reused
+        uint32_t row_start = pad;
+#pragma unroll
+        for (int k = r0; k < r0 + kPhaseRows; ++k) {
+            // byte offset of this lane's next kept element from the spare vector (negative: the strip lies before it)
+            int rb = ((int)(row_start + BT_FIELD(rank2, k)) - G::DUMP) * S;
+            unsigned char *const dump = strip + G::DUMP * S;
+            const uint32_t mk = BT_MASK(S, mp, k);
+            const uint32_t d[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
+            // every element is written, a dropped one to a place nobody reads: a select on the address instead of
+            // a branch around the write keeps the execution mask alone
+            if (S == 8) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int keep = (int)((mk >> j) & 1u);
+                    *reinterpret_cast<uint64_t *>(dump + __mul24(keep, rb)) = ((uint64_t)d[2 * j + 1] << 32) | d[2 * j];
+                    rb += keep * S;
+                }
+            } else if (S == 4) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int keep = (int)((mk >> j) & 1u);
+                    *reinterpret_cast<uint32_t *>(dump + __mul24(keep, rb)) = d[j];
+                    rb += keep * S;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int keep = (int)((mk >> j) & 1u);
+                    *reinterpret_cast<uint16_t *>(dump + __mul24(keep, rb)) = (uint16_t)(d[j >> 1] >> (16 * (j & 1)));
+                    rb += keep * S;
+                }
+            }
+            row_start += BT_FIELD(total2, k);
+        }
+        wave_lds_sync();
+        const uint32_t phase_total = row_start - pad;
         // capacity clamp: never write at or beyond values_cap
-        if (g0 >= cap) cnt = 0;
-        else if (cap - g0 < cnt) cnt = (uint32_t)(cap - g0);
-        ring_flush<S>(ring + start + kVecBytes, static_cast<char *>(job.values(item)) + g0 * S, cnt, lane);
-        wave_lds_sync();                 // the reads are done before the space is written again
-        ++q_head;
-        --q_n;
-        r_head = q_n != 0 ? (BT_Q(q_place, q_head) & 0xffffu) : r_tail;
-    };
-    // The oldest parked tile's prefix is asked for while a tile is worked on and looked at when the NEXT tile
-    // is worked on: a wave's loads come back in the order they were issued, so the answer cannot be seen before
-    // the other buffer's loads, which are older, have landed -- and those land just before the next tile's turn.
-    // The load is issued whether or not anything is parked (a spare line of the header then), so that the
-    // number of memory operations behind a tile's loads does not depend on it.
-    uint32_t polled_slot = 0;
-    uint64_t polled = 0;
-    bool polling = false;
-    auto ask_prefix = [&]() {
-        polling = q_n != 0;
-        polled_slot = polling ? BT_Q(q_slot, q_head) : 0u;
-        polled = ws_load64(polling ? ws_prefix(ws, polled_slot, cur) : ws + kHdrSpare);
-        ++polls;
-    };
-
-    // one tile: `x` holds its elements (asked for two tiles ago); at the end `x` is asked to fetch the tile after next
-    auto work_on = [&](uint4 (&x)[kRows], uint4 (&x_next)[kRows], const uint32_t slot) {
-        const Slot sl = job.at(slot);
-        if (sl.idle) {                   // a slot of a batched call that belongs to no tile
-            if (tid == 0) ws_store32(ws_count(ws, slot, cur), 1);
-            ask_tile(x_next, (uint64_t)slot + workers);
-            return;
-        }
-        const uint64_t n = job.n(sl.item);
-        const uint64_t n_words = (n + 31) >> 5;
-        const uint64_t wave_e0 = (uint64_t)sl.tile * G::TILE + (uint64_t)wave * G::WAVE;
-        const bool full = (uint64_t)(sl.tile + 1) * G::TILE <= n;
-
-        // Algorithm 1's test, on the bit pattern (optionally after the pruning of Section 4.3)
-        uint32_t mp[G::MW], rank2[kRows / 2], total2[kRows / 2];
-#pragma unroll
-        for (int i = 0; i < G::MW; ++i) mp[i] = 0;
-        if (!full) {                     // a ragged last tile: not asked for in advance; elements at or beyond n read as 0
-            const void *const in = job.in(sl.item);
-#pragma unroll
-            for (int k = 0; k < kRows; ++k)
-                x[k] = load_vec_guarded<S>(in, wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E, n);
-        }
-        if (full) {
-#pragma unroll
-            for (int k = 0; k < kRows; ++k) {
-                uint32_t mk = keep_mask<S, KEEP>(x[k], threshold_f, threshold);
-                asm volatile("" : "+v"(mk));             // row k has arrived: its mask exists from here on
-                mp[k / G::RPM] |= mk << (E * (k % G::RPM));
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < kRows; ++k) {
-                const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
-                // elements at or beyond n read as 0, which a negative threshold would keep: mask them
-                const uint32_t in_range = e0 >= n ? 0u : (n - e0 >= (uint64_t)E ? (1u << E) - 1u : (1u << (uint32_t)(n - e0)) - 1u);
-                mp[k / G::RPM] |= (keep_mask<S, KEEP>(x[k], threshold_f, threshold) & in_range) << (E * (k % G::RPM));
-            }
-        }
-        // Keep the masks as values of their own: otherwise the compiler keeps one compare
-        // result (a scalar register pair) per element alive until the values are written.
-#pragma unroll
-        for (int i = 0; i < G::MW; ++i) asm volatile("" : "+v"(mp[i]));
-        // The tile has arrived and its elements have been looked at: ask for the next one now, into the other
-        // buffer (this one is needed until the tile's values are parked), and behind it for the prefix of the oldest
-        // parked tile; what the previous turn asked about has come back with this tile's elements.
-        BT_TL(slot, 4);
-        const bool answered = polling;
-        const uint32_t answered_slot = polled_slot;
-        const uint64_t answer = polled;
-        if (kTilesAhead == 2) ask_tile(x_next, (uint64_t)slot + workers);
-        rank_rows<S>(mp, rank2, total2);
-        uint32_t wave_total = 0;
-#pragma unroll
-        for (int k = 0; k < kRows; ++k) wave_total += BT_FIELD(total2, k);
-
-        // (3) block total -> count for the scanner; what the waves before this one hold
-        const uint32_t par = barriers & 1u;
-        ++barriers;
-        if (lane == 0) s_wave_total[par][wave] = wave_total;
-        lds_barrier();
-        const uint32_t t0 = s_wave_total[par][0], t1 = s_wave_total[par][1], t2 = s_wave_total[par][2],
-                       t3 = s_wave_total[par][3];
-        if (tid == 0) ws_store32(ws_count(ws, slot, cur), t0 + t1 + t2 + t3 + 1);
-        BT_TL(slot, 1);
-        const uint32_t before_wave = uniform32((wave > 0 ? t0 : 0u) + (wave > 1 ? t1 : 0u) + (wave > 2 ? t2 : 0u));
-
-        // (2) the bitmap words: G lanes OR their E-bit masks into one 32-bit word; lane (g*G + i)
-        //     keeps the word of row r0 + i, group g: one store per G rows.
-        {
-            const int g = lane / G::G, i = lane % G::G;
-            uint32_t *const bitmap = job.bitmap(sl.item);
-#pragma unroll
-            for (int r0 = 0; r0 < kRows; r0 += G::G) {
-                uint32_t word = 0;
-#pragma unroll
-                for (int k = r0; k < r0 + G::G && k < kRows; ++k) {
-                    const uint32_t wk = group_or<G::G>(BT_MASK(S, mp, k) << (uint32_t)(E * i));
-                    if (i == k - r0) word = wk;
-                }
-                const uint64_t widx = (wave_e0 >> 5) + (uint64_t)(r0 + i) * G::WPR + (uint64_t)g;
-                if (r0 + i < kRows && widx < n_words) bitmap[widx] = word;
-            }
-        }
-
-        // the tile that was the oldest parked one a turn ago, if its prefix had come
-        if (answered) {
-            const uint64_t v = uniform64(answer);
-            if (v != 0) {
-                BT_TL(answered_slot, 2);
-                while (q_n != 0 && BT_Q(q_slot, q_head) == answered_slot) flush_head(v - 1);
-                BT_TL(answered_slot, 3);
-            }
-        }
-
-        // (4) kPhaseRows rows at a time, compact this wave's kept elements into its ring.  (A call
-        //     that has no room for any value and wants no tile index -- the bitmap alone is wanted -- skips this.)
-        if (job.cap(sl.item) != 0 || job.index(sl.item) != nullptr) {
-            uint32_t before = before_wave;
-#pragma unroll
-            for (int r0 = 0; r0 < kRows; r0 += kPhaseRows) {
-                uint32_t cnt = 0;
-#pragma unroll
-                for (int k = r0; k < r0 + kPhaseRows; ++k) cnt += BT_FIELD(total2, k);
-                cnt = uniform32(cnt);
-                const uint32_t need = 2 * kVecBytes + ((cnt * S + kVecBytes - 1) & ~(uint32_t)(kVecBytes - 1));
-                uint32_t start = 0;
-                for (;;) {
-                    bool fits = false;
-                    if (q_n == 0) {
-                        r_head = r_tail = 0;
-                        fits = true;
-                    } else if (q_n < (uint32_t)kQueue) {
-                        if (r_tail > r_head) {           // in use: one run; free: behind it and before it
-                            if (need <= (uint32_t)kRingBytes - r_tail) { start = r_tail; fits = true; }
-                            else if (need <= r_head) { start = 0; fits = true; }
-                        } else if (need <= r_head - r_tail) {   // in use: the two ends; free: the middle
-                            start = r_tail;
-                            fits = true;
-                        }
-                    }
-                    if (fits) break;
-                    // no room: the oldest entry has to leave first, however long its prefix takes
-                    ++blocked;
-                    const uint32_t s_old = BT_Q(q_slot, q_head);
-                    const uint64_t prefix = wait_prefix(ws, s_old, cur, hdr, limit, polls);
-                    BT_TL(s_old, 2);
-                    flush_head(prefix);
-                    BT_TL(s_old, 3);
-                }
-                r_tail = start + need;
-                {
-                    const uint32_t qi = (q_head + q_n) & (kQueue - 1);
-                    const bool me = (uint32_t)lane == qi;
-                    q_place = me ? (start | (cnt << 16)) : q_place;
-                    q_slot = me ? slot : q_slot;
-                    q_before = me ? before : q_before;
-                    q_item = me ? sl.item : q_item;
-                    ++q_n;
-                }
-                before += cnt;
-                // every element is written, a dropped one to a place nobody reads: a select on the address
-                // instead of a branch around the write keeps the execution mask alone
-                const int data_rel = (int)(start + kVecBytes) - kRingBytes - lane * S;   // of the entry's first value, from this lane's spare place
-#define BT_SCATTER(T, v) (*reinterpret_cast<T *>(dump + __mul24(keep, rb)) = (v))
-                uint32_t row_start = 0;
-#pragma unroll
-                for (int k = r0; k < r0 + kPhaseRows; ++k) {
-                    int rb = data_rel + (int)(row_start + BT_FIELD(rank2, k)) * S;
-                    const uint32_t mk = BT_MASK(S, mp, k);
-                    const uint32_t d[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
-                    if (S == 8) {
-#pragma unroll
-                        for (int j = 0; j < 2; ++j) {
-                            const int keep = (int)((mk >> j) & 1u);
-                            BT_SCATTER(uint64_t, ((uint64_t)d[2 * j + 1] << 32) | d[2 * j]);
-                            rb += keep * S;
-                        }
-                    } else if (S == 4) {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const int keep = (int)((mk >> j) & 1u);
-                            BT_SCATTER(uint32_t, d[j]);
-                            rb += keep * S;
-                        }
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) {
-                            const int keep = (int)((mk >> j) & 1u);
-                            BT_SCATTER(uint16_t, (uint16_t)(d[j >> 1] >> (16 * (j & 1))));
-                            rb += keep * S;
-                        }
-                    }
-                    row_start += BT_FIELD(total2, k);
-                }
-            }
-            wave_lds_sync();             // the values are in the ring before anything reads them
-        }
-
-        // (5) the dense tensor after pruning, if asked for (bt_activation_compress): what survives keeps its
-        //     bits, the rest is +0.  The output may be the input itself (every lane rewrites exactly the
-        //     vectors it has read).
-        if (DENSE) {
-            void *const dense = job.dense(sl.item);
-#pragma unroll
-            for (int k = 0; k < kRows; ++k) {
-                const uint32_t mk = BT_MASK(S, mp, k);
-                uint32_t d[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
-                // masks by arithmetic (0 - bit is all ones or zero), not by compares: see nonzero_mask
-                if (S == 8) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) d[j] &= 0u - ((mk >> (j >> 1)) & 1u);
-                } else if (S == 4) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) d[j] &= 0u - ((mk >> j) & 1u);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        d[j] &= (((mk >> (2 * j)) & 1u) * 0x0000ffffu) | (((mk >> (2 * j + 1)) & 1u) * 0xffff0000u);
-                }
-                const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
-                const uint4 o = make_uint4(d[0], d[1], d[2], d[3]);
-                if (full) stream_store<kCompressNtStore>(reinterpret_cast<uint4 *>(static_cast<char *>(dense) + e0 * S), o);
-                else store_vec_guarded<S>(dense, e0, n, o);
-            }
-        }
-        BT_TL(slot, 7);
-        // the tile after next takes this buffer: its loads are the last memory operations of the turn
-        if (kTilesAhead == 1) ask_tile(x_next, (uint64_t)slot + workers);   // one buffer: the next tile can only be asked for now
-        ask_prefix();
-    };
-
-    for (uint64_t slot = worker; slot < n_slots; slot += kTilesAhead * (uint64_t)workers) {
-        if (kTilesAhead == 1) {
-            work_on(xa, xa, (uint32_t)slot);
-        } else {
-            work_on(xa, xb, (uint32_t)slot);
-            if (slot + workers < n_slots) work_on(xb, xa, (uint32_t)(slot + workers));
-        }
+        uint32_t cnt = phase_total;
+        if (g0 >= values_cap) cnt = 0;
+        else if (values_cap - g0 < cnt) cnt = (uint32_t)(values_cap - g0);
+        strip_store<S>(strip, gdst, pad, cnt, lane);
+        g0 += phase_total;
     }
 
-    // what is still parked
-    while (q_n != 0) {
-        const uint32_t s_old = BT_Q(q_slot, q_head);
-        const uint64_t prefix = wait_prefix(ws, s_old, cur, hdr, limit, polls);
-        BT_TL(s_old, 2);
-        while (q_n != 0 && BT_Q(q_slot, q_head) == s_old) flush_head(prefix);
-        BT_TL(s_old, 3);
-        BT_TL_VALUE(s_old, 5, polls);
-        BT_TL_VALUE(s_old, 6, blocked);
+    // the dense tensor after pruning, if asked for (bt_activation_compress): what survives keeps its bits, the
+    // rest is +0.  Last, so that no store precedes the polling loads of (4); the dense output may be the input
+    // itself (every lane rewrites exactly the vectors it has read).
+    if (DENSE) {
+        void *const dense = job.dense(sl.item);
+#pragma unroll
+        for (int k = 0; k < kRows; ++k) {
+            const uint32_t mk = BT_MASK(S, mp, k);
+            uint32_t d[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
+            // masks by arithmetic (0 - bit is all ones or zero), not by compares: see nonzero_mask
+            if (S == 8) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) d[j] &= 0u - ((mk >> (j >> 1)) & 1u);
+            } else if (S == 4) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) d[j] &= 0u - ((mk >> j) & 1u);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    d[j] &= (((mk >> (2 * j)) & 1u) * 0x0000ffffu) | (((mk >> (2 * j + 1)) & 1u) * 0xffff0000u);
+            }
+            const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
+            const uint4 o = make_uint4(d[0], d[1], d[2], d[3]);
+            if (full) stream_store<kCompressNtStore>(reinterpret_cast<uint4 *>(static_cast<char *>(dense) + e0 * S), o);
+            else store_vec_guarded<S>(dense, e0, n, o);
+        }
     }
-    (void)blocked;
-#undef BT_Q
+    BT_TL(slot, 3);
 }
 
 // ---- Algorithm 2: bitmap -> dense ---------------------------------------------------------
@@ -1677,6 +1334,7 @@ __global__ __launch_bounds__(kBlock, kDecompressOcc) void decompress_kernel(cons
         if (w < wave) before_wave += c;
         tile_total += c;
     }
+    before_wave = uniform32(before_wave);       // the same in every lane: tell the compiler, so that addresses built on it stay scalar
     if (tid == 0) ws_store32(ws_count(ws, slot, cur), tile_total + 1);
     BT_TL(slot, 1);
     zero_previous(ws, Epoch{cur, prev_slots}, slot, n_slots);
@@ -1830,50 +1488,6 @@ bt_status launched() { return hipGetLastError() == hipSuccess ? BT_OK : BT_ERR_H
 // remembered; the query touches no stream.  The persistent kernels are launched with at most
 // this many workgroups, which is what lets their workgroups wait for one another.
 constexpr int kMaxDevices = 64;
-template <class Kernel> uint32_t resident_workgroups(Kernel kernel) {
-    static std::atomic<uint32_t> known[kMaxDevices];     // one table per kernel (per instantiation of this template)
-    int device = 0;
-    if (hipGetDevice(&device) != hipSuccess) return 2;
-    const bool cacheable = device >= 0 && device < kMaxDevices;
-    if (cacheable) {
-        const uint32_t k = known[device].load(std::memory_order_relaxed);
-        if (k != 0) return k;
-    }
-    int per_unit = 0, units = 0;
-    uint32_t total = 2;                                  // the scanner and one worker always fit
-    // the runtime's figure, and not more than the LDS of a compute unit (160 KiB) holds when a workgroup's share is
-    // rounded up generously (the runtime has been seen to count a workgroup's LDS without its allocation granule)
-    // and not more than the registers of a SIMD (512 per lane, handed out in eights; a workgroup has one wave on each
-    // SIMD) hold.  Counting too many here means workgroups that wait for one another without all being resident.
-    hipFuncAttributes attr;
-    int own_limit = 1 << 20;
-    if (hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(kernel)) == hipSuccess) {
-        if (attr.sharedSizeBytes > 0) own_limit = (int)(163840 / ((attr.sharedSizeBytes + 4095) / 4096 * 4096));
-        if (attr.numRegs > 0) {
-            const int by_regs = 512 / ((attr.numRegs + 7) / 8 * 8);
-            if (by_regs < own_limit) own_limit = by_regs;
-        }
-    } else {
-        (void)hipGetLastError();
-    }
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_unit, kernel, kBlock, 0) == hipSuccess && per_unit > own_limit)
-        per_unit = own_limit;
-    if (per_unit > 0 &&
-        hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess &&
-        units > 0 && (uint64_t)per_unit * (uint64_t)units >= 2)
-        total = (uint32_t)((uint64_t)per_unit * (uint64_t)units);
-    else
-        (void)hipGetLastError();
-    if (cacheable) known[device].store(total, std::memory_order_relaxed);
-    return total;
-}
-
-// Grid of a persistent launch over `slots` slots: the scanner plus as many workers as are resident, but no
-// worker without a slot.
-template <class Kernel> dim3 persistent_grid(Kernel kernel, uint64_t slots) {
-    uint64_t room = resident_workgroups(kernel) - 1;
-    return dim3((unsigned)((slots < room ? slots : room) + 1));
-}
 
 bt_status check_common(uint64_t n, bt_dtype dt, const void *d_ws, size_t ws_bytes) {
     if (elem_size(dt) == 0) return BT_ERR_DTYPE;
@@ -1949,7 +1563,7 @@ bt_status launch_compress(const Job &job, uint64_t slots, bt_dtype dtype, bool p
 #define BT_LAUNCH_COMPRESS(S_, KEEP_, DENSE_)                                                   \
     do {                                                                                        \
         auto kernel = compress_kernel<S_, KEEP_, DENSE_, Job>;                                  \
-        kernel<<<persistent_grid(kernel, slots), block, 0, hs>>>(job, ws, threshold, threshold_f); \
+        kernel<<<dim3((unsigned)(slots + 1)), block, 0, hs>>>(job, ws, threshold, threshold_f);  \
     } while (0)
     const int s = elem_size(dtype);
     if (!prune) {
