@@ -112,7 +112,7 @@ const char *bt_status_str(bt_status status);
  *   BT_WS_PATIENCE_WORD     polls after which a tile's workgroup stops waiting for the grid
  *                           scan and counts what lies before its tile itself, from the
  *                           bitmap (restoration) or the input (compression): correct, only
- *                           slower; 0 means the built-in 4096.  Written by the caller only,
+ *                           slower; looked at every 256th poll; 0 means the built-in 4096.  Written by the caller only,
  *                           like the wait limit; meant for tests of that path. */
 #define BT_WS_ERROR_WORD 2
 #define BT_WS_WAIT_LIMIT_WORD 3

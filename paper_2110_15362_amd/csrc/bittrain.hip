@@ -522,6 +522,13 @@ __device__ __forceinline__ uint32_t wait_limit(const uint32_t *hdr) {
     return asked != 0 ? asked : kSpinLimit;
 }
 
+// Polls after which a tile's workgroup counts for itself instead of waiting on.  Looked at every 256th poll
+// only: read from the header then, it costs neither a register nor a round trip per poll.
+__device__ __forceinline__ uint32_t patience_of(const uint32_t *hdr) {
+    const uint32_t asked = hdr[kHdrPatience];          // never written by a kernel
+    return asked != 0 ? asked : kPatience;
+}
+
 template <int SLEEP> __device__ __forceinline__ bool spin_expired(uint32_t *hdr, uint32_t &spins, const uint32_t limit) {
     // bounded wait: give up after the limit of polls, or soon after anyone has given up
     ++spins;
@@ -724,9 +731,10 @@ template <int S, int KEEP>
 __device__ __forceinline__ uint64_t prefix_from_input(const void *__restrict__ in, const uint32_t tile, const float threshold_f,
                                                    const double threshold, const int lane) {
     const uint64_t vectors = (uint64_t)tile * (Geo<S>::TILE / Geo<S>::E);      // all of them whole and inside the tensor
-    const uint4 *const p = static_cast<const uint4 *>(in);
+    const uint4 *const end = static_cast<const uint4 *>(in) + vectors;
     uint64_t mine = 0;
-    for (uint64_t v = (uint32_t)lane; v < vectors; v += kWaveSize) mine += (uint32_t)__popc(keep_mask<S, KEEP>(p[v], threshold_f, threshold));
+    for (const uint4 *q = static_cast<const uint4 *>(in) + lane; q < end; q += kWaveSize)
+        mine += (uint32_t)__popc(keep_mask<S, KEEP>(*q, threshold_f, threshold));
 #pragma unroll
     for (int d = 1; d < kWaveSize; d <<= 1) mine += __shfl_xor((unsigned long long)mine, d, kWaveSize);
     return uniform64(mine);
@@ -790,17 +798,11 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
 #pragma unroll
     for (int i = 0; i < G::MW; ++i) mp[i] = 0;
     BT_TL(slot, 0);
-    if (full) {
+    if (__builtin_expect(full, 1)) {
         const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const char *>(in) + wave_e0 * S) + lane;
 #pragma unroll
         for (int k = 0; k < kRows; ++k) x[k] = stream_load<kCompressNtLoad>(p + k * kWaveSize);
     }
-    // written at the end of the previous call; constant until every slot of this call has published
-    const Epoch ep = read_epoch(ws);
-    const uint32_t cur = uniform32(ep.cur);      // (the wave has the header's words from here on)
-    const uint32_t prev_slots = uniform32(ep.prev_slots);
-    const uint32_t asked_patience = hdr[kHdrPatience];          // never written by a kernel
-    const uint32_t patience = asked_patience != 0 ? asked_patience : kPatience;
     if (full) {
 #pragma unroll
         for (int k = 0; k < kRows; ++k) {
@@ -809,10 +811,15 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
             mp[k / G::RPM] |= mk << (E * (k % G::RPM));
         }
     } else {
+        // A tensor's ragged last tile, element by element and one row after the other: each row's addresses are
+        // made to depend on the row before having arrived (`after`, which is 0), because with the loads of all
+        // rows in flight together the addresses alone would need more registers than there are.
+        uint32_t after = 0;
 #pragma unroll
         for (int k = 0; k < kRows; ++k) {
-            const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E;
+            const uint64_t e0 = wave_e0 + (uint64_t)k * G::ROW + (uint64_t)lane * E + after;
             x[k] = load_vec_guarded<S>(in, e0, n);
+            asm volatile("" : "+v"(after), "+v"(x[k].x), "+v"(x[k].y), "+v"(x[k].z), "+v"(x[k].w));
             // elements at or beyond n read as 0, which a negative threshold would keep: mask them
             const uint32_t in_range = e0 >= n ? 0u : (n - e0 >= (uint64_t)E ? (1u << E) - 1u : (1u << (uint32_t)(n - e0)) - 1u);
             mp[k / G::RPM] |= (keep_mask<S, KEEP>(x[k], threshold_f, threshold) & in_range) << (E * (k % G::RPM));
@@ -827,8 +834,7 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
 #pragma unroll
     for (int k = 0; k < kRows; ++k) wave_total += BT_FIELD(total2, k);
 
-    // (3) lane (g * G + i) keeps the word of row r0 + i, group g: one store per G rows.  The store itself
-    //     waits until after (4): a store in flight would delay the polling loads there.
+    // (3) lane (g * G + i) keeps the word of row r0 + i, group g: one store per G rows.
     constexpr int kWordRegs = (kRows + G::G - 1) / G::G;
     uint32_t word[kWordRegs];
     {
@@ -847,7 +853,27 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
         }
     }
 
+    const auto store_words = [&]() {
+        uint32_t *const bitmap = job.bitmap(sl.item);
+        const int g = lane / G::G, i = lane % G::G;
+#pragma unroll
+        for (int r0 = 0; r0 < kRows; r0 += G::G) {
+            const uint64_t widx = (wave_e0 >> 5) + (uint64_t)(r0 + i) * G::WPR + (uint64_t)g;
+            if (r0 + i < kRows && widx < n_words) bitmap[widx] = word[r0 / G::G];
+        }
+    };
+    // Before the wait of (4) or after it?  After is better (a store in flight delays the polling loads, which share
+    // its completion counter: 3 % on fp32), but the words cost registers across the wait, and kernels for 16-bit
+    // elements have none to spare: there a spilled value would come back from memory right behind the value stores
+    // and wait for them (7 %).
+    constexpr bool kWordsEarly = S == 2;
+    if (kWordsEarly) store_words();
+
     // (4)
+    // written at the end of the previous call; constant until every slot of this call has published
+    const Epoch ep = read_epoch(ws);
+    const uint32_t cur = uniform32(ep.cur);      // (the wave has the header's words from here on)
+    const uint32_t prev_slots = uniform32(ep.prev_slots);
     if (lane == 0) s_wave_total[wave] = wave_total;
     lds_barrier();                      // also: every wave has read the header before the first wave publishes anything
     uint32_t before_wave = 0, tile_total = 0;
@@ -868,7 +894,7 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
             v = uniform64(ws_load64(ws_prefix(ws, slot, cur)));
             ++polls;
             if (v != 0) { v -= 1; break; }
-            if (polls > patience) {
+            if (__builtin_expect((polls & 255u) == 0 && polls > patience_of(hdr), 0)) {
                 // Count for ourselves.  The loop needs registers and the tile's elements fill them: park the elements
                 // in LDS meanwhile (the strips are not in use before the barrier below).
                 static_assert(kRows * kWaveSize * kVecBytes <= kWaves * G::LDS_WAVE, "room to park a wave's elements");
@@ -892,15 +918,7 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
     uint64_t g0 = uniform64(s_tile_prefix) + before_wave;          // index in the value array of this wave's next value
     BT_TL(slot, 2);
     BT_TL_VALUE(slot, 5, polls);
-    {
-        uint32_t *const bitmap = job.bitmap(sl.item);
-        const int g = lane / G::G, i = lane % G::G;
-#pragma unroll
-        for (int r0 = 0; r0 < kRows; r0 += G::G) {
-            const uint64_t widx = (wave_e0 >> 5) + (uint64_t)(r0 + i) * G::WPR + (uint64_t)g;
-            if (r0 + i < kRows && widx < n_words) bitmap[widx] = word[r0 / G::G];
-        }
-    }
+    if (!kWordsEarly) store_words();
 
     // (5)
     unsigned char *strip = s_stage + wave * G::LDS_WAVE;
@@ -1320,8 +1338,6 @@ __global__ __launch_bounds__(kBlock, kDecompressOcc) void decompress_kernel(cons
     const Epoch ep = read_epoch(ws);
     const uint32_t cur = uniform32(ep.cur);      // (the wave has the header's words from here on)
     const uint32_t prev_slots = uniform32(ep.prev_slots);
-    const uint32_t asked_patience = hdr[kHdrPatience];          // never written by a kernel
-    const uint32_t patience = asked_patience != 0 ? asked_patience : kPatience;
     // masks and ranks; what they add up to is this wave's share of the tile's count
     Restoring<S> r;
     const uint32_t wave_total = sl.idle ? 0u : restore_ranks<S>(rows, n, sl.tile, lane, wave, r);
@@ -1348,7 +1364,7 @@ __global__ __launch_bounds__(kBlock, kDecompressOcc) void decompress_kernel(cons
             v = uniform64(ws_load64(ws_prefix(ws, slot, cur)));
             ++polls;
             if (v != 0) { v -= 1; break; }
-            if (polls > patience) { v = prefix_from_bitmap<S>(bitmap, sl.tile, lane); break; }
+            if ((polls & 255u) == 0 && polls > patience_of(hdr)) { v = prefix_from_bitmap<S>(bitmap, sl.tile, lane); break; }
             __builtin_amdgcn_s_sleep(kTileSleep);
         }
         if (lane == 0) s_tile_j = v;
