@@ -124,13 +124,6 @@ def timeline(bt, wl, torch, dev, sets):
         for g in np.arange(2.0, end + 2.0, 2.0):
             print("| %.0f | %d | %d | %d | %d |" % (g, ((t[:, 0] != 0) & (us(t[:, 0]) <= g)).sum(), ((t[:, 1] != 0) & (us(t[:, 1]) <= g)).sum(),
                                                  ((t[:, 2] != 0) & (us(t[:, 2]) <= g)).sum(), ((t[:, 3] != 0) & (us(t[:, 3]) <= g)).sum()))
-        if name == "bt_compress":
-            ok = (t[:, 4] != 0) & (t[:, 7] != 0)
-            d = lambda a, b: np.median((t[ok, a] - t[ok, b]) / 100.0)
-            print("\nMedian over tiles (first wave of each workgroup), µs: asked → arrived %.2f, arrived → counted %.2f, counted → end of "
-                  "the tile's turn %.2f, counted → prefix seen %.2f." % (d(4, 0), d(1, 4), d(7, 1), d(2, 1)))
-            print("\nWaits of the first wave of a workgroup for room in its ring (recorded with the workgroup's last tile): "
-                  "%d workgroups, %d waits, at most %d per workgroup." % ((t[:, 6] != 0).sum() + 0, t[:, 6].sum(), t[:, 6].max()))
         p = a[8 * tiles:].reshape(max_passes, 2)
         p = p[p[:, 0] != 0]
         print("\nScanner passes that consumed counts (time, slots):", ", ".join(

@@ -42,9 +42,8 @@
  * Parity pins (tests/test_oracle_*.py): the theoretical columns of Table 1,
  * hand-built tensors, numpy.packbits / boolean indexing, enumeration of all
  * 2^16 zero patterns of a 16-element tensor, every n in [0,130], closed forms
- * for the all-zero and all-non-zero tensors, and a literal pure-Python
- * transcription of the two algorithms on small inputs.  No function here is
- * "parity unpinned".
+ * for the all-zero and all-non-zero tensors, and a pruning threshold that no
+ * single-precision number equals.  No function here is "parity unpinned".
  */
 #include <stddef.h>
 #include <stdint.h>

@@ -15,13 +15,12 @@
 //   grid    per-tile counts published in the workspace; one extra wave turns them
 //           into per-tile prefixes; a wave polls only the prefix of its own tile
 //
-// The codec kernels are PERSISTENT: a launch has at most as many workgroups as the
-// device holds at once, and workgroup w works through tiles w, w + G, w + 2G, ...
-// (G workgroups).  Every workgroup of a launch is therefore running while any of them
-// waits, whatever order the hardware starts them in; and a workgroup does not sit on a
-// tile while it waits for that tile's prefix: compression parks the tile's values in
-// LDS and reads the next tile meanwhile, restoration publishes the counts of its later
-// tiles before it restores the first.
+// A codec launch has one workgroup per 32 KiB tile (plus one, whose first wave is the
+// scanner).  No workgroup depends on another for progress: a workgroup whose prefix has
+// not come after a bounded number of polls counts the elements before its tile itself,
+// from the input (compression) or from the bitmap (restoration), so the order in which
+// the hardware starts the workgroups does not matter.  A workgroup ends with its stores
+// on their way; it never waits for them to land.
 //
 // There is no matrix contraction anywhere, so no MFMA: the path is bound by HBM
 // bandwidth and everything here is about moving each byte once, coalesced, and
@@ -64,8 +63,8 @@ constexpr int kDecompressOcc = BT_DECOMPRESS_OCC;
 constexpr int kHdrSeq = 0;       // calls completed on this workspace; its low bit picks the copy in use
 constexpr int kHdrPrevTiles = 1; // slots of the previous call (what it left behind in the other copy)
 constexpr int kHdrError = BT_WS_ERROR_WORD;           // set if a wait was given up
-constexpr int kHdrSpinLimit = BT_WS_WAIT_LIMIT_WORD;  // polls before a wait is given up; 0: kSpinLimit
-constexpr int kHdrPatience = BT_WS_PATIENCE_WORD;     // polls before a restoring workgroup counts for itself; 0: kPatience
+constexpr int kHdrSpinLimit = BT_WS_WAIT_LIMIT_WORD;  // scanner passes before its wait is given up; 0: kSpinLimit
+constexpr int kHdrPatience = BT_WS_PATIENCE_WORD;     // polls before a workgroup counts what precedes its tile itself; 0: kPatience
 constexpr size_t kHeaderBytes = 256;
 constexpr size_t kHdrSpare = 128;      // bytes [128, 256) of the header take stores that mean nothing (see the scanner)
 // Block of 256 slots, two copies c = 0, 1 of everything:
@@ -77,8 +76,8 @@ constexpr size_t kHdrSpare = 128;      // bytes [128, 256) of the header take st
 // slot number, never on the size of the workspace or of the call.
 constexpr int kSlotsPerBlock = 256;
 constexpr size_t kBlockBytes = 6144;
-constexpr uint32_t kSpinLimit = 1u << 20; // polls before a wait is given up
-constexpr uint32_t kPatience = 1u << 12;  // polls before a restoring wave counts the bitmap itself instead of waiting on
+constexpr uint32_t kSpinLimit = 1u << 20; // scanner passes before its wait is given up
+constexpr uint32_t kPatience = 1u << 12;  // polls before a workgroup counts what precedes its tile itself instead of waiting on
 #ifndef BT_SCANNER_SLEEP
 #define BT_SCANNER_SLEEP 1
 #endif
@@ -1499,11 +1498,7 @@ bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p
 
 bt_status launched() { return hipGetLastError() == hipSuccess ? BT_OK : BT_ERR_HIP; }
 
-// Workgroups of `kernel` that the current device holds at the same time: what the runtime
-// reports per compute unit, times the compute units.  Asked once per kernel and device, then
-// remembered; the query touches no stream.  The persistent kernels are launched with at most
-// this many workgroups, which is what lets their workgroups wait for one another.
-constexpr int kMaxDevices = 64;
+constexpr int kMaxDevices = 64;          // devices the static workspace keeps an address for
 
 bt_status check_common(uint64_t n, bt_dtype dt, const void *d_ws, size_t ws_bytes) {
     if (elem_size(dt) == 0) return BT_ERR_DTYPE;
