@@ -528,32 +528,35 @@ __device__ __forceinline__ uint32_t patience_of(const uint32_t *hdr) {
     return asked != 0 ? asked : kPatience;
 }
 
-template <int SLEEP> __device__ __forceinline__ bool spin_expired(uint32_t *hdr, uint32_t &spins, const uint32_t limit) {
-    // bounded wait: give up after the limit of polls, or soon after anyone has given up
-    ++spins;
-    if (spins > limit ||
-        ((spins & 255u) == 0 && __hip_atomic_load(&hdr[kHdrError], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
-        __hip_atomic_store(&hdr[kHdrError], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return true;
-    }
-    __builtin_amdgcn_s_sleep(SLEEP);   // units of 64 clocks
-    return false;
+// The scanner: one wave.  Workgroups come and go (one per tile) and a count is published as soon as
+// its tile has arrived; one wave that takes kRowScan rows of 64 counts starting at the frontier's row in
+// every pass, consumes the leading run of published ones (to the slot, not to the row) and asks again.
+// Every tile of a launch waits for the pass that reaches it, so the launch pays for each instruction of
+// this one wave: what is the same in all lanes (frontier, running sum, addresses of a row) is kept in
+// scalar registers, a row's prefixes are stored as soon as they are known, and rows behind the first
+// unpublished slot are not looked at.  Measured alternatives, all slower: four waves with a window of
+// 28 rows and an exchange through LDS; a second wave that does the stores; whole rows only; eight
+// consecutive slots per lane (fewer instructions, but loads and stores that touch eight times as many
+// lines); more or fewer rows per pass.  A row of 64 slots is also the unit in which batched tensors are
+// laid out: the running sum restarts where a tensor begins and goes to that tensor's nnz where it ends.
+// (All rows are asked for before anything is written: on this hardware one counter tracks a wave's loads
+// and stores in order of issue, so a load waited for after a store would also wait for that store.)  At
+// the end the scanner advances the header for the next call.
+constexpr int kRowScan = 7;
+
+// Offsets of the 64 entries of row `row` (slots 64 * row + lane) in copy c, from the workspace's start: the
+// same in every lane, so that the scanner's addresses are a scalar base plus a constant per lane.
+__device__ __forceinline__ uint32_t ws_count_row(uint32_t row, uint32_t copy) {
+    return (uint32_t)kHeaderBytes + (row >> 2) * (uint32_t)kBlockBytes + 1024u * copy + 256u * (row & 3u);
+}
+__device__ __forceinline__ uint32_t ws_prefix_row(uint32_t row, uint32_t copy) {
+    return (uint32_t)kHeaderBytes + (row >> 2) * (uint32_t)kBlockBytes + 2048u + 2048u * copy + 512u * (row & 3u);
 }
 
-// The scanner: one wave.  Workgroups come and go (one per tile) and a count is published as soon as
-// its workgroup has been started, so the counts arrive in index order at the pace at which tiles
-// finish; one wave that takes kRowScan rows of 64 counts starting at the frontier's row in every
-// pass, consumes the leading run of published ones and asks again keeps up with that.  A row of 64
-// slots is also the unit in which batched tensors are laid out: the running sum restarts where a
-// tensor begins and goes to that tensor's nnz where it ends.  (All rows are looked at before anything
-// is written: on this hardware one counter tracks a wave's loads and stores in order of issue, so a
-// load waited for after a store would also wait for that store.)  At the end the scanner advances
-// the header for the next call.
-constexpr int kRowScan = 7;
 template <class Job> __device__ __forceinline__ void scan_counts_rows(char *ws, const Job &job) {
     const uint32_t lane = threadIdx.x & (kWaveSize - 1);
     uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
-    const uint32_t seq = hdr[kHdrSeq];
+    const uint32_t seq = uniform32(hdr[kHdrSeq]);
     const uint32_t cur = seq & 1u;
     const uint32_t n_items = job.count();
     const uint32_t n_slots = job.slots();
@@ -561,56 +564,61 @@ template <class Job> __device__ __forceinline__ void scan_counts_rows(char *ws, 
     uint32_t item = 0;         // tensor that slot `frontier` belongs to
     uint64_t running = 0;      // stored values of tensor `item` in its tiles before `frontier`
     uint32_t spins = 0;
-    const uint32_t limit = wait_limit(hdr);
+    const uint32_t limit = uniform32(wait_limit(hdr));
 #ifdef BT_TIMELINE
     uint64_t *const timeline = g_timeline;      // read once: a load in the loop would join the scanner's waits
     uint32_t timeline_pass = 0;
 #endif
     while (frontier < n_slots) {
-        const uint32_t w0 = frontier & ~63u;
-        uint32_t c[kRowScan];
+        // what is the same in all lanes stays in scalar registers
+        frontier = uniform32(frontier);
+        item = uniform32(item);
+        running = uniform64(running);
+        const uint32_t row = frontier >> 6;
+        uint32_t c[kRowScan];          // 0: not published yet (or past the call's last slot)
 #pragma unroll
         for (int j = 0; j < kRowScan; ++j) {
-            const uint32_t t = w0 + 64u * j + lane;
             c[j] = 0;
-            if (t < n_slots)
-                c[j] = __hip_atomic_load(reinterpret_cast<const uint32_t *>(ws_count(ws, t, cur)), __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
+            if (64u * (row + j) + lane < n_slots)
+                c[j] = __hip_atomic_load(reinterpret_cast<const uint32_t *>(ws + ws_count_row(row + j, cur)) + lane,
+                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        uint64_t usable_lanes[kRowScan];
-#pragma unroll
-        for (int j = 0; j < kRowScan; ++j) {
-            const uint32_t t = w0 + 64u * j + lane;
-            usable_lanes[j] = __ballot(t < frontier || (t < n_slots && c[j] != 0));   // done before, or published
-        }
-        // rows are consumed in order while every slot of the row is usable
+        // rows are consumed in order while every slot of the row before was usable (published: the slots that
+        // were done before this pass still hold their counts)
         bool open = true;
         uint32_t new_frontier = frontier;
 #pragma unroll
         for (int j = 0; j < kRowScan; ++j) {
-            const uint32_t row0 = w0 + 64u * j;
-            const uint32_t t = row0 + lane;
-            if (open && row0 < n_slots) {
-                const uint64_t bad = ~usable_lanes[j];                             // lanes that stop the run
-                const uint32_t run = bad == 0 ? 64u : (uint32_t)__ffsll((unsigned long long)bad) - 1u;
+            if (open) {
+                const uint32_t row0 = 64u * (row + j);
+                const uint64_t bad = __ballot(c[j] == 0);                          // lanes that stop the run
+                const uint32_t run = uniform32(bad == 0 ? 64u : (uint32_t)__builtin_ctzll(bad));
                 const uint32_t row_end = row0 + run;                               // slots [row0, row_end) usable
                 if (row_end > new_frontier) {
                     while (item + 1 < n_items && row0 >= job.start(item + 1)) ++item;
                     if (row0 == job.start(item) && new_frontier <= row0) running = 0;   // a new tensor begins
-                    const bool fresh = t >= frontier && t < row_end;
+                    const uint32_t lo = j == 0 ? (frontier & 63u) : 0u;            // lanes [lo, run) are new
+                    const bool fresh = lane >= lo && lane < run;
                     const uint32_t mine = fresh ? c[j] - 1u : 0u;
                     const uint32_t incl = wave_inclusive_sum(mine);
-                    if (fresh) ws_store64(ws_prefix(ws, t, cur), running + (incl - mine) + 1);
-                    running += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-                    new_frontier = row_end;
-                    uint64_t *const nnz = job.nnz(item);
-                    if (row_end == job.start(item + 1) && lane == 0 && nnz != nullptr) *nnz = running;   // this tensor's number of values
+                    if (fresh)
+                        ws_store64(ws + ws_prefix_row(row + j, cur) + 8u * lane, running + (incl - mine) + 1);
+                    running = uniform64(running + (uint32_t)__builtin_amdgcn_readlane((int)incl, 63));
+                    new_frontier = uniform32(row_end);
+                    item = uniform32(item);
+                    if (row_end == job.start(item + 1)) {                          // this tensor's number of values
+                        uint64_t *const nnz = job.nnz(item);
+                        if (lane == 0 && nnz != nullptr) *nnz = running;
+                    }
                 }
                 open = run == 64u;
             }
         }
         // the scanner's wait for the call's counts is bounded in passes, fruitful or not
-        if (spin_expired<0>(hdr, spins, limit)) return;
+        if (++spins > limit) {
+            if (lane == 0) __hip_atomic_store(&hdr[kHdrError], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
         if (new_frontier == frontier) {
             __builtin_amdgcn_s_sleep(kScannerSleep);
             continue;
