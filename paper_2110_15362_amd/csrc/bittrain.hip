@@ -343,6 +343,7 @@ template <int MAXB> struct BatchLayout {
 };
 
 struct CompressOne {
+    static constexpr bool kMany = false;      // several tensors in one launch
     const void *in_;
     uint64_t n_;
     uint32_t *bitmap_;
@@ -368,6 +369,7 @@ struct CompressOne {
 };
 
 struct CompressMany {
+    static constexpr bool kMany = true;      // several tensors in one launch
     BatchLayout<kMaxBatchCompress> lay;
     const void *in_[kMaxBatchCompress];
     uint64_t n_[kMaxBatchCompress];
@@ -394,6 +396,7 @@ struct CompressMany {
 static_assert(sizeof(CompressMany) <= 3840, "kernel arguments of a batched compression");
 
 struct DecompressOne {
+    static constexpr bool kMany = false;      // several tensors in one launch
     const uint32_t *bitmap_;
     const void *values_;
     uint64_t cap_;
@@ -417,6 +420,7 @@ struct DecompressOne {
 };
 
 struct DecompressMany {
+    static constexpr bool kMany = true;      // several tensors in one launch
     BatchLayout<kMaxBatchDecompress> lay;
     const uint32_t *bitmap_[kMaxBatchDecompress];
     const void *values_[kMaxBatchDecompress];
@@ -595,18 +599,20 @@ template <class Job> __device__ __forceinline__ void scan_counts_rows(char *ws, 
                 const uint32_t run = uniform32(bad == 0 ? 64u : (uint32_t)__builtin_ctzll(bad));
                 const uint32_t row_end = row0 + run;                               // slots [row0, row_end) usable
                 if (row_end > new_frontier) {
-                    while (item + 1 < n_items && row0 >= job.start(item + 1)) ++item;
-                    if (row0 == job.start(item) && new_frontier <= row0) running = 0;   // a new tensor begins
+                    if constexpr (Job::kMany) {
+                        while (item + 1 < n_items && row0 >= job.start(item + 1)) ++item;
+                        if (row0 == job.start(item) && new_frontier <= row0) running = 0;   // a new tensor begins
+                    }
                     const uint32_t lo = j == 0 ? (frontier & 63u) : 0u;            // lanes [lo, run) are new
                     const bool fresh = lane >= lo && lane < run;
                     const uint32_t mine = fresh ? c[j] - 1u : 0u;
                     const uint32_t incl = wave_inclusive_sum(mine);
                     if (fresh)
-                        ws_store64(ws + ws_prefix_row(row + j, cur) + 8u * lane, running + (incl - mine) + 1);
+                        ws_store64(ws + ws_prefix_row(row + j, cur) + 8u * lane, (running + 1) + (incl - mine));
                     running = uniform64(running + (uint32_t)__builtin_amdgcn_readlane((int)incl, 63));
                     new_frontier = uniform32(row_end);
                     item = uniform32(item);
-                    if (row_end == job.start(item + 1)) {                          // this tensor's number of values
+                    if (row_end == (Job::kMany ? job.start(item + 1) : n_slots)) {    // this tensor's number of values
                         uint64_t *const nnz = job.nnz(item);
                         if (lane == 0 && nnz != nullptr) *nnz = running;
                     }
