@@ -652,9 +652,8 @@ template <class Job> __device__ __forceinline__ void scan_counts_rows(char *ws, 
 // summed again from its first slot in every pass (the slots done before still hold their counts, and they are
 // given the prefixes they have already), so the running sum kept between passes is the one at that row's start.
 // Measured against the scanner above on single tensors: 1 to 1.5 % faster in both directions with three rows
-// per pass; with four or six rows slower than with three, with two faster on large tensors and slower on
-// sparse ones.
-constexpr int kPairScan = 3;
+// per pass; four or six rows are slower than three; two are as fast or faster (3 % on large tensors) in
+// restoration and in compression slower on sparse tensors: restoration takes two rows, compression three.
 
 typedef uint32_t bt_u32x4 __attribute__((ext_vector_type(4)));
 // Two prefix entries in one store that is written through to where every compute unit sees it.  Only for
@@ -665,7 +664,7 @@ __device__ __forceinline__ void ws_store_two_small(void *p, uint32_t first, uint
     asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
 }
 
-template <class Job> __device__ __forceinline__ void scan_counts_pairs(char *ws, const Job &job) {
+template <int kPairScan, class Job> __device__ __forceinline__ void scan_counts_pairs(char *ws, const Job &job) {
     static_assert(!Job::kMany, "one tensor");
     const uint32_t lane = threadIdx.x & (kWaveSize - 1);
     uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
@@ -891,7 +890,7 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
     if (blockIdx.x == 0) {
         if (threadIdx.x < kWaveSize) {
             if constexpr (Job::kMany) scan_counts_rows(ws, job);
-            else scan_counts_pairs(ws, job);
+            else scan_counts_pairs<3>(ws, job);
         }
         return;
     }
@@ -1449,7 +1448,7 @@ __global__ __launch_bounds__(kBlock, kDecompressOcc) void decompress_kernel(cons
     if (blockIdx.x == 0) {
         if (threadIdx.x < kWaveSize) {
             if constexpr (Job::kMany) scan_counts_rows(ws, job);
-            else scan_counts_pairs(ws, job);
+            else scan_counts_pairs<2>(ws, job);
         }
         return;
     }
