@@ -113,10 +113,16 @@ const char *bt_status_str(bt_status status);
  *                           scan and counts what lies before its tile itself, from the
  *                           bitmap (restoration) or the input (compression): correct, only
  *                           slower; looked at every 256th poll; 0 means the built-in 4096.  Written by the caller only,
- *                           like the wait limit; meant for tests of that path. */
+ *                           like the wait limit; meant for tests of that path.
+ *   BT_WS_WIDE_WORD         non-zero: the grid scan of a call on one tensor writes every tile's
+ *                           offset with 8-byte stores, which it otherwise does only once the
+ *                           offsets reach 2^32 (below that it writes two neighbours' lower
+ *                           halves in one store).  Same results; written by the caller only;
+ *                           meant for tests of the wide path on tensors of ordinary size. */
 #define BT_WS_ERROR_WORD 2
 #define BT_WS_WAIT_LIMIT_WORD 3
 #define BT_WS_PATIENCE_WORD 4
+#define BT_WS_WIDE_WORD 5
 
 /* Put a workspace into its initial state (all zero bytes) by enqueueing a fill
  * kernel on `stream`.  Required once after allocating a workspace, before its

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libbittrain.so")
 
 BT_F32, BT_F16, BT_BF16, BT_F64 = 0, 1, 2, 3
 # 32-bit words of a workspace that a caller may look at (BT_WS_* of the C header)
-BT_WS_ERROR_WORD, BT_WS_WAIT_LIMIT_WORD, BT_WS_PATIENCE_WORD = 2, 3, 4
+BT_WS_ERROR_WORD, BT_WS_WAIT_LIMIT_WORD, BT_WS_PATIENCE_WORD, BT_WS_WIDE_WORD = 2, 3, 4, 5
 BT_STATIC_MAX_TILES = 16384
 BT_OK = 0
 STATUS_NAMES = {0: "BT_OK", 1: "BT_ERR_NULL", 2: "BT_ERR_DTYPE", 3: "BT_ERR_ALIGN", 4: "BT_ERR_WORKSPACE",

@@ -64,6 +64,7 @@ constexpr int kHdrSeq = 0;       // calls completed on this workspace; its low b
 constexpr int kHdrPrevTiles = 1; // slots of the previous call (what it left behind in the other copy)
 constexpr int kHdrError = BT_WS_ERROR_WORD;           // set if a wait was given up
 constexpr int kHdrSpinLimit = BT_WS_WAIT_LIMIT_WORD;  // scanner passes before its wait is given up; 0: kSpinLimit
+constexpr int kHdrWide = BT_WS_WIDE_WORD;             // non-zero: the one-tensor scanner writes 8-byte entries only
 constexpr int kHdrPatience = BT_WS_PATIENCE_WORD;     // polls before a workgroup counts what precedes its tile itself; 0: kPatience
 constexpr size_t kHeaderBytes = 256;
 constexpr size_t kHdrSpare = 128;      // bytes [128, 256) of the header take stores that mean nothing (see the scanner)
@@ -675,6 +676,7 @@ template <int kPairScan, class Job> __device__ __forceinline__ void scan_counts_
     uint64_t base = 0;         // stored values in the tiles before the frontier's row of 128 slots
     uint32_t spins = 0;
     const uint32_t limit = uniform32(wait_limit(hdr));
+    const bool wide = uniform32(hdr[kHdrWide]) != 0;      // never written by a kernel
 #ifdef BT_TIMELINE
     uint64_t *const timeline = g_timeline;      // read once: a load in the loop would join the scanner's waits
     uint32_t timeline_pass = 0;
@@ -694,7 +696,7 @@ template <int kPairScan, class Job> __device__ __forceinline__ void scan_counts_
             ca[j] = (uint32_t)two;
             cb[j] = t + 1 < n_slots ? (uint32_t)(two >> 32) : 0u;
         }
-        const bool small = (base >> 32) == 0 && (uint32_t)base < 0xF0000000u;   // all of this pass's entries below 2^32
+        const bool small = !wide && (base >> 32) == 0 && (uint32_t)base < 0xF0000000u;   // all of this pass's entries below 2^32
         bool open = true;
         uint32_t new_frontier = frontier;
 #pragma unroll

@@ -41,7 +41,7 @@ def test_every_declared_symbol_is_exported(bt):
 
 def test_binding_constants_are_the_headers(bt):
     text = open(os.path.join(os.path.dirname(__file__), "..", "include", "bittrain.h")).read()
-    for name in ("BT_WS_ERROR_WORD", "BT_WS_WAIT_LIMIT_WORD", "BT_WS_PATIENCE_WORD", "BT_STATIC_MAX_TILES"):
+    for name in ("BT_WS_ERROR_WORD", "BT_WS_WAIT_LIMIT_WORD", "BT_WS_PATIENCE_WORD", "BT_WS_WIDE_WORD", "BT_STATIC_MAX_TILES"):
         assert int(re.search(r"#define\s+%s\s+(\d+)" % name, text).group(1)) == getattr(bt, name)
 
 

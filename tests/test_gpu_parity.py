@@ -427,6 +427,27 @@ def test_restoration_that_stops_waiting_counts_the_bitmap_itself(gpu, oracle, dt
     assert int(ws.view(torch.int32)[bt.BT_WS_ERROR_WORD].item()) == 0
 
 
+@pytest.mark.parametrize("dt", DTYPES)
+def test_wide_prefix_entries_give_the_same_results(gpu, oracle, dt):
+    """Forced from the host: the scanner of a call on one tensor writes 8-byte entries (what it does by itself only
+    once the offsets reach 2^32) instead of pairs of lower halves.  Several passes of the scanner, a ragged last tile;
+    compression and restoration, two calls in a row on the same workspace."""
+    import paper_2110_15362_amd.bittrain as bt
+    n = 1100 * bt.bt_tile_elems(wl.DTYPES[dt]) + 77
+    x = wl.random_sparse(n, dt, 0.55, seed=123)
+    ws = bt.new_workspace(n, x.dtype)
+    ws.view(torch.int32)[bt.BT_WS_WIDE_WORD] = 1
+    o_bitmap, o_values, o_nnz = oracle.compress(wl.bits(x))
+    for _ in range(2):
+        bitmap, values, nnz, tail_ok = gpu.gpu_compress(x, ws=ws)
+        assert tail_ok and nnz == o_nnz
+        assert np.array_equal(bitmap, o_bitmap) and np.array_equal(values[:o_nnz], o_values)
+        out, guard_ok = gpu.gpu_decompress(o_bitmap, o_values, n, x.dtype, ws=ws)
+        assert guard_ok and np.array_equal(out, wl.bits(x))
+    assert int(ws.view(torch.int32)[bt.BT_WS_ERROR_WORD].item()) == 0
+    assert int(ws.view(torch.int32)[bt.BT_WS_WIDE_WORD].item()) == 1      # the kernels leave the caller's words alone
+
+
 def test_stream_probe_stays_inside_its_buffers(gpu):
     """The benchmark's plain stream reads tiles * read_rows * 4 KiB and writes tiles * write_rows * 4 KiB, no more."""
     from paper_2110_15362_amd import bench_aids as bt
