@@ -311,7 +311,7 @@ __device__ __forceinline__ uint32_t bitmap_bits(const uint32_t *bitmap, uint64_t
 //
 // A call works on one tensor or (the batched calls) on a list.  The tensors are laid end to
 // end in a numbering of SLOTS (= workspace entries): a call on one tensor has slot == tile;
-// a batched call starts every tensor at a multiple of 64 slots, so that a scanner row never
+// a batched call starts every tensor at a multiple of 128 slots, so that a scanner row never
 // spans two tensors, and the slots between a tensor's last tile and the next tensor's first
 // slot belong to no tile ("idle": they publish a count of zero).  Prefixes restart at 0 with
 // every tensor and each tensor's total goes to its nnz.  The kernels see the call through a
@@ -533,128 +533,27 @@ __device__ __forceinline__ uint32_t patience_of(const uint32_t *hdr) {
     return asked != 0 ? asked : kPatience;
 }
 
-// The scanner: one wave.  Workgroups come and go (one per tile) and a count is published as soon as
-// its tile has arrived; one wave that takes kRowScan rows of 64 counts starting at the frontier's row in
-// every pass, consumes the leading run of published ones (to the slot, not to the row) and asks again.
-// Every tile of a launch waits for the pass that reaches it, so the launch pays for each instruction of
-// this one wave: what is the same in all lanes (frontier, running sum, addresses of a row) is kept in
-// scalar registers, a row's prefixes are stored as soon as they are known, and rows behind the first
-// unpublished slot are not looked at.  Measured alternatives, all slower: four waves with a window of
-// 28 rows and an exchange through LDS; a second wave that does the stores; whole rows only; eight
-// consecutive slots per lane (fewer instructions, but loads and stores that touch eight times as many
-// lines); more or fewer rows per pass.  A row of 64 slots is also the unit in which batched tensors are
-// laid out: the running sum restarts where a tensor begins and goes to that tensor's nnz where it ends.
-// (All rows are asked for before anything is written: on this hardware one counter tracks a wave's loads
-// and stores in order of issue, so a load waited for after a store would also wait for that store.)  At
-// the end the scanner advances the header for the next call.
-constexpr int kRowScan = 7;
-
-// Offsets of the 64 entries of row `row` (slots 64 * row + lane) in copy c, from the workspace's start: the
-// same in every lane, so that the scanner's addresses are a scalar base plus a constant per lane.
-__device__ __forceinline__ uint32_t ws_count_row(uint32_t row, uint32_t copy) {
-    return (uint32_t)kHeaderBytes + (row >> 2) * (uint32_t)kBlockBytes + 1024u * copy + 256u * (row & 3u);
-}
-__device__ __forceinline__ uint32_t ws_prefix_row(uint32_t row, uint32_t copy) {
-    return (uint32_t)kHeaderBytes + (row >> 2) * (uint32_t)kBlockBytes + 2048u + 2048u * copy + 512u * (row & 3u);
-}
-
-template <class Job> __device__ __forceinline__ void scan_counts_rows(char *ws, const Job &job) {
-    const uint32_t lane = threadIdx.x & (kWaveSize - 1);
-    uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
-    const uint32_t seq = uniform32(hdr[kHdrSeq]);
-    const uint32_t cur = seq & 1u;
-    const uint32_t n_items = job.count();
-    const uint32_t n_slots = job.slots();
-    uint32_t frontier = 0;     // slots [0, frontier) are done
-    uint32_t item = 0;         // tensor that slot `frontier` belongs to
-    uint64_t running = 0;      // stored values of tensor `item` in its tiles before `frontier`
-    uint32_t spins = 0;
-    const uint32_t limit = uniform32(wait_limit(hdr));
-#ifdef BT_TIMELINE
-    uint64_t *const timeline = g_timeline;      // read once: a load in the loop would join the scanner's waits
-    uint32_t timeline_pass = 0;
-#endif
-    while (frontier < n_slots) {
-        // what is the same in all lanes stays in scalar registers
-        frontier = uniform32(frontier);
-        item = uniform32(item);
-        running = uniform64(running);
-        const uint32_t row = frontier >> 6;
-        uint32_t c[kRowScan];          // 0: not published yet (or past the call's last slot)
-#pragma unroll
-        for (int j = 0; j < kRowScan; ++j) {
-            c[j] = 0;
-            if (64u * (row + j) + lane < n_slots)
-                c[j] = __hip_atomic_load(reinterpret_cast<const uint32_t *>(ws + ws_count_row(row + j, cur)) + lane,
-                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        // rows are consumed in order while every slot of the row before was usable (published: the slots that
-        // were done before this pass still hold their counts)
-        bool open = true;
-        uint32_t new_frontier = frontier;
-#pragma unroll
-        for (int j = 0; j < kRowScan; ++j) {
-            if (open) {
-                const uint32_t row0 = 64u * (row + j);
-                const uint64_t bad = __ballot(c[j] == 0);                          // lanes that stop the run
-                const uint32_t run = uniform32(bad == 0 ? 64u : (uint32_t)__builtin_ctzll(bad));
-                const uint32_t row_end = row0 + run;                               // slots [row0, row_end) usable
-                if (row_end > new_frontier) {
-                    if constexpr (Job::kMany) {
-                        while (item + 1 < n_items && row0 >= job.start(item + 1)) ++item;
-                        if (row0 == job.start(item) && new_frontier <= row0) running = 0;   // a new tensor begins
-                    }
-                    const uint32_t lo = j == 0 ? (frontier & 63u) : 0u;            // lanes [lo, run) are new
-                    const bool fresh = lane >= lo && lane < run;
-                    const uint32_t mine = fresh ? c[j] - 1u : 0u;
-                    const uint32_t incl = wave_inclusive_sum(mine);
-                    if (fresh)
-                        ws_store64(ws + ws_prefix_row(row + j, cur) + 8u * lane, (running + 1) + (incl - mine));
-                    running = uniform64(running + (uint32_t)__builtin_amdgcn_readlane((int)incl, 63));
-                    new_frontier = uniform32(row_end);
-                    item = uniform32(item);
-                    if (row_end == (Job::kMany ? job.start(item + 1) : n_slots)) {    // this tensor's number of values
-                        uint64_t *const nnz = job.nnz(item);
-                        if (lane == 0 && nnz != nullptr) *nnz = running;
-                    }
-                }
-                open = run == 64u;
-            }
-        }
-        // the scanner's wait for the call's counts is bounded in passes, fruitful or not
-        if (++spins > limit) {
-            if (lane == 0) __hip_atomic_store(&hdr[kHdrError], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            return;
-        }
-        if (new_frontier == frontier) {
-            __builtin_amdgcn_s_sleep(kScannerSleep);
-            continue;
-        }
-#ifdef BT_TIMELINE
-        if (timeline != nullptr && lane == 0 && timeline_pass < g_timeline_passes) {
-            timeline[8 * (size_t)g_timeline_tiles + 2 * timeline_pass] = wall_clock64();
-            timeline[8 * (size_t)g_timeline_tiles + 2 * timeline_pass + 1] = ((uint64_t)frontier << 32) | new_frontier;
-            ++timeline_pass;
-        }
-#endif
-        frontier = new_frontier;
-    }
-    if (lane == 0) {
-        // every slot's workgroup has published its count by now, hence has read the header: advance it
-        __hip_atomic_store(&hdr[kHdrPrevTiles], n_slots, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&hdr[kHdrSeq], seq + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-}
-
-// The scanner of a launch on ONE tensor: as above, with two neighbouring slots per lane.  A pass looks at
-// kPairScan rows of 128 slots (lane i: slots 2 i and 2 i + 1 of the row, one 8-byte load), sums a lane's two
-// counts before the DPP prefix sum over the lanes, and stores a lane's two prefixes with one 16-byte store:
-// half the instructions per slot.  The leading run is still consumed to the slot.  The frontier's row of 128 is
-// summed again from its first slot in every pass (the slots done before still hold their counts, and they are
-// given the prefixes they have already), so the running sum kept between passes is the one at that row's start.
-// Measured against the scanner above on single tensors: 1 to 1.5 % faster in both directions with three rows
-// per pass; four or six rows are slower than three; two are as fast or faster (3 % on large tensors) in
-// restoration and in compression slower on sparse tensors: restoration takes two rows, compression three.
+// The scanner: one wave.  Workgroups come and go (one per tile) and a count is published as soon as its tile
+// has arrived; the scanner takes a few rows of 128 counts starting at the frontier's row in every pass, consumes
+// the leading run of published ones (to the slot, not to the row) and asks again.  Every tile of a launch waits
+// for the pass that reaches it, so the launch pays for each instruction of this one wave:
+//   - what is the same in all lanes (frontier, running sum) is kept in scalar registers;
+//   - a lane takes two neighbouring slots (slots 2 i and 2 i + 1 of the row, one 8-byte load), sums its two counts
+//     before the DPP prefix sum over the lanes, and stores its two prefixes with one 16-byte store;
+//   - a row's prefixes are stored as soon as they are known, and rows behind the first unpublished slot are not
+//     looked at.
+// The frontier's row is summed again from its first slot in every pass (the slots done before still hold their
+// counts, and they are given the prefixes they have already), so the running sum kept between passes is the one
+// at that row's start.  Batched tensors are laid out in whole rows of 128 slots: the running sum restarts where
+// a tensor begins and goes to that tensor's nnz where it ends.  All rows are asked for before anything is
+// written: on this hardware one counter tracks a wave's loads and stores in order of issue, so a load waited for
+// after a store would also wait for that store.  At the end the scanner advances the header for the next call.
+// Measured alternatives, all slower or no faster: one slot per lane (rows of 64; 1 to 1.5 % slower), four or
+// eight slots per lane (loads and stores spread over more lines), four waves with a window of 28 rows and an
+// exchange through LDS, four waves taking rows round robin with the running sum handed on through LDS, a second
+// wave that does the stores, whole rows only, a wider window when the last one was used up, more rows per pass
+// (restoration is best with two, compression with three).
+constexpr uint32_t kBatchRow = 128;     // slots: a batched tensor's share of a launch is a whole number of these
 
 typedef uint32_t bt_u32x4 __attribute__((ext_vector_type(4)));
 // Two prefix entries in one store that is written through to where every compute unit sees it.  Only for
@@ -665,15 +564,16 @@ __device__ __forceinline__ void ws_store_two_small(void *p, uint32_t first, uint
     asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
 }
 
-template <int kPairScan, class Job> __device__ __forceinline__ void scan_counts_pairs(char *ws, const Job &job) {
-    static_assert(!Job::kMany, "one tensor");
+template <int kRowScan, class Job> __device__ __forceinline__ void scan_counts(char *ws, const Job &job) {
     const uint32_t lane = threadIdx.x & (kWaveSize - 1);
     uint32_t *hdr = reinterpret_cast<uint32_t *>(ws);
     const uint32_t seq = uniform32(hdr[kHdrSeq]);
     const uint32_t cur = seq & 1u;
+    const uint32_t n_items = job.count();
     const uint32_t n_slots = job.slots();
     uint32_t frontier = 0;     // slots [0, frontier) are done
-    uint64_t base = 0;         // stored values in the tiles before the frontier's row of 128 slots
+    uint32_t item = 0;         // tensor that the frontier's row belongs to
+    uint64_t base = 0;         // stored values of that tensor in the tiles before the frontier's row of 128 slots
     uint32_t spins = 0;
     const uint32_t limit = uniform32(wait_limit(hdr));
     const bool wide = uniform32(hdr[kHdrWide]) != 0;      // never written by a kernel
@@ -683,11 +583,12 @@ template <int kPairScan, class Job> __device__ __forceinline__ void scan_counts_
 #endif
     while (frontier < n_slots) {
         frontier = uniform32(frontier);
+        item = uniform32(item);
         base = uniform64(base);
         const uint32_t row = frontier >> 7;
-        uint32_t ca[kPairScan], cb[kPairScan];          // count + 1 of the lane's two slots; 0: not published yet, or past the end
+        uint32_t ca[kRowScan], cb[kRowScan];          // count + 1 of the lane's two slots; 0: not published yet, or past the end
 #pragma unroll
-        for (int j = 0; j < kPairScan; ++j) {
+        for (int j = 0; j < kRowScan; ++j) {
             const uint32_t t = 128u * (row + j) + 2u * lane;
             uint64_t two = 0;
             if (t < n_slots)
@@ -700,7 +601,7 @@ template <int kPairScan, class Job> __device__ __forceinline__ void scan_counts_
         bool open = true;
         uint32_t new_frontier = frontier;
 #pragma unroll
-        for (int j = 0; j < kPairScan; ++j) {
+        for (int j = 0; j < kRowScan; ++j) {
             if (open) {
                 const uint32_t slot0 = 128u * (row + j);
                 const uint64_t bad_a = __ballot(ca[j] == 0), bad_b = __ballot(cb[j] == 0);
@@ -708,6 +609,12 @@ template <int kPairScan, class Job> __device__ __forceinline__ void scan_counts_
                 const uint32_t run_b = bad_b == 0 ? 64u : (uint32_t)__builtin_ctzll(bad_b);
                 const uint32_t run = uniform32(min(2u * run_a, 2u * run_b + 1u));   // usable slots of the row, in slot order
                 const uint32_t row_end = slot0 + run;
+                if constexpr (Job::kMany) {
+                    // batched tensors begin at multiples of 128 slots: the sum restarts there
+                    while (item + 1 < n_items && slot0 >= job.start(item + 1)) ++item;
+                    if (slot0 == job.start(item)) base = 0;
+                    item = uniform32(item);
+                }
                 if (row_end > new_frontier) {
                     const bool use_a = 2u * lane < run, use_b = 2u * lane + 1u < run;
                     const uint32_t va = use_a ? ca[j] - 1u : 0u, vb = use_b ? cb[j] - 1u : 0u;
@@ -724,8 +631,8 @@ template <int kPairScan, class Job> __device__ __forceinline__ void scan_counts_
                         if (use_b) ws_store64(entry + 8, pa + va);
                     }
                     new_frontier = row_end;
-                    if (row_end == n_slots) {                      // the tensor's number of values
-                        uint64_t *const nnz = job.nnz(0);
+                    if (row_end == (Job::kMany ? job.start(item + 1) : n_slots)) {      // this tensor's number of values
+                        uint64_t *const nnz = job.nnz(item);
                         if (lane == 0 && nnz != nullptr) *nnz = base + total;
                     }
                     if (run == 128u) base = uniform64(base + total);
@@ -890,10 +797,7 @@ __global__ __launch_bounds__(kBlock, kCompressOcc) void compress_kernel(const Jo
     __shared__ uint32_t s_wave_total[kWaves];
     if (workspace_failed(ws)) return;
     if (blockIdx.x == 0) {
-        if (threadIdx.x < kWaveSize) {
-            if constexpr (Job::kMany) scan_counts_rows(ws, job);
-            else scan_counts_pairs<3>(ws, job);
-        }
+        if (threadIdx.x < kWaveSize) scan_counts<3>(ws, job);
         return;
     }
     BT_TL_INIT;
@@ -1448,10 +1352,7 @@ __global__ __launch_bounds__(kBlock, kDecompressOcc) void decompress_kernel(cons
     __shared__ uint32_t s_wave_total[kWaves];
     if (workspace_failed(ws)) return;
     if (blockIdx.x == 0) {
-        if (threadIdx.x < kWaveSize) {
-            if constexpr (Job::kMany) scan_counts_rows(ws, job);
-            else scan_counts_pairs<2>(ws, job);
-        }
+        if (threadIdx.x < kWaveSize) scan_counts<2>(ws, job);
         return;
     }
     BT_TL_INIT;
@@ -1647,7 +1548,7 @@ bt_status check_common(uint64_t n, bt_dtype dt, const void *d_ws, size_t ws_byte
 // scanner rows; an empty tensor still takes one row, so that the scanner writes its nnz.
 uint64_t batch_slots_for(uint64_t n, int s) {
     const uint64_t tiles = tiles_for(n, s);
-    return ((tiles == 0 ? 1 : tiles) + kWaveSize - 1) / kWaveSize * kWaveSize;
+    return ((tiles == 0 ? 1 : tiles) + kBatchRow - 1) / kBatchRow * kBatchRow;
 }
 
 size_t workspace_bytes_for_slots(uint64_t slots) {

@@ -133,13 +133,13 @@ def test_batch_workspace_bytes_and_host_errors(bt):
     tile = {f32: 8192, f16: 16384}
 
     def expect(ns, code):
-        # every tensor takes its tiles rounded up to whole rows of 64 slots (at least one row);
+        # every tensor takes its tiles rounded up to whole rows of 128 slots (at least one row);
         # 24 bytes per slot in blocks of 256 slots, plus the 256-byte header; the largest launch decides,
         # whether the batch is cut into launches of 52 tensors (compression) or of 64 (restoration)
         need = 256 + 6144
         for per_launch in (52, 64):
             for first in range(0, len(ns), per_launch):
-                slots = sum(max(1, -(-(-(-n // tile[code])) // 64)) * 64 for n in ns[first:first + per_launch])
+                slots = sum(max(1, -(-(-(-n // tile[code])) // 128)) * 128 for n in ns[first:first + per_launch])
                 need = max(need, 256 + 6144 * -(-slots // 256))
         return need
 
